@@ -1,0 +1,196 @@
+/*
+ * cg.h -- C ABI of the MI355X (gfx950) library for one data-parallel worker's
+ * share of the CaffeGPI SGD iteration.
+ *
+ * What the library computes.  The paper distributes Caffe's mini-batch SGD
+ * (Fig. 1) over s ranks by data parallelism: every rank runs forward and
+ * backward on its share of the batch, the per-layer partial gradients are
+ * summed and the model of layer l is updated by
+ *        w^{l,k+1} = w^{l,k} - eps * sum_{r=1..s} dw_r^{l,k}          (Eq. 1)
+ * layer by layer, in inverse layer order, while the backward pass of the
+ * remaining layers is still running (section 2.3, Fig. 3; "layer-wise model
+ * update", section 3).  This library is ONE rank: the s-1 = K peer gradients
+ * are buffers already resident in this GPU's memory; the inter-node transport
+ * (GPI-2, section 3.1-3.2) is outside it.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers to dense row-major fp32 data,
+ *    16-byte aligned, activations NCHW, weights [M][C/groups][KH][KW].
+ *    Pointer arrays documented as HOST arrays are read during the call.
+ *  - Ownership: the caller allocates and frees every device buffer, including
+ *    workspaces.  The library allocates no device memory.
+ *  - Asynchrony: a call validates its arguments, enqueues work on the given
+ *    HIP stream (a hipStream_t passed as void*; NULL = the default stream) and
+ *    returns.  Nothing synchronises.  Outputs are valid in stream order.
+ *  - Errors: the return value is CG_OK (0) or a negative CG_E* code.  A call
+ *    that fails validation launches nothing.  Nothing aborts or throws.
+ *  - Outputs are overwritten (not accumulated into) and must not alias inputs,
+ *    except where a parameter is documented as updated in place.
+ *  - Every tensor must hold fewer than 2^31 bytes.
+ */
+#ifndef CG_H
+#define CG_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CG_OK = 0,
+    CG_EINVAL = -1,        /* null pointer, bad descriptor, misaligned pointer          */
+    CG_ENOSPC = -2,        /* workspace smaller than cg_*_workspace_bytes() reports      */
+    CG_EUNSUPPORTED = -3,  /* valid request outside what the kernels cover               */
+    CG_EHIP = -4           /* a HIP runtime call failed; see cg_last_hip_error()         */
+};
+
+/* One convolution layer on a batch: input [N,C,H,W], filters [M,C/groups,KH,KW],
+ * output [N,M,OH,OW] with OH = floor((H + 2*pad_h - KH)/stride_h) + 1. */
+typedef struct {
+    int N, C, H, W;
+    int M, KH, KW;
+    int stride_h, stride_w, pad_h, pad_w, groups;
+} cg_conv_desc;
+
+/* Solver constants of the update: step size eps of Eq. 1 (lr), and the
+ * "higher order terms" that depend on the model history (text after Eq. 1):
+ * momentum mu and L2 weight decay wd.  grad_scale multiplies the summed
+ * gradient (1 = Eq. 1 literally; 1/(K+1) gives the mean over ranks). */
+typedef struct { float lr, mu, wd, grad_scale; } cg_sgd;
+
+enum { CG_PASS_FWD = 0, CG_PASS_BWD_DATA = 1, CG_PASS_BWD_WEIGHT = 2 };
+
+/* Output spatial size of a convolution.  Returns CG_EINVAL for an invalid descriptor. */
+int cg_conv_out_shape(const cg_conv_desc *d, int *OH, int *OW);
+
+/* Bytes of device workspace the given pass needs for this descriptor (0 = none). */
+size_t cg_conv_workspace_bytes(const cg_conv_desc *d, int pass);
+
+/* Forward propagation of a convolution layer (section 2.1):
+ *   y[n,m,oh,ow] = bias[m] + sum_{c,kh,kw} x[n, g*C/G + c, oh*s-p+kh, ow*s-p+kw] * w[m,c,kh,kw]
+ * (cross-correlation; taps outside the image read 0; output channel m belongs
+ * to group g = m / (M/G)).  bias may be NULL.  ws/ws_bytes: see
+ * cg_conv_workspace_bytes(d, CG_PASS_FWD). */
+int cg_conv_fwd(const cg_conv_desc *d, const float *x, const float *w, const float *bias,
+                float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* Backward propagation to the layer input (section 2.1): dx is the adjoint of
+ * x -> y applied to dy.  dy [N,M,OH,OW], w as above, dx [N,C,H,W] overwritten. */
+int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w,
+                     float *dx, void *ws, size_t ws_bytes, void *stream);
+
+/* "compute local gradient dw_r^{(k,l)}" (Fig. 3, first line of the turn):
+ *   dw[m,c,kh,kw] = sum_{n,oh,ow} dy[n,m,oh,ow] * x[n, g*C/G + c, oh*s-p+kh, ow*s-p+kw]
+ *   dbias[m]      = sum_{n,oh,ow} dy[n,m,oh,ow]             (dbias may be NULL)
+ * Both overwritten.  The sum over n,oh,ow is split into slices reduced in a
+ * fixed order, so results are reproducible run to run. */
+int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const float *dy,
+                       float *dw, float *dbias, void *ws, size_t ws_bytes, void *stream);
+
+/* Gradient aggregation over s = K+1 ranks fused with the model update of one
+ * layer (Eq. 1; "reduced (added to) with its own gradient data", section 3.2;
+ * update on the reduced gradient, section 3.2 first paragraph).  Per element
+ * i < n, every operation rounded to fp32 in this order, no fused multiply-add:
+ *     s = g_local[i];  for k = 0..K-1:  s = s + g_peers[k][i];
+ *     if (grad_scale != 1) s = s * grad_scale;
+ *     d = s + wd * w[i];   vn = mu * v[i] + lr * d;   w[i] = w[i] - vn;   v[i] = vn;
+ * w, v: updated in place.  g_local, g_peers[k]: read only, n floats each (the
+ * gradient of a layer has the size of its model, section 3.2).
+ * g_peers: HOST array of K device pointers (may be NULL when K == 0).
+ * 0 <= K <= CG_MAX_PEERS.  n == 0 is a no-op. */
+#define CG_MAX_PEERS 64
+int cg_grad_reduce_sgd(float *w, float *v, const float *g_local,
+                       const float *const *g_peers, int K, size_t n,
+                       const cg_sgd *sgd, void *stream);
+
+/* ---- whole iteration ------------------------------------------------------ */
+
+enum {
+    CG_LAYER_CONV = 0, CG_LAYER_RELU, CG_LAYER_LRN, CG_LAYER_MAXPOOL, CG_LAYER_AVGPOOL,
+    CG_LAYER_FC, CG_LAYER_DROPOUT, CG_LAYER_CONCAT, CG_LAYER_SOFTMAX_CE
+};
+
+/* One layer of the net.  inputs[0..n_inputs) are producer layer indices
+ * (-1 = the net input); only CONCAT takes more than one.
+ *  CONV       : conv.{M,KH,KW,stride_*,pad_*,groups} (N,C,H,W are inferred)
+ *  MAXPOOL    : square window k, stride, pad; output size ceil((H+2p-k)/s)+1,
+ *               the last window must start inside image+pad; first maximum wins
+ *  LRN        : across channels, scale = kappa + alpha/size * sum x^2, y = x*scale^-beta
+ *  AVGPOOL    : global average over H x W
+ *  FC         : out features; weights [out][C*H*W]
+ *  DROPOUT    : y = x * mask / (1 - drop_p), keep-mask supplied per step
+ *  SOFTMAX_CE : mean over the batch of -log softmax(z)[label]; must be last */
+typedef struct {
+    int kind;
+    int n_inputs;
+    int inputs[4];
+    cg_conv_desc conv;
+    int k, stride, pad;
+    int lrn_size;
+    float lrn_alpha, lrn_beta, lrn_kappa;
+    int fc_out;
+    float drop_p;
+} cg_layer_desc;
+
+typedef struct cg_net cg_net;
+
+/* Records shapes and creates the per-layer HIP events; allocates no device memory.
+ * B = this worker's batch, (C,H,W) = input image shape. */
+int cg_net_create(const cg_layer_desc *layers, int L, int B, int C, int H, int W, cg_net **out);
+int cg_net_destroy(cg_net *net);
+
+/* Number of floats in layer's parameter bucket (weights then bias, contiguous);
+ * 0 for layers without parameters, negative on error. */
+long long cg_net_param_count(const cg_net *net, int layer);
+
+/* Attach the caller-owned buffers of a parameter layer: model w, history v,
+ * this worker's gradient g_local (written by every step), and K peer gradient
+ * buckets (HOST array of K device pointers, copied), each param_count floats. */
+int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local,
+                const float *const *g_peers, int K);
+
+/* Device workspace (activations, gradients of activations, kernel scratch). */
+size_t cg_net_workspace_bytes(const cg_net *net);
+
+enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1 };
+
+/* One SGD iteration of this worker (Fig. 1 with the turn-based schedule of
+ * Fig. 3): forward through layers 1..L, loss, then for l = L..1 the local
+ * gradient of layer l followed, on update_stream, by its aggregation and model
+ * update (cg_grad_reduce_sgd) while compute_stream continues with layer l-1.
+ * Layer l's forward in the NEXT call waits only for layer l's own update
+ * ("finalize", section 2.3): there is no device-wide barrier.
+ *  x [B,C,H,W], labels [B] (int32, device), dropout_masks: HOST array of L
+ *  device pointers (uint8 keep-masks, one per DROPOUT layer, NULL elsewhere;
+ *  the array may be NULL if the net has no dropout layer), loss_dev: 1 float.
+ *  flags: CG_STEP_SERIAL runs the same kernels in the same order on
+ *  compute_stream alone (the separate-phases schedule the paper improves on).
+ * The two streams must differ unless CG_STEP_SERIAL is given. */
+int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
+                  const uint8_t *const *dropout_masks, const cg_sgd *sgd,
+                  void *ws, size_t ws_bytes, void *compute_stream, void *update_stream,
+                  float *loss_dev, int flags);
+
+/* Where a layer's output (which = 0) or the gradient with respect to its
+ * output (which = 1) lives inside a workspace of base address ws after a step;
+ * for inspection by tests.  count receives the number of floats. */
+int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count);
+
+/* Test hook (host only, launches nothing): which element of which tensor the
+ * implicit-GEMM view of a convolution pass reads for operand A (0) or B (1) at
+ * (row, k) of the given group.  elem_offset is in floats from the tensor's base
+ * (forward: A = w, B = x; backward-data, stride 1 only: A = the group-wise
+ * transposed filter copy [g][c][m][kh][kw], B = dy; backward-weight: A = dy,
+ * B = x); valid = 0 means the element is a zero-padding tap. */
+int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operand, unsigned row, unsigned k,
+                          unsigned group, long long *elem_offset, int *valid);
+
+const char *cg_strerror(int code);
+const char *cg_version(void);
+int cg_last_hip_error(void);   /* hipError_t of the most recent CG_EHIP on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif

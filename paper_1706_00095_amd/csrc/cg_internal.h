@@ -1,0 +1,153 @@
+// Internal declarations shared by the translation units of libcg (never installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "cg.h"
+
+namespace cg {
+
+// Records the failing hipError_t for cg_last_hip_error() and maps it to CG_EHIP.
+int hip_fail(hipError_t e);
+
+#define CG_HIP_TRY(expr)                                   \
+    do {                                                   \
+        hipError_t e__ = (expr);                           \
+        if (e__ != hipSuccess) return ::cg::hip_fail(e__); \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- index maps: how a GEMM coordinate becomes a tensor element ---------------------------
+//
+// Every operand of every pass (forward, backward-data, backward-weight, fully connected) is
+// addressed as  element(row, k) = ptr[ R.off + K.off ],  valid iff
+//   (unsigned)(R.a + K.a) < limA  &&  (unsigned)(R.b + K.b) < limB,
+// where R = info(row index) and K = info(reduction index).  An index is split twice,
+// idx = q1*d1 + r1, r1 = q2*d2 + r2, and
+//   off = q1*s1 + q2*s2 + r2*s3 + o0,   a = q2*sa + a0,   b = r2*sb + b0.
+// A pixel index (n,oh,ow) of a convolution input uses d1 = OH*OW, d2 = OW, a = oh*s - p,
+// b = ow*s - p; a filter-tap index (c,kh,kw) uses d1 = KH*KW, d2 = KW, a = kh, b = kw; a plain
+// matrix dimension uses d1 = d2 = 1.  The sum a_row + a_k is then the input row ih, and the
+// unsigned compare against H implements zero padding.
+
+struct FastDiv {       // exact n / d for n < 2^31:  q = (uint64(n) * mul) >> sh
+    uint32_t d, mul, sh;
+};
+
+struct IndexMap {
+    uint32_t count;    // indices >= count are out of range (read as 0 / not stored)
+    FastDiv d1, d2;
+    int32_t s1, s2, s3, o0;
+    int32_t sa, a0, sb, b0;
+};
+
+struct Info { int32_t off, a, b; };
+
+constexpr int32_t kInvalidA = 0x20000000;   // pushes a_row + a_k far outside any limA
+
+FastDiv make_fastdiv(uint32_t d);
+IndexMap linear_map(uint32_t count, int32_t stride);
+// idx = q*d + r  ->  off = q*sq + r*sr
+IndexMap split_map(uint32_t count, uint32_t d, int32_t sq, int32_t sr);
+
+__host__ __device__ inline uint32_t fdiv(uint32_t n, const FastDiv &f)
+{
+    return (uint32_t)(((uint64_t)n * f.mul) >> f.sh);
+}
+
+__host__ __device__ inline Info map_info(const IndexMap &m, uint32_t idx, uint32_t limit)
+{
+    Info r;
+    if (idx >= limit) { r.off = 0; r.a = kInvalidA; r.b = 0; return r; }
+    const uint32_t q1 = fdiv(idx, m.d1), r1 = idx - q1 * m.d1.d;
+    const uint32_t q2 = fdiv(r1, m.d2), r2 = r1 - q2 * m.d2.d;
+    r.off = (int32_t)q1 * m.s1 + (int32_t)q2 * m.s2 + (int32_t)r2 * m.s3 + m.o0;
+    r.a = (int32_t)q2 * m.sa + m.a0;
+    r.b = (int32_t)r2 * m.sb + m.b0;
+    return r;
+}
+
+struct Operand {
+    const float *ptr;
+    IndexMap row, k;
+    uint32_t limA, limB;
+    int64_t gstride;      // elements between groups
+    int vec4_ok;          // rows and k are unit-stride in k, K % 4 == 0, 16-byte aligned
+};
+
+enum { LD_KMAJ_V4 = 0, LD_KMAJ_S = 1, LD_RMAJ_S = 2 };   // how an operand tile is fetched / laid out
+
+// C[m][n] = sum_k A(m,k) * B(n,k)   (+ bias), for `groups` independent problems, the K range
+// optionally cut into `splits` slices whose partial results go to consecutive output planes.
+struct IgemmProblem {
+    Operand A, B;
+    int a_mode, b_mode;
+    float *c_ptr;
+    int32_t c_row_stride;     // C row m lives at m * c_row_stride (+ column offset)
+    IndexMap c_col;           // column n -> offset
+    int64_t c_gstride, c_split_stride;
+    const float *bias;        // per row (bias_mode 1) or per column (2); NULL / 0 = none
+    int bias_mode;
+    int32_t bias_gstride;
+    uint32_t M, N, K;
+    uint32_t groups, splits, k_per_split;
+    int accumulate;           // C += result instead of C = result
+};
+
+// Validates the problem against what the kernels assume and launches it.
+int igemm_launch(const IgemmProblem &p, hipStream_t stream);
+// Host-side evaluation of one operand element: offset and validity (for tests of the maps).
+void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, uint32_t K, int64_t *off, int *valid);
+
+// out[i] = sum_{s<splits} part[s*stride + i] in index order (+ nothing else); n floats.
+int splitk_reduce_launch(const float *part, int64_t stride, int splits, float *out, size_t n, hipStream_t stream);
+// db[m] = sum over n and pixels of dy[n][m][pix]
+int bias_grad_launch(const float *dy, int N, int M, int P, float *db, hipStream_t stream);
+
+
+// ---- convolution / fully-connected passes (conv.hip) ----------------------------------------
+struct BwdWeightPlan { uint32_t splits, k_per_split; size_t ws_bytes; };
+int conv_check(const cg_conv_desc *d, int *OH, int *OW);
+BwdWeightPlan plan_bwd_weight(const cg_conv_desc &d, int OH, int OW);
+int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y,
+                  hipStream_t stream);
+int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
+                       size_t ws_bytes, int accumulate, hipStream_t stream);
+int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
+                         void *ws, size_t ws_bytes, hipStream_t stream);
+int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y,
+                hipStream_t stream);
+int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate,
+                     hipStream_t stream);
+int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db,
+                       hipStream_t stream);
+
+// ---- gradient aggregation + update (sgd.hip) --------------------------------------------------
+int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *const *g_peers, int K,
+                         size_t n, const cg_sgd &sgd, hipStream_t stream);
+
+// ---- the other layers (layers.hip) -------------------------------------------------------------
+int fc_bias_grad_launch(const float *dy, int B, int OUT, float *db, hipStream_t stream);
+int relu_fwd_launch(const float *x, float *y, size_t n, hipStream_t s);
+int relu_bwd_launch(const float *x, const float *dy, float *dx, size_t n, int accumulate, hipStream_t s);
+int pool_out_size(int H, int k, int s, int p);
+int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, int H, int W, int k, int s, int p,
+                       hipStream_t st);
+int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, int N, int C, int H, int W, int k, int s,
+                       int p, int accumulate, hipStream_t st);
+int lrn_fwd_launch(const float *x, float *y, float *scale, int N, int C, int HW, int size, float alpha, float beta,
+                   float kappa, hipStream_t st);
+int lrn_bwd_launch(const float *x, const float *y, const float *scale, const float *dy, float *dx, int N, int C,
+                   int HW, int size, float alpha, float beta, int accumulate, hipStream_t st);
+int avgpool_fwd_launch(const float *x, float *y, int NC, int HW, hipStream_t st);
+int avgpool_bwd_launch(const float *dy, float *dx, int NC, int HW, int accumulate, hipStream_t st);
+int dropout_launch(const float *x, const uint8_t *mask, float *y, size_t n, float p, int accumulate, hipStream_t st);
+// per_sample: B floats of scratch
+int softmax_ce_launch(const float *z, const int32_t *labels, float *loss, float *dz, float *per_sample, int B, int C,
+                      hipStream_t st);
+// dst[n][c_off + c][hw] = src[n][c][hw]  (forward of a channel concat) or the reverse slice copy
+int concat_copy_launch(const float *src, float *dst, int N, int Csrc, int Cdst, int c_off, int HW, int to_concat,
+                       int accumulate, hipStream_t st);
+
+}  // namespace cg

@@ -1,0 +1,416 @@
+// Convolution and fully-connected passes expressed as implicit-GEMM problems.
+//
+// Forward:          Y[m][(n,oh,ow)]   = sum_{(c,kh,kw)} W[m][(c,kh,kw)] * X(n,c,oh*s-p+kh,ow*s-p+kw)
+// Backward-data:    dX[c][(n,ih,iw)]  = sum_{(m,kh,kw)} Wt[c][(m,kh,kw)] * dY(n,m,(ih+p-kh)/s,(iw+p-kw)/s)
+// Backward-weight:  dW[m][(c,kh,kw)]  = sum_{(n,oh,ow)} dY[m][(n,oh,ow)] * X(n,c,oh*s-p+kh,ow*s-p+kw)
+// (section 2.1: forward propagation, backward propagation, gradient on the weights; the last
+// one is the "compute local gradient" step of every turn in Fig. 3).
+#include "cg_internal.h"
+
+namespace cg {
+
+namespace {
+
+// input pixel grid seen through the filter: index (n, oh, ow) -> window origin in x
+IndexMap window_origin_map(const cg_conv_desc &d, int OH, int OW)
+{
+    IndexMap m{};
+    m.count = (uint32_t)d.N * OH * OW;
+    m.d1 = make_fastdiv((uint32_t)OH * OW);
+    m.d2 = make_fastdiv((uint32_t)OW);
+    m.s1 = d.C * d.H * d.W;
+    m.s2 = d.stride_h * d.W;
+    m.s3 = d.stride_w;
+    m.o0 = -d.pad_h * d.W - d.pad_w;
+    m.sa = d.stride_h; m.a0 = -d.pad_h;
+    m.sb = d.stride_w; m.b0 = -d.pad_w;
+    return m;
+}
+
+// filter tap index (c, kh, kw) -> displacement inside x
+IndexMap tap_map(const cg_conv_desc &d, int Cg)
+{
+    IndexMap m{};
+    m.count = (uint32_t)Cg * d.KH * d.KW;
+    m.d1 = make_fastdiv((uint32_t)d.KH * d.KW);
+    m.d2 = make_fastdiv((uint32_t)d.KW);
+    m.s1 = d.H * d.W;
+    m.s2 = d.W;
+    m.s3 = 1;
+    m.sa = 1; m.sb = 1;
+    return m;
+}
+
+// wt[g][c][ml][kh][kw] = w[g*Mg + ml][c][kh][kw]
+__global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__restrict__ w, float *__restrict__ wt,
+                                                                int G, int Mg, int Cg, int KK)
+{
+    const size_t total = (size_t)G * Mg * Cg * KK;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int kk = (int)(i % KK);
+        size_t r = i / KK;
+        const int ml = (int)(r % Mg); r /= Mg;
+        const int c = (int)(r % Cg);
+        const int g = (int)(r / Cg);
+        wt[i] = w[(((size_t)g * Mg + ml) * Cg + c) * KK + kk];
+    }
+}
+
+// General-stride backward-data, gather form, one thread per dx element.  Only the taps with
+// (ih + p - kh) divisible by the stride contribute.
+__global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_desc d, int OH, int OW,
+                                                               const float *__restrict__ dy,
+                                                               const float *__restrict__ w, float *__restrict__ dx,
+                                                               int accumulate)
+{
+    const int Cg = d.C / d.groups, Mg = d.M / d.groups;
+    const size_t total = (size_t)d.N * d.C * d.H * d.W;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int iw = (int)(i % d.W);
+        size_t r = i / d.W;
+        const int ih = (int)(r % d.H); r /= d.H;
+        const int c = (int)(r % d.C);
+        const int n = (int)(r / d.C);
+        const int g = c / Cg, cl = c - g * Cg;
+        float s = 0.f;
+        const int kh0 = (ih + d.pad_h) % d.stride_h, kw0 = (iw + d.pad_w) % d.stride_w;
+        for (int ml = 0; ml < Mg; ++ml) {
+            const int m = g * Mg + ml;
+            const float *wp = w + ((size_t)m * Cg + cl) * d.KH * d.KW;
+            const float *yp = dy + ((size_t)n * d.M + m) * OH * OW;
+            for (int kh = kh0; kh < d.KH; kh += d.stride_h) {
+                const int oh = (ih + d.pad_h - kh) / d.stride_h;
+                if (ih + d.pad_h - kh < 0 || oh >= OH) continue;
+                for (int kw = kw0; kw < d.KW; kw += d.stride_w) {
+                    const int ow = (iw + d.pad_w - kw) / d.stride_w;
+                    if (iw + d.pad_w - kw < 0 || ow >= OW) continue;
+                    s += yp[oh * OW + ow] * wp[kh * d.KW + kw];
+                }
+            }
+        }
+        dx[i] = accumulate ? dx[i] + s : s;
+    }
+}
+
+}  // namespace
+
+int conv_check(const cg_conv_desc *d, int *OH, int *OW)
+{
+    if (!d) return CG_EINVAL;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->M <= 0 || d->KH <= 0 || d->KW <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0 || d->groups <= 0)
+        return CG_EINVAL;
+    if (d->C % d->groups || d->M % d->groups) return CG_EINVAL;
+    const int eh = d->H + 2 * d->pad_h - d->KH, ew = d->W + 2 * d->pad_w - d->KW;
+    if (eh < 0 || ew < 0) return CG_EINVAL;
+    const int oh = eh / d->stride_h + 1, ow = ew / d->stride_w + 1;
+    const uint64_t lim = (1ull << 31) / 4;   // elements per tensor
+    if ((uint64_t)d->N * d->C * d->H * d->W >= lim || (uint64_t)d->N * d->M * oh * ow >= lim ||
+        (uint64_t)d->M * (d->C / d->groups) * d->KH * d->KW >= lim)
+        return CG_EUNSUPPORTED;
+    if (d->KH > 4096 || d->KW > 4096 || d->H > (1 << 20) || d->W > (1 << 20)) return CG_EUNSUPPORTED;
+    if (OH) *OH = oh;
+    if (OW) *OW = ow;
+    return CG_OK;
+}
+
+BwdWeightPlan plan_bwd_weight(const cg_conv_desc &d, int OH, int OW)
+{
+    BwdWeightPlan pl;
+    const uint32_t Mg = d.M / d.groups, Ng = (uint32_t)(d.C / d.groups) * d.KH * d.KW;
+    const uint64_t K = (uint64_t)d.N * OH * OW;
+    const uint32_t mt = Mg > 96 ? 128 : (Mg > 64 ? 96 : (Mg > 32 ? 64 : 32));
+    const uint64_t tiles = (uint64_t)((Mg + mt - 1) / mt) * ((Ng + 127) / 128) * d.groups;
+    uint64_t want = (1024 + tiles - 1) / tiles;        // aim at ~4 blocks per compute unit
+    const uint64_t max_by_k = (K + 255) / 256;         // at least 256 reduction steps per slice
+    if (want > max_by_k) want = max_by_k;
+    if (want < 1) want = 1;
+    if (want > 512) want = 512;
+    uint64_t per = (K + want - 1) / want;
+    per = (per + 15) / 16 * 16;
+    pl.k_per_split = (uint32_t)per;
+    pl.splits = (uint32_t)((K + per - 1) / per);
+    pl.ws_bytes = pl.splits > 1 ? (size_t)pl.splits * d.M * Ng * sizeof(float) : 0;
+    return pl;
+}
+
+static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *w,
+                                const float *bias, float *y)
+{
+    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, Kg = Cg * d.KH * d.KW, P = OH * OW;
+    IgemmProblem p{};
+    p.A.ptr = w;
+    p.A.row = linear_map(Mg, Kg);
+    p.A.k = linear_map(Kg, 1);
+    p.A.limA = p.A.limB = 1;
+    p.A.gstride = (int64_t)Mg * Kg;
+    p.A.vec4_ok = (Kg % 4 == 0);
+    p.a_mode = p.A.vec4_ok ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.B.ptr = x;
+    p.B.row = window_origin_map(d, OH, OW);
+    p.B.k = tap_map(d, Cg);
+    p.B.limA = d.H; p.B.limB = d.W;
+    p.B.gstride = (int64_t)Cg * d.H * d.W;
+    p.b_mode = LD_RMAJ_S;
+    p.c_ptr = y;
+    p.c_row_stride = P;
+    p.c_col = split_map((uint32_t)d.N * P, P, d.M * P, 1);
+    p.c_gstride = (int64_t)Mg * P;
+    p.bias = bias; p.bias_mode = bias ? 1 : 0; p.bias_gstride = Mg;
+    p.M = Mg; p.N = (uint32_t)d.N * P; p.K = Kg;
+    p.groups = G; p.splits = 1; p.k_per_split = p.K;
+    return p;
+}
+
+int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y,
+                  hipStream_t stream)
+{
+    int OH, OW;
+    const int rc = conv_check(&d, &OH, &OW);
+    if (rc) return rc;
+    return igemm_launch(fwd_problem(d, OH, OW, x, w, bias, y), stream);
+}
+
+static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *wt,
+                                     float *dx, int accumulate)
+{
+    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW, P = OH * OW;
+    const int Kp = Mg * KK;
+    IgemmProblem p{};
+    p.A.ptr = wt;
+    p.A.row = linear_map(Cg, Kp);
+    p.A.k = linear_map(Kp, 1);
+    p.A.limA = p.A.limB = 1;
+    p.A.gstride = (int64_t)Cg * Kp;
+    p.A.vec4_ok = (Kp % 4 == 0);
+    p.a_mode = p.A.vec4_ok ? LD_KMAJ_V4 : LD_KMAJ_S;
+    // dy seen from an input pixel (n, ih, iw): origin (ih + p, iw + p), taps subtract (kh, kw)
+    p.B.ptr = dy;
+    IndexMap pix{};
+    pix.count = (uint32_t)d.N * d.H * d.W;
+    pix.d1 = make_fastdiv((uint32_t)d.H * d.W);
+    pix.d2 = make_fastdiv((uint32_t)d.W);
+    pix.s1 = d.M * P; pix.s2 = OW; pix.s3 = 1; pix.o0 = d.pad_h * OW + d.pad_w;
+    pix.sa = 1; pix.a0 = d.pad_h; pix.sb = 1; pix.b0 = d.pad_w;
+    IndexMap tap{};
+    tap.count = (uint32_t)Kp;
+    tap.d1 = make_fastdiv((uint32_t)KK);
+    tap.d2 = make_fastdiv((uint32_t)d.KW);
+    tap.s1 = P; tap.s2 = -OW; tap.s3 = -1;
+    tap.sa = -1; tap.sb = -1;
+    p.B.row = pix; p.B.k = tap;
+    p.B.limA = OH; p.B.limB = OW;
+    p.B.gstride = (int64_t)Mg * P;
+    p.b_mode = LD_RMAJ_S;
+    const int HW = d.H * d.W;
+    p.c_ptr = dx;
+    p.c_row_stride = HW;
+    p.c_col = split_map((uint32_t)d.N * HW, HW, d.C * HW, 1);
+    p.c_gstride = (int64_t)Cg * HW;
+    p.M = Cg; p.N = (uint32_t)d.N * HW; p.K = Kp;
+    p.groups = G; p.splits = 1; p.k_per_split = p.K;
+    p.accumulate = accumulate;
+    return p;
+}
+
+int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
+                       size_t ws_bytes, int accumulate, hipStream_t stream)
+{
+    int OH, OW;
+    const int rc = conv_check(&d, &OH, &OW);
+    if (rc) return rc;
+    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW;
+    if (d.stride_h != 1 || d.stride_w != 1) {
+        const size_t total = (size_t)d.N * d.C * d.H * d.W;
+        const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
+        hipLaunchKernelGGL(bwd_data_strided_kernel, dim3(blocks), dim3(256), 0, stream, d, OH, OW, dy, w, dx,
+                           accumulate);
+        CG_HIP_TRY(hipGetLastError());
+        return CG_OK;
+    }
+    const size_t need = (size_t)d.M * Cg * KK * sizeof(float);
+    if (!ws || ws_bytes < need) return CG_ENOSPC;
+    if (!aligned16(ws)) return CG_EINVAL;
+    float *wt = static_cast<float *>(ws);
+    {
+        const size_t total = (size_t)d.M * Cg * KK;
+        const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+        hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
+        CG_HIP_TRY(hipGetLastError());
+    }
+    return igemm_launch(bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate), stream);
+}
+
+static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const BwdWeightPlan &pl,
+                                       const float *x, const float *dy, float *dw, void *ws)
+{
+    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, Kg = Cg * d.KH * d.KW, P = OH * OW;
+    IgemmProblem p{};
+    p.A.ptr = dy;
+    p.A.row = linear_map(Mg, P);
+    p.A.k = split_map((uint32_t)d.N * P, P, d.M * P, 1);
+    p.A.limA = p.A.limB = 1;
+    p.A.gstride = (int64_t)Mg * P;
+    p.a_mode = LD_KMAJ_S;
+    p.B.ptr = x;
+    p.B.row = tap_map(d, Cg);
+    p.B.k = window_origin_map(d, OH, OW);
+    p.B.limA = d.H; p.B.limB = d.W;
+    p.B.gstride = (int64_t)Cg * d.H * d.W;
+    p.b_mode = LD_KMAJ_S;
+    p.c_ptr = pl.splits > 1 ? static_cast<float *>(ws) : dw;
+    p.c_row_stride = Kg;
+    p.c_col = linear_map(Kg, 1);
+    p.c_gstride = (int64_t)Mg * Kg;
+    p.c_split_stride = (int64_t)d.M * Kg;
+    p.M = Mg; p.N = Kg; p.K = (uint32_t)d.N * P;
+    p.groups = G; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
+    return p;
+}
+
+int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
+                         void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    int OH, OW;
+    const int rc = conv_check(&d, &OH, &OW);
+    if (rc) return rc;
+    const int Kg = (d.C / d.groups) * d.KH * d.KW, P = OH * OW;
+    const BwdWeightPlan pl = plan_bwd_weight(d, OH, OW);
+    if (pl.splits > 1) {
+        if (!ws || ws_bytes < pl.ws_bytes) return CG_ENOSPC;
+        if (!aligned16(ws)) return CG_EINVAL;
+    }
+    int r = igemm_launch(bwd_weight_problem(d, OH, OW, pl, x, dy, dw, ws), stream);
+    if (r) return r;
+    if (pl.splits > 1) {
+        r = splitk_reduce_launch(static_cast<const float *>(ws), (int64_t)d.M * Kg, (int)pl.splits, dw,
+                                 (size_t)d.M * Kg, stream);
+        if (r) return r;
+    }
+    if (db) return bias_grad_launch(dy, d.N, d.M, P, db, stream);
+    return CG_OK;
+}
+
+// ---- fully connected: y[b][o] = bias[o] + sum_i x[b][i] W[o][i] ------------------------------
+
+int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y,
+                hipStream_t stream)
+{
+    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    IgemmProblem p{};
+    const bool v4 = IN % 4 == 0;
+    p.A.ptr = x; p.A.row = linear_map(B, IN); p.A.k = linear_map(IN, 1); p.A.limA = p.A.limB = 1; p.A.vec4_ok = v4;
+    p.B.ptr = W; p.B.row = linear_map(OUT, IN); p.B.k = linear_map(IN, 1); p.B.limA = p.B.limB = 1; p.B.vec4_ok = v4;
+    p.a_mode = p.b_mode = v4 ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.c_ptr = y; p.c_row_stride = OUT; p.c_col = linear_map(OUT, 1);
+    p.bias = bias; p.bias_mode = bias ? 2 : 0;
+    p.M = B; p.N = OUT; p.K = IN;
+    p.groups = 1; p.splits = 1; p.k_per_split = p.K;
+    return igemm_launch(p, stream);
+}
+
+// dx[b][i] = sum_o dy[b][o] W[o][i]
+int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate,
+                     hipStream_t stream)
+{
+    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    IgemmProblem p{};
+    const bool v4 = OUT % 4 == 0;
+    p.A.ptr = dy; p.A.row = linear_map(B, OUT); p.A.k = linear_map(OUT, 1); p.A.limA = p.A.limB = 1; p.A.vec4_ok = v4;
+    p.a_mode = v4 ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.B.ptr = W; p.B.row = linear_map(IN, 1); p.B.k = linear_map(OUT, IN); p.B.limA = p.B.limB = 1;
+    p.b_mode = LD_RMAJ_S;
+    p.c_ptr = dx; p.c_row_stride = IN; p.c_col = linear_map(IN, 1);
+    p.M = B; p.N = IN; p.K = OUT;
+    p.groups = 1; p.splits = 1; p.k_per_split = p.K;
+    p.accumulate = accumulate;
+    return igemm_launch(p, stream);
+}
+
+// dW[o][i] = sum_b dy[b][o] x[b][i];  db[o] = sum_b dy[b][o]
+int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db,
+                       hipStream_t stream)
+{
+    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    IgemmProblem p{};
+    p.A.ptr = dy; p.A.row = linear_map(OUT, 1); p.A.k = linear_map(B, OUT); p.A.limA = p.A.limB = 1;
+    p.B.ptr = x; p.B.row = linear_map(IN, 1); p.B.k = linear_map(B, IN); p.B.limA = p.B.limB = 1;
+    p.a_mode = p.b_mode = LD_RMAJ_S;
+    p.c_ptr = dW; p.c_row_stride = IN; p.c_col = linear_map(IN, 1);
+    p.M = OUT; p.N = IN; p.K = B;
+    p.groups = 1; p.splits = 1; p.k_per_split = p.K;
+    const int r = igemm_launch(p, stream);
+    if (r) return r;
+    if (db) return fc_bias_grad_launch(dy, B, OUT, db, stream);
+    return CG_OK;
+}
+
+}  // namespace cg
+
+// ---- C ABI --------------------------------------------------------------------------------
+
+using namespace cg;
+
+extern "C" int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operand, unsigned row, unsigned k,
+                                     unsigned group, long long *elem_offset, int *valid)
+{
+    int OH, OW;
+    const int rc = conv_check(d, &OH, &OW);
+    if (rc) return rc;
+    if (!elem_offset || !valid || (operand != 0 && operand != 1) || group >= (unsigned)d->groups) return CG_EINVAL;
+    IgemmProblem p;
+    if (pass == CG_PASS_FWD) p = fwd_problem(*d, OH, OW, nullptr, nullptr, nullptr, nullptr);
+    else if (pass == CG_PASS_BWD_DATA) {
+        if (d->stride_h != 1 || d->stride_w != 1) return CG_EUNSUPPORTED;
+        p = bwd_data_problem(*d, OH, OW, nullptr, nullptr, nullptr, 0);
+    } else if (pass == CG_PASS_BWD_WEIGHT)
+        p = bwd_weight_problem(*d, OH, OW, plan_bwd_weight(*d, OH, OW), nullptr, nullptr, nullptr, nullptr);
+    else return CG_EINVAL;
+    const Operand &op = operand == 0 ? p.A : p.B;
+    if (row >= op.row.count || k >= p.K) return CG_EINVAL;
+    int64_t off;
+    igemm_host_element(op, row, k, p.K, &off, valid);
+    *elem_offset = off + (int64_t)group * op.gstride;
+    return CG_OK;
+}
+
+extern "C" int cg_conv_out_shape(const cg_conv_desc *d, int *OH, int *OW)
+{
+    return conv_check(d, OH, OW);
+}
+
+extern "C" size_t cg_conv_workspace_bytes(const cg_conv_desc *d, int pass)
+{
+    int OH, OW;
+    if (conv_check(d, &OH, &OW)) return 0;
+    if (pass == CG_PASS_BWD_DATA) {
+        if (d->stride_h != 1 || d->stride_w != 1) return 0;
+        return (size_t)d->M * (d->C / d->groups) * d->KH * d->KW * sizeof(float);
+    }
+    if (pass == CG_PASS_BWD_WEIGHT) return plan_bwd_weight(*d, OH, OW).ws_bytes;
+    return 0;
+}
+
+extern "C" int cg_conv_fwd(const cg_conv_desc *d, const float *x, const float *w, const float *bias, float *y,
+                           void *, size_t, void *stream)
+{
+    if (!d || !x || !w || !y) return CG_EINVAL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return CG_EINVAL;
+    return conv_fwd_impl(*d, x, w, bias, y, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    if (!d || !dy || !w || !dx) return CG_EINVAL;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return CG_EINVAL;
+    return conv_bwd_data_impl(*d, dy, w, dx, ws, ws_bytes, 0, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const float *dy, float *dw, float *dbias,
+                                  void *ws, size_t ws_bytes, void *stream)
+{
+    if (!d || !x || !dy || !dw) return CG_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CG_EINVAL;
+    return conv_bwd_weight_impl(*d, x, dy, dw, dbias, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}

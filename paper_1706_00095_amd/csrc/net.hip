@@ -1,0 +1,379 @@
+// One worker's SGD iteration with the turn-based, barrier-free schedule (section 2.3, Fig. 3).
+//
+// Two HIP streams.  The compute stream runs forward 1..L, the loss, and backward L..1.  As soon
+// as the local gradient of layer l is complete an event is recorded; the update stream waits
+// for it and runs that layer's (K+1)-buffer gradient sum + model update while the compute
+// stream continues with layer l-1 -- the paper's overlap of the reduction/update of one layer
+// with the gradient computation of the layers below it.  "Finalize" is per layer as well: the
+// next iteration's forward of layer l waits only on layer l's own update event, so there is no
+// device-wide synchronisation anywhere (design principle 2, section 2.2).
+//
+// Within a layer's turn backward-data runs before backward-weight: backward-data still reads
+// the layer's model, which the update overwrites.
+#include <new>
+#include <vector>
+#include "cg_internal.h"
+
+struct cg_net {
+    struct Layer {
+        cg_layer_desc d;
+        int inC = 0, inH = 0, inW = 0;        // shape of inputs[0]
+        int C = 0, H = 0, W = 0;              // output shape
+        cg_conv_desc conv{};                  // completed descriptor (CONV)
+        size_t act_off = 0, grad_off = 0, aux_off = 0;   // float offsets into the workspace
+        size_t out_elems = 0, aux_elems = 0;
+        long long n_params = 0, n_weights = 0;
+        float *w = nullptr, *v = nullptr, *g = nullptr;
+        std::vector<const float *> peers;
+        bool bound = false;
+        hipEvent_t ev_grad = nullptr, ev_upd = nullptr;
+        bool upd_pending = false;             // an update of this layer was enqueued by a previous step
+        bool grad_written = false;            // per step: has anything been written to this layer's gradient?
+        bool needs_grad = false;              // false when no parameter lies upstream of this output
+    };
+    int B = 0, C = 0, H = 0, W = 0;
+    std::vector<Layer> layers;
+    size_t scratch_off = 0, scratch_bytes = 0;   // kernel scratch (filter transpose, split-K partials)
+    size_t loss_off = 0;                         // B floats of per-sample loss
+    size_t ws_floats = 0;
+};
+
+namespace {
+
+using namespace cg;
+using Layer = cg_net::Layer;
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+void in_shape(const cg_net &net, int src, int *C, int *H, int *W)
+{
+    if (src < 0) { *C = net.C; *H = net.H; *W = net.W; }
+    else { *C = net.layers[src].C; *H = net.layers[src].H; *W = net.layers[src].W; }
+}
+
+}  // namespace
+
+extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, int H, int W, cg_net **out)
+{
+    if (!descs || !out || L <= 0 || B <= 0 || C <= 0 || H <= 0 || W <= 0) return CG_EINVAL;
+    cg_net *net = new (std::nothrow) cg_net;
+    if (!net) return CG_EINVAL;
+    net->B = B; net->C = C; net->H = H; net->W = W;
+    net->layers.resize(L);
+    size_t off = 0, scratch = 0;
+    int rc = CG_OK;
+    for (int i = 0; i < L && rc == CG_OK; ++i) {
+        Layer &ly = net->layers[i];
+        ly.d = descs[i];
+        const cg_layer_desc &d = ly.d;
+        if (d.n_inputs < 1 || d.n_inputs > 4 || (d.kind != CG_LAYER_CONCAT && d.n_inputs != 1)) { rc = CG_EINVAL; break; }
+        for (int k = 0; k < d.n_inputs; ++k)
+            if (d.inputs[k] < -1 || d.inputs[k] >= i) rc = CG_EINVAL;      // producers come first
+        if (rc) break;
+        in_shape(*net, d.inputs[0], &ly.inC, &ly.inH, &ly.inW);
+        ly.needs_grad = false;
+        for (int k = 0; k < d.n_inputs; ++k)
+            if (d.inputs[k] >= 0 && (net->layers[d.inputs[k]].needs_grad)) ly.needs_grad = true;
+        switch (d.kind) {
+        case CG_LAYER_CONV: {
+            ly.conv = d.conv;
+            ly.conv.N = B; ly.conv.C = ly.inC; ly.conv.H = ly.inH; ly.conv.W = ly.inW;
+            int OH, OW;
+            rc = conv_check(&ly.conv, &OH, &OW);
+            if (rc) break;
+            ly.C = ly.conv.M; ly.H = OH; ly.W = OW;
+            ly.n_weights = (long long)ly.conv.M * (ly.inC / ly.conv.groups) * ly.conv.KH * ly.conv.KW;
+            ly.n_params = ly.n_weights + ly.conv.M;
+            size_t s1 = cg_conv_workspace_bytes(&ly.conv, CG_PASS_BWD_DATA);
+            size_t s2 = cg_conv_workspace_bytes(&ly.conv, CG_PASS_BWD_WEIGHT);
+            if (s1 > scratch) scratch = s1;
+            if (s2 > scratch) scratch = s2;
+            ly.needs_grad = true;
+            break;
+        }
+        case CG_LAYER_FC:
+            if (d.fc_out <= 0) { rc = CG_EINVAL; break; }
+            ly.C = d.fc_out; ly.H = ly.W = 1;
+            ly.n_weights = (long long)d.fc_out * ly.inC * ly.inH * ly.inW;
+            ly.n_params = ly.n_weights + d.fc_out;
+            if (ly.n_weights >= (1ll << 29)) rc = CG_EUNSUPPORTED;
+            ly.needs_grad = true;
+            break;
+        case CG_LAYER_RELU: case CG_LAYER_DROPOUT:
+            ly.C = ly.inC; ly.H = ly.inH; ly.W = ly.inW;
+            if (d.kind == CG_LAYER_DROPOUT && !(d.drop_p >= 0.f && d.drop_p < 1.f)) rc = CG_EINVAL;
+            break;
+        case CG_LAYER_LRN:
+            ly.C = ly.inC; ly.H = ly.inH; ly.W = ly.inW;
+            if (d.lrn_size <= 0 || d.lrn_size > ly.inC + 64) rc = CG_EINVAL;
+            ly.aux_elems = (size_t)B * ly.C * ly.H * ly.W;      // scale
+            break;
+        case CG_LAYER_MAXPOOL:
+            if (d.k <= 0 || d.stride <= 0 || d.pad < 0 || d.pad >= d.k) { rc = CG_EINVAL; break; }
+            ly.C = ly.inC;
+            ly.H = pool_out_size(ly.inH, d.k, d.stride, d.pad);
+            ly.W = pool_out_size(ly.inW, d.k, d.stride, d.pad);
+            if (ly.H <= 0 || ly.W <= 0) rc = CG_EINVAL;
+            ly.aux_elems = (size_t)B * ly.C * ly.H * ly.W;      // argmax (int32)
+            break;
+        case CG_LAYER_AVGPOOL:
+            ly.C = ly.inC; ly.H = ly.W = 1;
+            break;
+        case CG_LAYER_CONCAT: {
+            int cs = 0;
+            for (int k = 0; k < d.n_inputs; ++k) {
+                int c, h, w;
+                in_shape(*net, d.inputs[k], &c, &h, &w);
+                if (h != ly.inH || w != ly.inW) rc = CG_EINVAL;
+                cs += c;
+            }
+            ly.C = cs; ly.H = ly.inH; ly.W = ly.inW;
+            break;
+        }
+        case CG_LAYER_SOFTMAX_CE:
+            if (i != L - 1 || d.inputs[0] < 0) { rc = CG_EINVAL; break; }
+            ly.C = ly.H = ly.W = 1;
+            break;
+        default:
+            rc = CG_EINVAL;
+        }
+        if (rc) break;
+        ly.out_elems = (size_t)B * ly.C * ly.H * ly.W;
+        if (ly.out_elems >= (1ull << 29)) { rc = CG_EUNSUPPORTED; break; }
+        ly.act_off = off; off += round_up(ly.out_elems, 64);
+        ly.grad_off = off; off += round_up(ly.out_elems, 64);
+        ly.aux_off = off; off += round_up(ly.aux_elems, 64);
+    }
+    if (rc == CG_OK && net->layers[L - 1].d.kind != CG_LAYER_SOFTMAX_CE) rc = CG_EINVAL;
+    if (rc == CG_OK) {
+        // the logits feed the loss only: its gradient is written by the loss kernel
+        const int src = net->layers[L - 1].d.inputs[0];
+        for (int i = 0; i < L - 1; ++i)
+            for (int k = 0; k < net->layers[i].d.n_inputs; ++k)
+                if (net->layers[i].d.inputs[k] == src) rc = CG_EUNSUPPORTED;
+    }
+    if (rc == CG_OK) {
+        net->loss_off = off; off += round_up((size_t)B, 64);
+        net->scratch_off = off; net->scratch_bytes = round_up(scratch, 256);
+        off += net->scratch_bytes / sizeof(float);
+        net->ws_floats = off;
+        for (Layer &ly : net->layers)
+            if (ly.n_params) {
+                if (hipEventCreateWithFlags(&ly.ev_grad, hipEventDisableTiming) != hipSuccess ||
+                    hipEventCreateWithFlags(&ly.ev_upd, hipEventDisableTiming) != hipSuccess) { rc = CG_EHIP; break; }
+            }
+    }
+    if (rc != CG_OK) { cg_net_destroy(net); return rc; }
+    *out = net;
+    return CG_OK;
+}
+
+extern "C" int cg_net_destroy(cg_net *net)
+{
+    if (!net) return CG_OK;
+    for (Layer &ly : net->layers) {
+        if (ly.ev_grad) (void)hipEventDestroy(ly.ev_grad);
+        if (ly.ev_upd) (void)hipEventDestroy(ly.ev_upd);
+    }
+    delete net;
+    return CG_OK;
+}
+
+extern "C" long long cg_net_param_count(const cg_net *net, int layer)
+{
+    if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
+    return net->layers[layer].n_params;
+}
+
+extern "C" int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local, const float *const *g_peers,
+                           int K)
+{
+    if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
+    Layer &ly = net->layers[layer];
+    if (!ly.n_params || !w || !v || !g_local || K < 0 || K > CG_MAX_PEERS || (K > 0 && !g_peers)) return CG_EINVAL;
+    if (!aligned16(w) || !aligned16(v) || !aligned16(g_local)) return CG_EINVAL;
+    if (ly.n_weights % 4) return CG_EUNSUPPORTED;   // the bias part of the bucket must stay 16-byte aligned
+    for (int k = 0; k < K; ++k)
+        if (!g_peers[k] || !aligned16(g_peers[k])) return CG_EINVAL;
+    ly.w = w; ly.v = v; ly.g = g_local;
+    ly.peers.assign(g_peers, g_peers + K);
+    ly.bound = true;
+    return CG_OK;
+}
+
+extern "C" size_t cg_net_workspace_bytes(const cg_net *net)
+{
+    return net ? net->ws_floats * sizeof(float) : 0;
+}
+
+extern "C" int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count)
+{
+    if (!net || !ws || !ptr || !count || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
+    const Layer &ly = net->layers[layer];
+    float *base = static_cast<float *>(ws);
+    if (which == 0) *ptr = base + ly.act_off;
+    else if (which == 1) *ptr = base + ly.grad_off;
+    else return CG_EINVAL;
+    *count = ly.out_elems;
+    return CG_OK;
+}
+
+extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels, const uint8_t *const *masks,
+                             const cg_sgd *sgd, void *ws, size_t ws_bytes, void *compute_stream,
+                             void *update_stream, float *loss_dev, int flags)
+{
+    if (!net || !x || !labels || !sgd || !ws || !loss_dev) return CG_EINVAL;
+    if (ws_bytes < net->ws_floats * sizeof(float)) return CG_ENOSPC;
+    if (!aligned16(ws) || !aligned16(x)) return CG_EINVAL;
+    const bool serial = (flags & CG_STEP_SERIAL) != 0;
+    hipStream_t S0 = static_cast<hipStream_t>(compute_stream);
+    hipStream_t S1 = serial ? S0 : static_cast<hipStream_t>(update_stream);
+    if (!serial && S0 == S1) return CG_EINVAL;
+    const int L = (int)net->layers.size();
+    for (int i = 0; i < L; ++i) {
+        const Layer &ly = net->layers[i];
+        if (ly.n_params && !ly.bound) return CG_EINVAL;
+        if (ly.d.kind == CG_LAYER_DROPOUT && (!masks || !masks[i])) return CG_EINVAL;
+    }
+    float *base = static_cast<float *>(ws);
+    void *scratch = base + net->scratch_off;
+    const size_t scratch_bytes = net->scratch_bytes;
+    const int B = net->B;
+    auto act = [&](int i) -> const float * { return i < 0 ? x : base + net->layers[i].act_off; };
+    int rc = CG_OK;
+
+    // ---- forward, layers 1..L --------------------------------------------------------------
+    for (int i = 0; i < L && rc == CG_OK; ++i) {
+        Layer &ly = net->layers[i];
+        const cg_layer_desc &d = ly.d;
+        const float *in = act(d.inputs[0]);
+        float *out = base + ly.act_off;
+        ly.grad_written = false;
+        if (ly.n_params && ly.upd_pending) {
+            // finalize, per layer: the model of this layer must have received its update
+            CG_HIP_TRY(hipStreamWaitEvent(S0, ly.ev_upd, 0));
+            ly.upd_pending = false;
+        }
+        const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
+        switch (d.kind) {
+        case CG_LAYER_CONV:
+            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, S0);
+            break;
+        case CG_LAYER_FC:
+            rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, S0);
+            break;
+        case CG_LAYER_RELU: rc = relu_fwd_launch(in, out, in_elems, S0); break;
+        case CG_LAYER_LRN:
+            rc = lrn_fwd_launch(in, out, base + ly.aux_off, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha,
+                                d.lrn_beta, d.lrn_kappa, S0);
+            break;
+        case CG_LAYER_MAXPOOL:
+            rc = maxpool_fwd_launch(in, out, reinterpret_cast<int32_t *>(base + ly.aux_off), B, ly.inC, ly.inH,
+                                    ly.inW, d.k, d.stride, d.pad, S0);
+            break;
+        case CG_LAYER_AVGPOOL: rc = avgpool_fwd_launch(in, out, B * ly.inC, ly.inH * ly.inW, S0); break;
+        case CG_LAYER_DROPOUT: rc = dropout_launch(in, masks[i], out, in_elems, d.drop_p, 0, S0); break;
+        case CG_LAYER_CONCAT: {
+            int c_off = 0;
+            for (int k = 0; k < d.n_inputs && rc == CG_OK; ++k) {
+                int c, h, w;
+                in_shape(*net, d.inputs[k], &c, &h, &w);
+                rc = concat_copy_launch(act(d.inputs[k]), out, B, c, ly.C, c_off, ly.H * ly.W, 1, 0, S0);
+                c_off += c;
+            }
+            break;
+        }
+        case CG_LAYER_SOFTMAX_CE: {
+            Layer &src = net->layers[d.inputs[0]];
+            rc = softmax_ce_launch(in, labels, loss_dev, base + src.grad_off, base + net->loss_off, B,
+                                   src.C * src.H * src.W, S0);
+            src.grad_written = true;
+            break;
+        }
+        }
+    }
+    if (rc) return rc;
+
+    // ---- backward, layers L..1, one turn per layer ----------------------------------------
+    for (int i = L - 2; i >= 0 && rc == CG_OK; --i) {
+        Layer &ly = net->layers[i];
+        const cg_layer_desc &d = ly.d;
+        if (!ly.needs_grad) continue;                // no parameter upstream of or inside this layer
+        if (!ly.grad_written) return CG_EINVAL;      // an output nobody consumed
+        const float *dy = base + ly.grad_off;
+        const float *in = act(d.inputs[0]);
+        const int s0 = d.inputs[0];
+        // gradient with respect to the (first) input, if anything upstream needs it
+        const bool want_dx = s0 >= 0 && net->layers[s0].needs_grad;
+        float *dx = want_dx ? base + net->layers[s0].grad_off : nullptr;
+        const int accum = want_dx && net->layers[s0].grad_written ? 1 : 0;
+        const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
+        switch (d.kind) {
+        case CG_LAYER_CONV:
+            if (want_dx) rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, scratch, scratch_bytes, accum, S0);
+            if (rc == CG_OK)
+                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch, scratch_bytes, S0);
+            break;
+        case CG_LAYER_FC: {
+            const int IN = ly.inC * ly.inH * ly.inW;
+            if (want_dx) rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, accum, S0);
+            if (rc == CG_OK) rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, S0);
+            break;
+        }
+        case CG_LAYER_RELU:
+            if (want_dx) rc = relu_bwd_launch(in, dy, dx, in_elems, accum, S0);
+            break;
+        case CG_LAYER_LRN:
+            if (want_dx)
+                rc = lrn_bwd_launch(in, base + ly.act_off, base + ly.aux_off, dy, dx, B, ly.C, ly.H * ly.W,
+                                    d.lrn_size, d.lrn_alpha, d.lrn_beta, accum, S0);
+            break;
+        case CG_LAYER_MAXPOOL:
+            if (want_dx)
+                rc = maxpool_bwd_launch(dy, reinterpret_cast<const int32_t *>(base + ly.aux_off), dx, B, ly.inC,
+                                        ly.inH, ly.inW, d.k, d.stride, d.pad, accum, S0);
+            break;
+        case CG_LAYER_AVGPOOL:
+            if (want_dx) rc = avgpool_bwd_launch(dy, dx, B * ly.inC, ly.inH * ly.inW, accum, S0);
+            break;
+        case CG_LAYER_DROPOUT:
+            if (want_dx) rc = dropout_launch(dy, masks[i], dx, in_elems, d.drop_p, accum, S0);
+            break;
+        case CG_LAYER_CONCAT: {
+            int c_off = 0;
+            for (int k = 0; k < d.n_inputs && rc == CG_OK; ++k) {
+                int c, h, w;
+                in_shape(*net, d.inputs[k], &c, &h, &w);
+                const int sk = d.inputs[k];
+                if (sk >= 0 && net->layers[sk].needs_grad) {
+                    Layer &src = net->layers[sk];
+                    rc = concat_copy_launch(dy, base + src.grad_off, B, c, ly.C, c_off, ly.H * ly.W, 0,
+                                            src.grad_written ? 1 : 0, S0);
+                    src.grad_written = true;
+                }
+                c_off += c;
+            }
+            break;
+        }
+        default: break;
+        }
+        if (rc) return rc;
+        if (want_dx && d.kind != CG_LAYER_CONCAT) net->layers[s0].grad_written = true;
+
+        if (ly.n_params) {
+            // the turn's second half: aggregate this layer's gradient over the ranks and update its model
+            if (!serial) {
+                CG_HIP_TRY(hipEventRecord(ly.ev_grad, S0));
+                CG_HIP_TRY(hipStreamWaitEvent(S1, ly.ev_grad, 0));
+            }
+            rc = grad_reduce_sgd_impl(ly.w, ly.v, ly.g, ly.peers.data(), (int)ly.peers.size(), (size_t)ly.n_params,
+                                      *sgd, S1);
+            if (rc) return rc;
+            if (!serial) {
+                CG_HIP_TRY(hipEventRecord(ly.ev_upd, S1));
+                ly.upd_pending = true;
+            }
+        }
+    }
+    return rc;
+}

@@ -1,0 +1,106 @@
+"""GPU parity of cg_train_step (forward, backward in inverse layer order, per-layer gradient
+aggregation + update on the second stream) against the oracle's iteration, and the schedule
+invariant: the overlapped two-stream step is bit-identical to the serial one-stream step."""
+import numpy as np
+import pytest
+import torch
+
+import cg_synth
+import paper_1706_00095_amd as cg
+from gpu_util import host, max_abs_rel
+from net_util import GpuNet
+from oracle import net as onet
+from test_oracle_net import _small_alexnet_like
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+SGD = (0.01, 0.9, 5e-4, 1.0)
+
+NETS = {
+    "tiny_cnn_cfg1": lambda: cg_synth.tiny_cnn_layers() + (10, 8, 4, "xavier", 1e-2, 0),
+    "alexnet_like": lambda: _small_alexnet_like() + (7, 6, 4, "fan_in", 1e-3, 4),
+    "inception": lambda: cg_synth.inception_layers(modules=2, cin=12, hw=6, num_classes=9) + (9, 5, 8, "fan_in", 1e-3, 5),
+}
+
+
+def _build(name):
+    layers, in_shape, ncls, B, K, init, pstd, seed = NETS[name]()
+    t = cg_synth.net_tensors(layers, in_shape, B, K, seed=seed, num_classes=ncls, init=init, peer_std=pstd)
+    return layers, in_shape, B, t
+
+
+@pytest.mark.parametrize("name", list(NETS))
+def test_one_iteration_matches_oracle(orc32, name):
+    layers, in_shape, B, t = _build(name)
+    gn = GpuNet(layers, in_shape, B, t)
+    gn.step(SGD)
+    gn.sync()
+    # oracle: same inputs
+    buckets = {k: v.copy() for k, v in t["buckets"].items()}
+    hist = {k: np.zeros_like(v) for k, v in buckets.items()}
+    loss, acts, aux = onet.forward(orc32, layers, t["x"], buckets, t["labels"], t["masks"])
+    grads, dact, _ = onet.backward(orc32, layers, t["x"], buckets, t["masks"], acts, aux)
+    assert abs(float(host(gn.loss)[0]) - float(loss)) <= TOL * max(1.0, abs(float(loss)))
+    for li in range(len(layers) - 1):
+        assert max_abs_rel(host(gn.act(li)), acts[li].ravel()) <= TOL, ("activation", li, layers[li]["kind"])
+    for li, dref in dact.items():
+        if li == len(layers) - 1:
+            continue
+        assert max_abs_rel(host(gn.act(li, 1)), dref.ravel()) <= TOL, ("gradient", li, layers[li]["kind"])
+    for li in grads:
+        assert max_abs_rel(host(gn.g[li]), grads[li]) <= TOL, ("g_local", li)
+        # the update applied to the GPU's own local gradient is bit-exact (Eq. 1, fixed order) ...
+        w, v = t["buckets"][li].copy(), np.zeros_like(t["buckets"][li])
+        orc32.grad_reduce_sgd(w, v, host(gn.g[li]), t["peers"][li], *SGD)
+        assert host(gn.w[li]).tobytes() == w.tobytes() and host(gn.v[li]).tobytes() == v.tobytes()
+        # ... and the whole iteration's model agrees with the oracle's to the conv tolerance
+        orc32.grad_reduce_sgd(buckets[li], hist[li], grads[li], t["peers"][li], *SGD)
+        step_ref = buckets[li] - t["buckets"][li]
+        step_got = host(gn.w[li]) - t["buckets"][li]
+        assert max_abs_rel(step_got, step_ref) <= TOL
+
+
+@pytest.mark.parametrize("name", list(NETS))
+def test_overlapped_schedule_is_bit_identical_to_serial(name):
+    """Strictly synchronous semantics (section 2.2): overlapping the per-layer updates with
+    the rest of backward must not change a single bit, over consecutive iterations (the
+    second one exercises the per-layer wait of forward on the previous update)."""
+    layers, in_shape, B, t = _build(name)
+    a, b = GpuNet(layers, in_shape, B, t), GpuNet(layers, in_shape, B, t)
+    for _ in range(3):
+        a.step(SGD, cg.CG_STEP_OVERLAP)
+        b.step(SGD, cg.CG_STEP_SERIAL)
+    a.sync(); b.sync()
+    assert torch.equal(a.loss[:1], b.loss[:1])
+    for li in a.w:
+        assert torch.equal(a.w[li], b.w[li]) and torch.equal(a.v[li], b.v[li]) and torch.equal(a.g[li], b.g[li])
+    # and it moved: three steps change the model
+    assert not torch.equal(a.w[max(a.w)], GpuNet(layers, in_shape, B, t).w[max(a.w)])
+
+
+def test_loss_decreases_over_iterations_on_fixed_batch():
+    layers, in_shape, B, t = _build("tiny_cnn_cfg1")
+    for li in t["peers"]:
+        t["peers"][li] = []        # single worker: plain SGD on one batch must reduce its loss
+    gn = GpuNet(layers, in_shape, B, t)
+    losses = []
+    for _ in range(30):
+        gn.step((0.05, 0.9, 0.0, 1.0))
+        gn.sync()
+        losses.append(float(host(gn.loss)[0]))
+    assert losses[-1] < 0.7 * losses[0]
+
+
+def test_errors(orc32):
+    layers, in_shape, B, t = _build("tiny_cnn_cfg1")
+    gn = GpuNet(layers, in_shape, B, t)
+    small = torch.empty(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(cg.CgError) as e:
+        cg.cg_train_step(gn.net, gn.x, gn.labels, None, cg.cg_sgd(*SGD), small, gn.s0, gn.s1, gn.loss, 0)
+    assert e.value.code == cg.CG_ENOSPC
+    with pytest.raises(cg.CgError) as e:      # both streams equal without the serial flag
+        cg.cg_train_step(gn.net, gn.x, gn.labels, None, cg.cg_sgd(*SGD), gn.ws, gn.s0, gn.s0, gn.loss, 0)
+    assert e.value.code == cg.CG_EINVAL
+    bad = [dict(kind="relu", inputs=[-1])]
+    with pytest.raises(cg.CgError):
+        cg.Net(bad, 2, (3, 4, 4))            # no loss layer

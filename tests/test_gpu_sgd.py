@@ -1,0 +1,89 @@
+"""GPU parity of cg_grad_reduce_sgd: bit-exact against the float32 oracle (Eq. 1 with the
+solver's history terms, fixed left-to-right sum)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1706_00095_amd as cg
+from gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+def _run_both(orc32, n, K, sgd, seed, v_zero=False, special=None):
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal(n) * 1e-2).astype(F32)
+    v = np.zeros(n, F32) if v_zero else (rng.standard_normal(n) * 1e-4).astype(F32)
+    g = (rng.standard_normal(n) * 1e-3).astype(F32)
+    peers = [(rng.standard_normal(n) * 1e-3).astype(F32) for _ in range(K)]
+    if special is not None:
+        special(w, v, g, peers)
+    dw, dv, dg, dp = dev(w), dev(v), dev(g), [dev(p) for p in peers]
+    cg.cg_grad_reduce_sgd(dw, dv, dg, dp, n, cg.cg_sgd(*sgd))
+    orc32.grad_reduce_sgd(w, v, g, peers, *sgd)
+    gw, gv = host(dw), host(dv)
+    assert gw.tobytes() == w.tobytes(), f"w differs at {np.flatnonzero(gw.view(np.uint32) != w.view(np.uint32))[:5]}"
+    assert gv.tobytes() == v.tobytes()
+    assert np.array_equal(host(dg), g)            # inputs untouched
+
+
+@pytest.mark.parametrize("K", [0, 1, 2, 4, 7, 8, 16, 17, 33, 64])
+def test_bit_exact_all_peer_counts(orc32, K):
+    _run_both(orc32, 70003, K, (0.01, 0.9, 5e-4, 1.0), seed=K)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 1024, 1027, 4 * 256 * 2048 + 1, 4097000])
+def test_bit_exact_ragged_sizes(orc32, n):
+    _run_both(orc32, n, 4, (0.01, 0.9, 5e-4, 1.0), seed=n % 1000)
+
+
+@pytest.mark.parametrize("sgd", [(0.01, 0.9, 5e-4, 0.2), (0.0, 0.9, 5e-4, 1.0), (1.0, 0.0, 0.0, 1.0),
+                                 (0.01, 0.0, 0.0, 1.0), (0.3, 0.99, 0.1, 1.0 / 9)])
+def test_bit_exact_solver_constants(orc32, sgd):
+    _run_both(orc32, 50001, 8, sgd, seed=7)
+
+
+def test_zero_history_first_step(orc32):
+    _run_both(orc32, 34944, 4, (0.01, 0.9, 5e-4, 1.0), seed=3, v_zero=True)
+
+
+def test_denormals_and_nonfinite_match(orc32):
+    def special(w, v, g, peers):
+        g[:8] = [1e-45, -1e-45, 1e-40, np.inf, -np.inf, np.nan, 0.0, -0.0]
+        peers[0][:8] = [1e-45, 1e-45, -1e-41, 1.0, np.inf, 0.0, -0.0, -0.0]
+        w[8:12] = [1e-44, -1e-39, 3e-39, 0.0]
+        v[8:12] = [1e-45, 1e-45, -1e-45, -0.0]
+        g[8:12] = 0.0
+        for p in peers:
+            p[8:12] = 0.0
+    _run_both(orc32, 4099, 2, (1.0, 0.5, 0.5, 1.0), seed=11, special=special)
+
+
+def test_eq1_identical_buffers(orc32):
+    """K identical 12-bit buffers: the sum is exactly (K+1) g (invariant of Eq. 1)."""
+    n = 10000
+    rng = np.random.default_rng(5)
+    g = (rng.integers(-2048, 2048, n) / 1024.0).astype(F32)
+    for K in (4, 8, 16):
+        dw, dv = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+        dg = dev(g)
+        cg.cg_grad_reduce_sgd(dw, dv, dg, [dev(g) for _ in range(K)], n, cg.cg_sgd(1.0, 0.0, 0.0, 1.0))
+        assert np.array_equal(host(dv), F32(K + 1) * g)
+        assert np.array_equal(host(dw), -(F32(K + 1) * g))
+
+
+def test_two_consecutive_steps_and_stream_argument(orc32):
+    n, K = 20001, 4
+    rng = np.random.default_rng(9)
+    w = (rng.standard_normal(n) * 1e-2).astype(F32); v = np.zeros(n, F32)
+    g = (rng.standard_normal(n) * 1e-3).astype(F32)
+    peers = [(rng.standard_normal(n) * 1e-3).astype(F32) for _ in range(K)]
+    dw, dv, dg, dp = dev(w), dev(v), dev(g), [dev(p) for p in peers]
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(2):
+        cg.cg_grad_reduce_sgd(dw, dv, dg, dp, n, cg.cg_sgd(0.01, 0.9, 5e-4, 1.0), stream=s)
+        orc32.grad_reduce_sgd(w, v, g, peers, 0.01, 0.9, 5e-4)
+    s.synchronize()
+    assert host(dw).tobytes() == w.tobytes() and host(dv).tobytes() == v.tobytes()
