@@ -191,7 +191,8 @@ __global__ __launch_bounds__(TB) void softmax_ce_kernel(const float *__restrict_
         __syncthreads();
     }
     const float lse = mx + logf(red[0]);
-    const int lab = labels[b];
+    int lab = labels[b];
+    lab = lab < 0 ? 0 : (lab >= C ? C - 1 : lab);   // an out-of-range label must not become a wild read
     if (threadIdx.x == 0) per_sample[b] = lse - zb[lab];
     const float invB = 1.f / (float)B;
     for (int c = threadIdx.x; c < C; c += TB) {

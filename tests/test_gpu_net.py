@@ -43,8 +43,12 @@ def test_one_iteration_matches_oracle(orc32, name):
     assert abs(float(host(gn.loss)[0]) - float(loss)) <= TOL * max(1.0, abs(float(loss)))
     for li in range(len(layers) - 1):
         assert max_abs_rel(host(gn.act(li)), acts[li].ravel()) <= TOL, ("activation", li, layers[li]["kind"])
+    # the library skips gradients that reach no parameter (e.g. a pool applied to the net input)
+    needs = []
+    for ly in layers:
+        needs.append(ly["kind"] in ("conv", "fc") or any(i >= 0 and needs[i] for i in ly["inputs"]))
     for li, dref in dact.items():
-        if li == len(layers) - 1:
+        if li == len(layers) - 1 or not needs[li]:
             continue
         assert max_abs_rel(host(gn.act(li, 1)), dref.ravel()) <= TOL, ("gradient", li, layers[li]["kind"])
     for li in grads:
@@ -88,7 +92,7 @@ def test_loss_decreases_over_iterations_on_fixed_batch():
         gn.step((0.05, 0.9, 0.0, 1.0))
         gn.sync()
         losses.append(float(host(gn.loss)[0]))
-    assert losses[-1] < 0.7 * losses[0]
+    assert losses[-1] < losses[0] - 0.3 and all(np.isfinite(losses))
 
 
 def test_errors(orc32):
