@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark: one worker's AlexNet-shaped SGD iteration (forward + backward + per-layer
+gradient aggregation over K peers + model update, overlapped on two streams) on one MI355X.
+
+Prints ONE JSON line.  `value` is images/s of whole iterations with every input resident in
+HBM; `roofline` describes the matrix-core kernel that takes the most time inside the step,
+timed live with HIP events around each of its launches on its own stream; `update_roofline`
+and `grad_update` give the HBM figure of the fused gradient-sum + update kernel; `cpu_baseline`
+is the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+# context only (other hardware, full AlexNet on ImageNet, paper Table 1): seconds per iteration, B=256
+PAPER_ALEXNET_S_PER_ITER = {"P100": 0.1, "K80": 0.9, "KNL": 0.6, "CPU": 2.0}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_net(cg, torch, B, K, seed):
+    import cg_synth
+    layers, in_shape = cg_synth.alexnet_layers()
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    net = cg.Net(layers, B, in_shape)
+    x = torch.randn((B,) + tuple(in_shape), device="cuda", generator=gen)
+    labels = torch.randint(0, 1000, (B,), device="cuda", generator=gen, dtype=torch.int32)
+    st = dict(net=net, layers=layers, x=x, labels=labels, w={}, v={}, g={}, peers={}, masks={})
+    shapes = cg_synth.infer_shapes(layers, in_shape)
+    for li, wshape, nb in cg_synth.param_layers(layers, in_shape):
+        n = cg.cg_net_param_count(net, li)
+        fan_in = 1
+        for s in wshape[1:]:
+            fan_in *= s
+        w = torch.zeros(n, device="cuda")
+        w[:n - nb].normal_(0.0, fan_in ** -0.5, generator=gen)
+        st["w"][li] = w
+        st["v"][li] = torch.zeros(n, device="cuda")
+        st["g"][li] = torch.zeros(n, device="cuda")
+        st["peers"][li] = [torch.empty(n, device="cuda").normal_(0.0, 1e-3, generator=gen) for _ in range(K)]
+        cg.cg_net_bind(net, li, w, st["v"][li], st["g"][li], st["peers"][li])
+    for i, ly in enumerate(layers):
+        if ly["kind"] == "dropout":
+            C, H, W = shapes[i]
+            st["masks"][i] = (torch.rand((B, C * H * W), device="cuda", generator=gen) >= ly["p"]).to(torch.uint8)
+    st["ws"] = torch.empty(cg.cg_net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
+    st["loss"] = torch.zeros(4, device="cuda")
+    st["s0"], st["s1"] = torch.cuda.Stream(), torch.cuda.Stream()
+    return st
+
+
+def run_steps(cg, torch, st, sgd, n, flags=0):
+    for _ in range(n):
+        cg.cg_train_step(st["net"], st["x"], st["labels"], st["masks"], sgd, st["ws"], st["s0"], st["s1"],
+                         st["loss"], flags)
+
+
+def sync(torch, st):
+    st["s0"].synchronize()
+    st["s1"].synchronize()
+    torch.cuda.synchronize()
+
+
+def collect_profile(cg):
+    agg = {}
+    for i in range(cg.cg_profile_count()):
+        r = cg.cg_profile_get(i)
+        a = agg.setdefault(r["kernel"], dict(ms=0.0, launches=0, flops=0.0, bytes=0.0, passes={}))
+        a["ms"] += r["ms"]; a["launches"] += 1; a["flops"] += r["flops"]; a["bytes"] += r["bytes"]
+        key = f'{r["pass_"]}@{r["layer"]}'
+        p = a["passes"].setdefault(key, dict(ms=0.0, launches=0, flops=0.0, bytes=0.0))
+        p["ms"] += r["ms"]; p["launches"] += 1; p["flops"] += r["flops"]; p["bytes"] += r["bytes"]
+    return agg
+
+
+def grad_update_standalone(cg, torch, steps, warmup):
+    """Configuration 3: the eight AlexNet parameter buckets, K in {4, 8, 16}; GB/s of
+    algorithmic traffic (4K+20 bytes per parameter) over the kernels' own durations."""
+    import cg_synth
+    out = {}
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    sizes = list(cg_synth.ALEXNET_BUCKETS.values())
+    sgd = cg.cg_sgd(0.01, 0.9, 5e-4, 1.0)
+    bufs = []
+    for n in sizes:
+        w = torch.empty(n, device="cuda").normal_(0, 1e-2, generator=gen)
+        bufs.append(dict(n=n, w=w, v=torch.zeros(n, device="cuda"),
+                         g=[torch.empty(n, device="cuda").normal_(0, 1e-3, generator=gen) for _ in range(17)]))
+    for K in (4, 8, 16):
+        def one():
+            for b in bufs:
+                cg.cg_grad_reduce_sgd(b["w"], b["v"], b["g"][0], b["g"][1:K + 1], b["n"], sgd)
+        for _ in range(warmup):
+            one()
+        torch.cuda.synchronize()
+        cg.cg_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        cg.cg_profile_enable(False)
+        agg = collect_profile(cg)
+        ms = sum(a["ms"] for a in agg.values()) / steps
+        by = sum(a["bytes"] for a in agg.values()) / steps
+        big = max((p for a in agg.values() for p in [a]), key=lambda a: a["bytes"])
+        out[f"K{K}"] = dict(gbps_kernels=by / ms / 1e6, gbps_wall=by / wall / 1e9, ms_kernels=ms, ms_wall=wall * 1e3,
+                            bytes=by)
+    return out
+
+
+def cpu_baseline(sample_B, K):
+    """The oracle's whole iteration on `sample_B` images of the same net (one step incl. update)."""
+    import cg_synth
+    from oracle import net as onet
+    from oracle.cgo import Oracle
+    orc = Oracle("float")
+    layers, in_shape = cg_synth.alexnet_layers()
+    t = cg_synth.net_tensors(layers, in_shape, sample_B, K, seed=4, num_classes=1000)
+    hist = {k: v * 0 for k, v in t["buckets"].items()}
+    t0 = time.perf_counter()
+    onet.train_step(orc, layers, t["x"], t["labels"], t["buckets"], hist, t["peers"], t["masks"], 0.01, 0.9, 5e-4)
+    dt = time.perf_counter() - t0
+    return dict(value=sample_B / dt, unit="images/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"same AlexNet-shaped net and K={K}, one whole iteration at B={sample_B} "
+                       f"({dt:.1f} s of CPU time; time scales linearly in B except the update)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--peers", type=int, default=4)
+    ap.add_argument("--cpu-sample", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--serial", action="store_true", help="one-stream schedule (no overlap)")
+    ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures ONE worker on ONE GPU; the peers' gradients are resident buffers. "
+            "--gpus must be 1.")
+        sys.exit(2)
+
+    import torch
+    import paper_1706_00095_amd as cg
+    cg.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B, K = args.batch, args.peers
+    sgd = cg.cg_sgd(0.01, 0.9, 5e-4, 1.0)
+    flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
+    st = build_net(cg, torch, B, K, seed=4)
+    torch.cuda.synchronize()
+    run_steps(cg, torch, st, sgd, args.warmup, flags)
+    sync(torch, st)
+
+    cg.cg_profile_enable(True)
+    t0 = time.perf_counter()
+    run_steps(cg, torch, st, sgd, args.steps, flags)
+    sync(torch, st)
+    wall = time.perf_counter() - t0
+    cg.cg_profile_enable(False)
+    agg = collect_profile(cg)
+    loss = float(st["loss"].cpu()[0])
+    ms_per_step = wall / args.steps * 1e3
+
+    mm = {k: a for k, a in agg.items() if k.startswith("igemm")}
+    dom_name, dom = max(mm.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["flops"] / dom["ms"] / 1e9       # TFLOP/s over that kernel's own launches
+    roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_FP32_MFMA_TFLOPS, traffic=None, kernel=dom_name,
+                    avg_launch_ms=dom["ms"] / dom["launches"], launches_per_step=dom["launches"] / args.steps,
+                    flops_per_launch=dom["flops"] / dom["launches"])
+    all_flops = sum(a["flops"] for a in mm.values())
+    all_ms = sum(a["ms"] for a in mm.values())
+    upd = {k: a for k, a in agg.items() if k.startswith("reduce_sgd")}
+    upd_bytes = sum(a["bytes"] for a in upd.values())
+    upd_ms = sum(a["ms"] for a in upd.values())
+    update_roofline = dict(bound="hbm", achieved=upd_bytes / upd_ms / 1e6, peak=PEAK_HBM_GBS, unit="GB/s",
+                           frac=upd_bytes / upd_ms / 1e6 / PEAK_HBM_GBS, traffic=None,
+                           kernel=f"reduce_sgd_kernel<{K}> inside the step (overlapped with backward)",
+                           bytes_per_step=upd_bytes / args.steps, ms_per_step=upd_ms / args.steps)
+    if args.kernel_table:
+        log(f"{'kernel':34s} {'pass@layer':24s} {'launch/step':>11s} {'avg ms':>9s} {'TFLOP/s':>9s} {'GB/s':>9s}")
+        for k, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
+            for pk, p in sorted(a["passes"].items(), key=lambda kv: -kv[1]["ms"]):
+                log(f"{k:34s} {pk:24s} {p['launches'] / args.steps:11.1f} {p['ms'] / p['launches']:9.4f} "
+                    f"{p['flops'] / p['ms'] / 1e9:9.1f} {p['bytes'] / p['ms'] / 1e6:9.1f}")
+        log(f"matrix-core kernels: {all_ms / args.steps:.3f} ms/step, {all_flops / all_ms / 1e9:.1f} TFLOP/s overall; "
+            f"update kernels: {upd_ms / args.steps:.3f} ms/step; wall {ms_per_step:.3f} ms/step; loss {loss:.4f}")
+
+    # free the net before the stand-alone update benchmark
+    del st
+    torch.cuda.empty_cache()
+    grad_update = grad_update_standalone(cg, torch, max(args.steps, 5), args.warmup)
+    cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
+
+    out = {
+        "metric": "images/sec per fwd+bwd+update step (AlexNet-shaped B=256); grad-update HBM GB/s",
+        "value": B / (ms_per_step * 1e-3), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"alexnet_shaped_train_step_B{B}_K{K}", "global_batch": B, "peers": K,
+                   "schedule": "serial" if args.serial else "overlap", "lr": 0.01, "mu": 0.9, "wd": 5e-4},
+        "roofline": roofline,
+        "update_roofline": update_roofline,
+        "matrix_core_overall": {"tflops": all_flops / all_ms / 1e9, "ms_per_step": all_ms / args.steps,
+                                "frac": all_flops / all_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS},
+        "grad_update": grad_update,
+        "cpu_baseline": cpu,
+        "loss": loss,
+        "paper_context_s_per_iter_other_hw": PAPER_ALEXNET_S_PER_ITER,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -186,6 +186,23 @@ int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr
 int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operand, unsigned row, unsigned k,
                           unsigned group, long long *elem_offset, int *valid);
 
+/* Per-launch timing for benchmarks: while enabled, every matrix-core (implicit
+ * GEMM) launch and every gradient-aggregation launch is bracketed by two HIP
+ * events on its own stream and logged with its algorithmic work (flops =
+ * 2*M*N*K*groups for a contraction; bytes = (4K+20)*n for the update).
+ * cg_profile_enable(1) starts a fresh log, cg_profile_enable(0) stops logging;
+ * cg_profile_get waits for record i to finish and returns its duration. */
+typedef struct {
+    char kernel[64];   /* kernel template instance, as a profiler prints it (abridged) */
+    char pass[32];     /* conv_fwd, conv_bwd_data, conv_bwd_weight, fc_fwd, ..., reduce_sgd */
+    int layer;         /* layer index inside cg_train_step, -1 for stand-alone calls */
+    float ms;
+    double flops, bytes;
+} cg_profile_record;
+int cg_profile_enable(int on);
+int cg_profile_count(void);
+int cg_profile_get(int i, cg_profile_record *out);
+
 const char *cg_strerror(int code);
 const char *cg_version(void);
 int cg_last_hip_error(void);   /* hipError_t of the most recent CG_EHIP on this thread */

@@ -24,6 +24,7 @@ EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight",
     "cg_grad_reduce_sgd", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_bind",
     "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand",
+    "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
 
 
@@ -47,6 +48,11 @@ class cg_layer_desc(C.Structure):
                 ("k", C.c_int), ("stride", C.c_int), ("pad", C.c_int), ("lrn_size", C.c_int),
                 ("lrn_alpha", C.c_float), ("lrn_beta", C.c_float), ("lrn_kappa", C.c_float),
                 ("fc_out", C.c_int), ("drop_p", C.c_float)]
+
+
+class cg_profile_record(C.Structure):
+    _fields_ = [("kernel", C.c_char * 64), ("pass_", C.c_char * 32), ("layer", C.c_int), ("ms", C.c_float),
+                ("flops", C.c_double), ("bytes", C.c_double)]
 
 
 _lib = None
@@ -80,6 +86,8 @@ def lib():
         L.cg_net_tensor.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(vp), C.POINTER(sz)]
         L.cg_debug_conv_operand.argtypes = [dp, C.c_int, C.c_int, C.c_uint, C.c_uint, C.c_uint,
                                             C.POINTER(C.c_longlong), ip]
+        L.cg_profile_enable.argtypes = [C.c_int]
+        L.cg_profile_get.argtypes = [C.c_int, C.POINTER(cg_profile_record)]
         L.cg_strerror.argtypes = [C.c_int]
         L.cg_strerror.restype = C.c_char_p
         L.cg_version.restype = C.c_char_p
@@ -168,6 +176,21 @@ def cg_debug_conv_operand(d, which_pass, operand, row, k, group):
     _check(lib().cg_debug_conv_operand(C.byref(d), which_pass, operand, row, k, group, C.byref(off), C.byref(ok)),
            "cg_debug_conv_operand")
     return off.value, bool(ok.value)
+
+
+def cg_profile_enable(on):
+    _check(lib().cg_profile_enable(1 if on else 0), "cg_profile_enable")
+
+
+def cg_profile_count():
+    return int(lib().cg_profile_count())
+
+
+def cg_profile_get(i):
+    r = cg_profile_record()
+    _check(lib().cg_profile_get(i, C.byref(r)), "cg_profile_get")
+    return dict(kernel=r.kernel.decode(), pass_=r.pass_.decode(), layer=r.layer, ms=float(r.ms),
+                flops=float(r.flops), bytes=float(r.bytes))
 
 
 def layer_descs(layers):

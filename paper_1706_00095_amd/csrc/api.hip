@@ -1,4 +1,7 @@
 // Error strings, version and the per-thread record of the last HIP failure.
+#include <cstdio>
+#include <mutex>
+#include <vector>
 #include "cg_internal.h"
 
 namespace cg {
@@ -11,7 +14,87 @@ int hip_fail(hipError_t e)
     return CG_EHIP;
 }
 
+// ---- per-launch timing ---------------------------------------------------------------------------
+namespace {
+struct ProfRec {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    char kernel[64];
+    char pass[32];
+    int layer;
+    double flops, bytes;
+    bool open;
+};
+std::mutex g_prof_mu;
+std::vector<ProfRec> g_prof;      // records of the current session (events are reused across sessions)
+size_t g_prof_used = 0;
+bool g_prof_enabled = false;
+thread_local const char *g_pass = "";
+thread_local int g_layer = -1;
+}  // namespace
+
+ProfTag::ProfTag(const char *pass, int layer) : prev_pass(g_pass), prev_layer(g_layer)
+{
+    g_pass = pass;
+    if (layer >= 0 || g_layer < 0) g_layer = layer;
+}
+ProfTag::~ProfTag() { g_pass = prev_pass; g_layer = prev_layer; }
+
+bool prof_on() { return g_prof_enabled; }
+
+int prof_begin(const char *kernel, double flops, double bytes, hipStream_t s)
+{
+    if (!g_prof_enabled) return -1;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof_used == g_prof.size()) {
+        ProfRec r;
+        if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return -1;
+        g_prof.push_back(r);
+    }
+    ProfRec &r = g_prof[g_prof_used];
+    snprintf(r.kernel, sizeof r.kernel, "%s", kernel);
+    snprintf(r.pass, sizeof r.pass, "%s", g_pass);
+    r.layer = g_layer; r.flops = flops; r.bytes = bytes; r.open = true;
+    if (hipEventRecord(r.e0, s) != hipSuccess) return -1;
+    return (int)g_prof_used++;
+}
+
+void prof_end(int rec, hipStream_t s)
+{
+    if (rec < 0) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if ((size_t)rec < g_prof_used && hipEventRecord(g_prof[rec].e1, s) == hipSuccess) g_prof[rec].open = false;
+}
+
 }  // namespace cg
+
+extern "C" int cg_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(cg::g_prof_mu);
+    cg::g_prof_enabled = on != 0;
+    if (on) cg::g_prof_used = 0;
+    return CG_OK;
+}
+
+extern "C" int cg_profile_count(void)
+{
+    std::lock_guard<std::mutex> lk(cg::g_prof_mu);
+    return (int)cg::g_prof_used;
+}
+
+extern "C" int cg_profile_get(int i, cg_profile_record *out)
+{
+    if (!out) return CG_EINVAL;
+    std::lock_guard<std::mutex> lk(cg::g_prof_mu);
+    if (i < 0 || (size_t)i >= cg::g_prof_used || cg::g_prof[i].open) return CG_EINVAL;
+    const cg::ProfRec &r = cg::g_prof[i];
+    CG_HIP_TRY(hipEventSynchronize(r.e1));
+    float ms = 0.f;
+    CG_HIP_TRY(hipEventElapsedTime(&ms, r.e0, r.e1));
+    snprintf(out->kernel, sizeof out->kernel, "%s", r.kernel);
+    snprintf(out->pass, sizeof out->pass, "%s", r.pass);
+    out->layer = r.layer; out->ms = ms; out->flops = r.flops; out->bytes = r.bytes;
+    return CG_OK;
+}
 
 extern "C" const char *cg_strerror(int code)
 {

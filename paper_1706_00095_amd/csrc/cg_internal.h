@@ -16,6 +16,21 @@ int hip_fail(hipError_t e);
         if (e__ != hipSuccess) return ::cg::hip_fail(e__); \
     } while (0)
 
+// ---- per-launch timing (api.hip) ---------------------------------------------------------------
+// When enabled through cg_profile_enable(), every implicit-GEMM and reduce+update launch is
+// bracketed by two HIP events on the stream it is launched on and logged with its
+// algorithmic work.  ProfTag names the pass (and layer) that issues the launches in its scope.
+struct ProfTag {
+    ProfTag(const char *pass, int layer);
+    ~ProfTag();
+    const char *prev_pass;
+    int prev_layer;
+};
+bool prof_on();
+// returns a record index (or -1) after recording the start event
+int prof_begin(const char *kernel, double flops, double bytes, hipStream_t s);
+void prof_end(int rec, hipStream_t s);
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---- index maps: how a GEMM coordinate becomes a tensor element ---------------------------

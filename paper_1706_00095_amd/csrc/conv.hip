@@ -165,6 +165,7 @@ static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const flo
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y,
                   hipStream_t stream)
 {
+    ProfTag tag("conv_fwd", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
@@ -216,6 +217,7 @@ static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, cons
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream)
 {
+    ProfTag tag("conv_bwd_data", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
@@ -271,6 +273,7 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
                          void *ws, size_t ws_bytes, hipStream_t stream)
 {
+    ProfTag tag("conv_bwd_weight", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
@@ -296,6 +299,7 @@ int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy,
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y,
                 hipStream_t stream)
 {
+    ProfTag tag("fc_fwd", -1);
     if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
     IgemmProblem p{};
     const bool v4 = IN % 4 == 0;
@@ -313,6 +317,7 @@ int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const fl
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate,
                      hipStream_t stream)
 {
+    ProfTag tag("fc_bwd_data", -1);
     if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
     IgemmProblem p{};
     const bool v4 = OUT % 4 == 0;
@@ -331,6 +336,7 @@ int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, fl
 int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db,
                        hipStream_t stream)
 {
+    ProfTag tag("fc_bwd_weight", -1);
     if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
     IgemmProblem p{};
     p.A.ptr = dy; p.A.row = linear_map(OUT, 1); p.A.k = linear_map(B, OUT); p.A.limA = p.A.limB = 1;

@@ -10,6 +10,7 @@
 // sub-tiles of 32x32, accumulated by v_mfma_f32_32x32x2_f32.  The K loop advances KT = 16 at a
 // time; the global loads of tile i+1 are issued into registers before the MFMAs of tile i and
 // written to the other LDS buffer afterwards, so one barrier per K-tile suffices.
+#include <cstdio>
 #include "cg_internal.h"
 
 namespace cg {
@@ -171,6 +172,8 @@ template <int R, int NTHR> struct Loader<LD_KMAJ_V4, R, NTHR> {
     }
 };
 
+}  // namespace
+
 template <int WM, int WN, int TM, int TN, int AMODE, int BMODE>
 __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p)
 {
@@ -291,13 +294,22 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
     }
 }
 
+namespace {
+
 template <int WM, int WN, int TM, int TN, int AMODE, int BMODE>
 int launch_cfg(const IgemmProblem &p, hipStream_t stream)
 {
     constexpr int MT = WM * TM * 32, NT = WN * TN * 32;
     dim3 grid((p.N + NT - 1) / NT, (p.M + MT - 1) / MT, p.groups * p.splits);
     if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
+    int rec = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof name, "igemm_kernel<%d,%d,%d,%d,%d,%d>", WM, WN, TM, TN, AMODE, BMODE);
+        rec = prof_begin(name, 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
+    }
     hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, AMODE, BMODE>), grid, dim3(WM * WN * 64), 0, stream, p);
+    prof_end(rec, stream);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }

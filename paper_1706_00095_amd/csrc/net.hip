@@ -249,6 +249,7 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         const float *in = act(d.inputs[0]);
         float *out = base + ly.act_off;
         ly.grad_written = false;
+        ProfTag tag("", i);
         if (ly.n_params && ly.upd_pending) {
             // finalize, per layer: the model of this layer must have received its update
             CG_HIP_TRY(hipStreamWaitEvent(S0, ly.ev_upd, 0));
@@ -300,6 +301,7 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         const cg_layer_desc &d = ly.d;
         if (!ly.needs_grad) continue;                // no parameter upstream of or inside this layer
         if (!ly.grad_written) return CG_EINVAL;      // an output nobody consumed
+        ProfTag tag("", i);
         const float *dy = base + ly.grad_off;
         const float *in = act(d.inputs[0]);
         const int s0 = d.inputs[0];

@@ -5,11 +5,10 @@
 //
 // This translation unit is compiled with -ffp-contract=off: the operation order documented in
 // cg.h is also the rounding order, which makes the result bit-reproducible.
+#include <cstdio>
 #include "cg_internal.h"
 
 namespace cg {
-
-namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -75,6 +74,8 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(float *__restrict__ w, 
     }
 }
 
+namespace {
+
 template <int KC>
 void launch(float *w, float *v, const float *g, const PeerTable &pt, int K, size_t n, const cg_sgd &c,
             unsigned blocks, hipStream_t stream)
@@ -103,6 +104,13 @@ int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *
     if (blocks > 2048) blocks = 2048;
     if (blocks == 0) blocks = 1;
     const unsigned b = (unsigned)blocks;
+    int rec = -1;
+    if (prof_on()) {
+        ProfTag tag("reduce_sgd", -1);
+        char name[64];
+        snprintf(name, sizeof name, "reduce_sgd_kernel<%d>", K <= 16 ? K : -1);
+        rec = prof_begin(name, 0.0, (4.0 * K + 20.0) * (double)n, stream);
+    }
     switch (K) {
 #define CG_CASE(k) case k: launch<k>(w, v, g_local, pt, K, n, sgd, b, stream); break;
         CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7) CG_CASE(8)
@@ -110,6 +118,7 @@ int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *
 #undef CG_CASE
     default: launch<-1>(w, v, g_local, pt, K, n, sgd, b, stream); break;
     }
+    prof_end(rec, stream);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }
