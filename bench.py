@@ -27,14 +27,16 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_net(cg, torch, B, K, seed):
+def build_net(cg, torch, B, K, seed, n_batches=16):
     import cg_synth
     layers, in_shape = cg_synth.alexnet_layers()
     gen = torch.Generator(device="cuda").manual_seed(seed)
     net = cg.Net(layers, B, in_shape)
-    x = torch.randn((B,) + tuple(in_shape), device="cuda", generator=gen)
-    labels = torch.randint(0, 1000, (B,), device="cuda", generator=gen, dtype=torch.int32)
-    st = dict(net=net, layers=layers, x=x, labels=labels, w={}, v={}, g={}, peers={}, masks={})
+    # a small pool of resident batches, visited round-robin: training on one fixed batch memorises
+    # it within ten steps and then diverges, which says nothing about speed but ends in NaNs
+    xs = [torch.randn((B,) + tuple(in_shape), device="cuda", generator=gen) for _ in range(n_batches)]
+    ls = [torch.randint(0, 1000, (B,), device="cuda", generator=gen, dtype=torch.int32) for _ in range(n_batches)]
+    st = dict(net=net, layers=layers, xs=xs, ls=ls, it=0, w={}, v={}, g={}, peers={}, masks={})
     shapes = cg_synth.infer_shapes(layers, in_shape)
     for li, wshape, nb in cg_synth.param_layers(layers, in_shape):
         n = cg.cg_net_param_count(net, li)
@@ -60,7 +62,9 @@ def build_net(cg, torch, B, K, seed):
 
 def run_steps(cg, torch, st, sgd, n, flags=0):
     for _ in range(n):
-        cg.cg_train_step(st["net"], st["x"], st["labels"], st["masks"], sgd, st["ws"], st["s0"], st["s1"],
+        i = st["it"] % len(st["xs"])
+        st["it"] += 1
+        cg.cg_train_step(st["net"], st["xs"][i], st["ls"][i], st["masks"], sgd, st["ws"], st["s0"], st["s1"],
                          st["loss"], flags)
 
 

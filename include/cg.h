@@ -166,15 +166,19 @@ enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1 };
  *  the array may be NULL if the net has no dropout layer), loss_dev: 1 float.
  *  flags: CG_STEP_SERIAL runs the same kernels in the same order on
  *  compute_stream alone (the separate-phases schedule the paper improves on).
+ * The loss and the local gradients are valid in compute_stream order, the
+ * updated w and v in update_stream order.
  * The two streams must differ unless CG_STEP_SERIAL is given. */
 int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                   const uint8_t *const *dropout_masks, const cg_sgd *sgd,
                   void *ws, size_t ws_bytes, void *compute_stream, void *update_stream,
                   float *loss_dev, int flags);
 
-/* Where a layer's output (which = 0) or the gradient with respect to its
- * output (which = 1) lives inside a workspace of base address ws after a step;
- * for inspection by tests.  count receives the number of floats. */
+/* Where a layer's output (which = 0), the gradient with respect to its output
+ * (which = 1) or its saved forward state (which = 2: the LRN scale as floats,
+ * the max-pool argmax as int32 flat indices ih*W+iw; empty for other layers)
+ * lives inside a workspace of base address ws after a step; for inspection by
+ * tests.  count receives the number of 4-byte elements. */
 int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count);
 
 /* Test hook (host only, launches nothing): which element of which tensor the

@@ -115,28 +115,35 @@ int igemm_launch(const IgemmProblem &p, hipStream_t stream);
 // Host-side evaluation of one operand element: offset and validity (for tests of the maps).
 void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, uint32_t K, int64_t *off, int *valid);
 
-// out[i] = sum_{s<splits} part[s*stride + i] in index order (+ nothing else); n floats.
-int splitk_reduce_launch(const float *part, int64_t stride, int splits, float *out, size_t n, hipStream_t stream);
-// db[m] = sum over n and pixels of dy[n][m][pix]
-int bias_grad_launch(const float *dy, int N, int M, int P, float *db, hipStream_t stream);
+// Split-K front end: when C has too few tiles to fill the chip, the K range is cut into slices
+// whose partial results go to `ws` and are then added in slice order (so results do not depend
+// on scheduling).  igemm_ws_bytes() says how much workspace igemm_run() needs for a problem.
+struct SplitPlan { uint32_t splits, k_per_split; size_t ws_bytes; };
+SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups, int a_mode);
+size_t igemm_ws_bytes(const IgemmProblem &p);
+int igemm_run(const IgemmProblem &p, void *ws, size_t ws_bytes, hipStream_t stream);
+// db[m] = sum over n and pixels of dy[n][m][pix]; two passes over `ws`, fixed order
+size_t bias_grad_ws_bytes(int N, int M);
+int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, size_t ws_bytes,
+                     hipStream_t stream);
 
 
 // ---- convolution / fully-connected passes (conv.hip) ----------------------------------------
-struct BwdWeightPlan { uint32_t splits, k_per_split; size_t ws_bytes; };
 int conv_check(const cg_conv_desc *d, int *OH, int *OW);
-BwdWeightPlan plan_bwd_weight(const cg_conv_desc &d, int OH, int OW);
-int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y,
-                  hipStream_t stream);
+size_t conv_ws_bytes(const cg_conv_desc &d, int pass);
+size_t fc_ws_bytes(int B, int IN, int OUT, int pass);
+int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
+                  size_t ws_bytes, hipStream_t stream);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream);
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
                          void *ws, size_t ws_bytes, hipStream_t stream);
-int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y,
-                hipStream_t stream);
-int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate,
-                     hipStream_t stream);
-int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db,
-                       hipStream_t stream);
+int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
+                size_t ws_bytes, hipStream_t stream);
+int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate, void *ws,
+                     size_t ws_bytes, hipStream_t stream);
+int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
+                       size_t ws_bytes, hipStream_t stream);
 
 // ---- gradient aggregation + update (sgd.hip) --------------------------------------------------
 int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *const *g_peers, int K,

@@ -11,6 +11,8 @@ namespace cg {
 
 namespace {
 
+size_t round256(size_t v) { return (v + 255) / 256 * 256; }
+
 // input pixel grid seen through the filter: index (n, oh, ow) -> window origin in x
 IndexMap window_origin_map(const cg_conv_desc &d, int OH, int OW)
 {
@@ -114,26 +116,6 @@ int conv_check(const cg_conv_desc *d, int *OH, int *OW)
     return CG_OK;
 }
 
-BwdWeightPlan plan_bwd_weight(const cg_conv_desc &d, int OH, int OW)
-{
-    BwdWeightPlan pl;
-    const uint32_t Mg = d.M / d.groups, Ng = (uint32_t)(d.C / d.groups) * d.KH * d.KW;
-    const uint64_t K = (uint64_t)d.N * OH * OW;
-    const uint32_t mt = Mg > 96 ? 128 : (Mg > 64 ? 96 : (Mg > 32 ? 64 : 32));
-    const uint64_t tiles = (uint64_t)((Mg + mt - 1) / mt) * ((Ng + 127) / 128) * d.groups;
-    uint64_t want = (1024 + tiles - 1) / tiles;        // aim at ~4 blocks per compute unit
-    const uint64_t max_by_k = (K + 255) / 256;         // at least 256 reduction steps per slice
-    if (want > max_by_k) want = max_by_k;
-    if (want < 1) want = 1;
-    if (want > 512) want = 512;
-    uint64_t per = (K + want - 1) / want;
-    per = (per + 15) / 16 * 16;
-    pl.k_per_split = (uint32_t)per;
-    pl.splits = (uint32_t)((K + per - 1) / per);
-    pl.ws_bytes = pl.splits > 1 ? (size_t)pl.splits * d.M * Ng * sizeof(float) : 0;
-    return pl;
-}
-
 static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *w,
                                 const float *bias, float *y)
 {
@@ -162,14 +144,14 @@ static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const flo
     return p;
 }
 
-int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y,
-                  hipStream_t stream)
+int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
+                  size_t ws_bytes, hipStream_t stream)
 {
     ProfTag tag("conv_fwd", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
-    return igemm_launch(fwd_problem(d, OH, OW, x, w, bias, y), stream);
+    return igemm_run(fwd_problem(d, OH, OW, x, w, bias, y), ws, ws_bytes, stream);
 }
 
 static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *wt,
@@ -230,8 +212,8 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         CG_HIP_TRY(hipGetLastError());
         return CG_OK;
     }
-    const size_t need = (size_t)d.M * Cg * KK * sizeof(float);
-    if (!ws || ws_bytes < need) return CG_ENOSPC;
+    const size_t wt_bytes = round256((size_t)d.M * Cg * KK * sizeof(float));
+    if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
     if (!aligned16(ws)) return CG_EINVAL;
     float *wt = static_cast<float *>(ws);
     {
@@ -240,11 +222,12 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
         CG_HIP_TRY(hipGetLastError());
     }
-    return igemm_launch(bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate), stream);
+    return igemm_run(bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate), static_cast<char *>(ws) + wt_bytes,
+                     ws_bytes - wt_bytes, stream);
 }
 
-static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const BwdWeightPlan &pl,
-                                       const float *x, const float *dy, float *dw, void *ws)
+static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *dy,
+                                       float *dw)
 {
     const int G = d.groups, Cg = d.C / G, Mg = d.M / G, Kg = Cg * d.KH * d.KW, P = OH * OW;
     IgemmProblem p{};
@@ -260,13 +243,12 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
     p.B.limA = d.H; p.B.limB = d.W;
     p.B.gstride = (int64_t)Cg * d.H * d.W;
     p.b_mode = LD_KMAJ_S;
-    p.c_ptr = pl.splits > 1 ? static_cast<float *>(ws) : dw;
+    p.c_ptr = dw;
     p.c_row_stride = Kg;
     p.c_col = linear_map(Kg, 1);
     p.c_gstride = (int64_t)Mg * Kg;
-    p.c_split_stride = (int64_t)d.M * Kg;
     p.M = Mg; p.N = Kg; p.K = (uint32_t)d.N * P;
-    p.groups = G; p.splits = pl.splits; p.k_per_split = pl.k_per_split;
+    p.groups = G; p.splits = 1; p.k_per_split = p.K;
     return p;
 }
 
@@ -277,30 +259,40 @@ int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy,
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
-    const int Kg = (d.C / d.groups) * d.KH * d.KW, P = OH * OW;
-    const BwdWeightPlan pl = plan_bwd_weight(d, OH, OW);
-    if (pl.splits > 1) {
-        if (!ws || ws_bytes < pl.ws_bytes) return CG_ENOSPC;
+    const IgemmProblem p = bwd_weight_problem(d, OH, OW, x, dy, dw);
+    const size_t split_bytes = round256(igemm_ws_bytes(p));
+    const size_t bias_bytes = db ? bias_grad_ws_bytes(d.N, d.M) : 0;
+    if (split_bytes + bias_bytes > 0) {
+        if (!ws || ws_bytes < split_bytes + bias_bytes) return CG_ENOSPC;
         if (!aligned16(ws)) return CG_EINVAL;
     }
-    int r = igemm_launch(bwd_weight_problem(d, OH, OW, pl, x, dy, dw, ws), stream);
+    const int r = igemm_run(p, ws, split_bytes, stream);
     if (r) return r;
-    if (pl.splits > 1) {
-        r = splitk_reduce_launch(static_cast<const float *>(ws), (int64_t)d.M * Kg, (int)pl.splits, dw,
-                                 (size_t)d.M * Kg, stream);
-        if (r) return r;
-    }
-    if (db) return bias_grad_launch(dy, d.N, d.M, P, db, stream);
+    if (db) return bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes, stream);
     return CG_OK;
+}
+
+size_t conv_ws_bytes(const cg_conv_desc &d, int pass)
+{
+    int OH, OW;
+    if (conv_check(&d, &OH, &OW)) return 0;
+    if (pass == CG_PASS_FWD) return igemm_ws_bytes(fwd_problem(d, OH, OW, nullptr, nullptr, nullptr, nullptr));
+    if (pass == CG_PASS_BWD_DATA) {
+        if (d.stride_h != 1 || d.stride_w != 1) return 0;
+        return round256((size_t)d.M * (d.C / d.groups) * d.KH * d.KW * sizeof(float)) +
+               igemm_ws_bytes(bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0));
+    }
+    if (pass == CG_PASS_BWD_WEIGHT)
+        return round256(igemm_ws_bytes(bwd_weight_problem(d, OH, OW, nullptr, nullptr, nullptr))) +
+               bias_grad_ws_bytes(d.N, d.M);
+    return 0;
 }
 
 // ---- fully connected: y[b][o] = bias[o] + sum_i x[b][i] W[o][i] ------------------------------
 
-int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y,
-                hipStream_t stream)
+static IgemmProblem fc_fwd_problem(int B, int IN, int OUT, const float *x, const float *W, const float *bias,
+                                   float *y)
 {
-    ProfTag tag("fc_fwd", -1);
-    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
     IgemmProblem p{};
     const bool v4 = IN % 4 == 0;
     p.A.ptr = x; p.A.row = linear_map(B, IN); p.A.k = linear_map(IN, 1); p.A.limA = p.A.limB = 1; p.A.vec4_ok = v4;
@@ -310,15 +302,13 @@ int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const fl
     p.bias = bias; p.bias_mode = bias ? 2 : 0;
     p.M = B; p.N = OUT; p.K = IN;
     p.groups = 1; p.splits = 1; p.k_per_split = p.K;
-    return igemm_launch(p, stream);
+    return p;
 }
 
 // dx[b][i] = sum_o dy[b][o] W[o][i]
-int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate,
-                     hipStream_t stream)
+static IgemmProblem fc_bwd_data_problem(int B, int IN, int OUT, const float *dy, const float *W, float *dx,
+                                        int accumulate)
 {
-    ProfTag tag("fc_bwd_data", -1);
-    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
     IgemmProblem p{};
     const bool v4 = OUT % 4 == 0;
     p.A.ptr = dy; p.A.row = linear_map(B, OUT); p.A.k = linear_map(OUT, 1); p.A.limA = p.A.limB = 1; p.A.vec4_ok = v4;
@@ -329,15 +319,12 @@ int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, fl
     p.M = B; p.N = IN; p.K = OUT;
     p.groups = 1; p.splits = 1; p.k_per_split = p.K;
     p.accumulate = accumulate;
-    return igemm_launch(p, stream);
+    return p;
 }
 
 // dW[o][i] = sum_b dy[b][o] x[b][i];  db[o] = sum_b dy[b][o]
-int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db,
-                       hipStream_t stream)
+static IgemmProblem fc_bwd_weight_problem(int B, int IN, int OUT, const float *x, const float *dy, float *dW)
 {
-    ProfTag tag("fc_bwd_weight", -1);
-    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
     IgemmProblem p{};
     p.A.ptr = dy; p.A.row = linear_map(OUT, 1); p.A.k = linear_map(B, OUT); p.A.limA = p.A.limB = 1;
     p.B.ptr = x; p.B.row = linear_map(IN, 1); p.B.k = linear_map(B, IN); p.B.limA = p.B.limB = 1;
@@ -345,10 +332,42 @@ int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, 
     p.c_ptr = dW; p.c_row_stride = IN; p.c_col = linear_map(IN, 1);
     p.M = OUT; p.N = IN; p.K = B;
     p.groups = 1; p.splits = 1; p.k_per_split = p.K;
-    const int r = igemm_launch(p, stream);
+    return p;
+}
+
+int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
+                size_t ws_bytes, hipStream_t stream)
+{
+    ProfTag tag("fc_fwd", -1);
+    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    return igemm_run(fc_fwd_problem(B, IN, OUT, x, W, bias, y), ws, ws_bytes, stream);
+}
+
+int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate, void *ws,
+                     size_t ws_bytes, hipStream_t stream)
+{
+    ProfTag tag("fc_bwd_data", -1);
+    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    return igemm_run(fc_bwd_data_problem(B, IN, OUT, dy, W, dx, accumulate), ws, ws_bytes, stream);
+}
+
+int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
+                       size_t ws_bytes, hipStream_t stream)
+{
+    ProfTag tag("fc_bwd_weight", -1);
+    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    const int r = igemm_run(fc_bwd_weight_problem(B, IN, OUT, x, dy, dW), ws, ws_bytes, stream);
     if (r) return r;
     if (db) return fc_bias_grad_launch(dy, B, OUT, db, stream);
     return CG_OK;
+}
+
+size_t fc_ws_bytes(int B, int IN, int OUT, int pass)
+{
+    if (B <= 0 || IN <= 0 || OUT <= 0) return 0;
+    if (pass == CG_PASS_FWD) return igemm_ws_bytes(fc_fwd_problem(B, IN, OUT, nullptr, nullptr, nullptr, nullptr));
+    if (pass == CG_PASS_BWD_DATA) return igemm_ws_bytes(fc_bwd_data_problem(B, IN, OUT, nullptr, nullptr, nullptr, 0));
+    return igemm_ws_bytes(fc_bwd_weight_problem(B, IN, OUT, nullptr, nullptr, nullptr));
 }
 
 }  // namespace cg
@@ -370,7 +389,7 @@ extern "C" int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operan
         if (d->stride_h != 1 || d->stride_w != 1) return CG_EUNSUPPORTED;
         p = bwd_data_problem(*d, OH, OW, nullptr, nullptr, nullptr, 0);
     } else if (pass == CG_PASS_BWD_WEIGHT)
-        p = bwd_weight_problem(*d, OH, OW, plan_bwd_weight(*d, OH, OW), nullptr, nullptr, nullptr, nullptr);
+        p = bwd_weight_problem(*d, OH, OW, nullptr, nullptr, nullptr);
     else return CG_EINVAL;
     const Operand &op = operand == 0 ? p.A : p.B;
     if (row >= op.row.count || k >= p.K) return CG_EINVAL;
@@ -387,22 +406,15 @@ extern "C" int cg_conv_out_shape(const cg_conv_desc *d, int *OH, int *OW)
 
 extern "C" size_t cg_conv_workspace_bytes(const cg_conv_desc *d, int pass)
 {
-    int OH, OW;
-    if (conv_check(d, &OH, &OW)) return 0;
-    if (pass == CG_PASS_BWD_DATA) {
-        if (d->stride_h != 1 || d->stride_w != 1) return 0;
-        return (size_t)d->M * (d->C / d->groups) * d->KH * d->KW * sizeof(float);
-    }
-    if (pass == CG_PASS_BWD_WEIGHT) return plan_bwd_weight(*d, OH, OW).ws_bytes;
-    return 0;
+    return d ? conv_ws_bytes(*d, pass) : 0;
 }
 
 extern "C" int cg_conv_fwd(const cg_conv_desc *d, const float *x, const float *w, const float *bias, float *y,
-                           void *, size_t, void *stream)
+                           void *ws, size_t ws_bytes, void *stream)
 {
     if (!d || !x || !w || !y) return CG_EINVAL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return CG_EINVAL;
-    return conv_fwd_impl(*d, x, w, bias, y, static_cast<hipStream_t>(stream));
+    return conv_fwd_impl(*d, x, w, bias, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,

@@ -409,30 +409,124 @@ int igemm_launch(const IgemmProblem &p, hipStream_t stream)
     return CG_EUNSUPPORTED;
 }
 
-// ---- small companions of the split-K backward-weight pass --------------------------------
+// ---- split-K: more blocks for problems whose C has few tiles ---------------------------------
 
 namespace {
 
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int64_t stride,
-                                                            int splits, float *__restrict__ out, size_t n)
+struct FinishArgs {
+    const float *part;
+    int64_t plane;            // floats between consecutive K slices: groups * M * N
+    int splits;
+    float *c_ptr;
+    int32_t c_row_stride;
+    IndexMap c_col;
+    int64_t c_gstride;
+    const float *bias;
+    int bias_mode;
+    int32_t bias_gstride;
+    uint32_t M, N;
+    FastDiv divN, divMN;
+    int accumulate;
+    uint32_t total;           // groups * M * N
+};
+
+// C = (sum over K slices, in slice order) + bias, written through the problem's output map.
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
 {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-        float s = part[i];
-        for (int k = 1; k < splits; ++k) s += part[(size_t)k * stride + i];
-        out[i] = s;
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < a.total; i += gridDim.x * 256) {
+        float s = a.part[i];
+        for (int k = 1; k < a.splits; ++k) s += a.part[(int64_t)k * a.plane + i];
+        const uint32_t g = fdiv(i, a.divMN), r = i - g * a.divMN.d;
+        const uint32_t m = fdiv(r, a.divN), n = r - m * a.divN.d;
+        if (a.bias_mode == 1) s += a.bias[(int64_t)g * a.bias_gstride + m];
+        else if (a.bias_mode == 2) s += a.bias[(int64_t)g * a.bias_gstride + n];
+        const Info ci = map_info(a.c_col, n, a.N);
+        float *dst = a.c_ptr + (int64_t)g * a.c_gstride + ((int32_t)m * a.c_row_stride + ci.off);
+        if (a.accumulate) s += *dst;
+        *dst = s;
     }
 }
 
-// One block per output channel m: sums dy[n][m][0..P) over n in a fixed tree order.
-__global__ __launch_bounds__(256) void bias_grad_kernel(const float *__restrict__ dy, int N, int M, int P,
-                                                        float *__restrict__ db)
+}  // namespace
+
+SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups, int a_mode)
 {
-    const int m = blockIdx.x;
+    SplitPlan pl{1, K, 0};
+    const uint32_t mt = (uint32_t)pick_mt(M, a_mode != LD_RMAJ_S);
+    const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
+    if (tiles >= 512) return pl;
+    uint64_t want = (1024 + tiles - 1) / tiles;      // aim at ~4 resident blocks per compute unit
+    const uint64_t max_by_k = K / 128;               // keep at least 8 K-tiles per slice
+    if (want > max_by_k) want = max_by_k;
+    if (want > 512) want = 512;
+    if (want < 2) return pl;
+    if ((uint64_t)groups * M * N >= (1ull << 31)) return pl;
+    uint64_t per = (K + want - 1) / want;
+    per = (per + KT - 1) / KT * KT;
+    pl.k_per_split = (uint32_t)per;
+    pl.splits = (uint32_t)((K + per - 1) / per);
+    if (pl.splits < 2) return SplitPlan{1, K, 0};
+    pl.ws_bytes = (size_t)pl.splits * groups * M * N * sizeof(float);
+    return pl;
+}
+
+size_t igemm_ws_bytes(const IgemmProblem &p)
+{
+    return plan_split(p.M, p.N, p.K, p.groups, p.a_mode).ws_bytes;
+}
+
+int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t stream)
+{
+    const SplitPlan pl = plan_split(p0.M, p0.N, p0.K, p0.groups, p0.a_mode);
+    if (pl.splits <= 1) {
+        IgemmProblem p = p0;
+        p.splits = 1; p.k_per_split = p.K;
+        return igemm_launch(p, stream);
+    }
+    if (!ws || ws_bytes < pl.ws_bytes) return CG_ENOSPC;
+    if (!aligned16(ws) || !p0.c_ptr) return CG_EINVAL;
+    if (p0.bias_mode && !p0.bias) return CG_EINVAL;
+    IgemmProblem p = p0;
+    p.c_ptr = static_cast<float *>(ws);
+    p.c_row_stride = (int32_t)p0.N;
+    p.c_col = linear_map(p0.N, 1);
+    p.c_gstride = (int64_t)p0.M * p0.N;
+    p.c_split_stride = (int64_t)p0.groups * p0.M * p0.N;
+    p.bias = nullptr; p.bias_mode = 0; p.accumulate = 0;
+    p.splits = pl.splits; p.k_per_split = pl.k_per_split;
+    const int rc = igemm_launch(p, stream);
+    if (rc) return rc;
+    FinishArgs a{};
+    a.part = static_cast<const float *>(ws);
+    a.plane = p.c_split_stride;
+    a.splits = (int)pl.splits;
+    a.c_ptr = p0.c_ptr; a.c_row_stride = p0.c_row_stride; a.c_col = p0.c_col; a.c_gstride = p0.c_gstride;
+    a.bias = p0.bias; a.bias_mode = p0.bias_mode; a.bias_gstride = p0.bias_gstride;
+    a.M = p0.M; a.N = p0.N;
+    a.divN = make_fastdiv(p0.N);
+    a.divMN = make_fastdiv(p0.M * p0.N);
+    a.accumulate = p0.accumulate;
+    a.total = p0.groups * p0.M * p0.N;
+    const unsigned blocks = (a.total + 255) / 256 < 8192 ? (a.total + 255) / 256 : 8192;
+    hipLaunchKernelGGL(splitk_finish_kernel, dim3(blocks), dim3(256), 0, stream, a);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
+// ---- bias gradient of a convolution: db[m] = sum over n and pixels of dy[n][m][pix] ------------
+
+namespace {
+
+// block (m, s) sums the samples of slice s; the slices are added afterwards in slice order
+__global__ __launch_bounds__(256) void bias_grad_partial_kernel(const float *__restrict__ dy, int N, int M, int P,
+                                                                int n_per, float *__restrict__ part)
+{
+    const int m = blockIdx.x, sl = blockIdx.y;
+    const int n_beg = sl * n_per, n_end = min(N, n_beg + n_per);
     float s = 0.f;
-    const long long total = (long long)N * P;
-    for (long long i = threadIdx.x; i < total; i += 256) {
-        const long long n = i / P, q = i - n * P;
-        s += dy[((size_t)n * M + m) * P + q];
+    for (int n = n_beg; n < n_end; ++n) {
+        const float *src = dy + ((size_t)n * M + m) * P;
+        for (int q = threadIdx.x; q < P; q += 256) s += src[q];
     }
     __shared__ float red[256];
     red[threadIdx.x] = s;
@@ -441,25 +535,45 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const float *__restrict_
         if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) db[m] = red[0];
+    if (threadIdx.x == 0) part[(size_t)sl * M + m] = red[0];
+}
+
+__global__ __launch_bounds__(256) void bias_grad_finish_kernel(const float *__restrict__ part, int M, int S,
+                                                               float *__restrict__ db)
+{
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= M) return;
+    float s = 0.f;
+    for (int k = 0; k < S; ++k) s += part[(size_t)k * M + m];
+    db[m] = s;
+}
+
+int bias_slices(int N, int M)
+{
+    int S = (2048 + M - 1) / M;
+    if (S > N) S = N;
+    return S < 1 ? 1 : S;
 }
 
 }  // namespace
 
-int splitk_reduce_launch(const float *part, int64_t stride, int splits, float *out, size_t n, hipStream_t stream)
+size_t bias_grad_ws_bytes(int N, int M)
 {
-    if (!part || !out || splits < 1) return CG_EINVAL;
-    if (n == 0) return CG_OK;
-    const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, part, stride, splits, out, n);
-    CG_HIP_TRY(hipGetLastError());
-    return CG_OK;
+    return (size_t)bias_slices(N, M) * M * sizeof(float);
 }
 
-int bias_grad_launch(const float *dy, int N, int M, int P, float *db, hipStream_t stream)
+int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, size_t ws_bytes,
+                     hipStream_t stream)
 {
     if (!dy || !db || N <= 0 || M <= 0 || P <= 0) return CG_EINVAL;
-    hipLaunchKernelGGL(bias_grad_kernel, dim3(M), dim3(256), 0, stream, dy, N, M, P, db);
+    if (!ws || ws_bytes < bias_grad_ws_bytes(N, M)) return CG_ENOSPC;
+    const int S = bias_slices(N, M);
+    const int n_per = (N + S - 1) / S;
+    const int S2 = (N + n_per - 1) / n_per;
+    float *part = static_cast<float *>(ws);
+    hipLaunchKernelGGL(bias_grad_partial_kernel, dim3(M, S2), dim3(256), 0, stream, dy, N, M, P, n_per, part);
+    CG_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, part, M, S2, db);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }

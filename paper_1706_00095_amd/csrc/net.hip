@@ -84,10 +84,10 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
             ly.C = ly.conv.M; ly.H = OH; ly.W = OW;
             ly.n_weights = (long long)ly.conv.M * (ly.inC / ly.conv.groups) * ly.conv.KH * ly.conv.KW;
             ly.n_params = ly.n_weights + ly.conv.M;
-            size_t s1 = cg_conv_workspace_bytes(&ly.conv, CG_PASS_BWD_DATA);
-            size_t s2 = cg_conv_workspace_bytes(&ly.conv, CG_PASS_BWD_WEIGHT);
-            if (s1 > scratch) scratch = s1;
-            if (s2 > scratch) scratch = s2;
+            for (int pass = 0; pass < 3; ++pass) {
+                const size_t sb = conv_ws_bytes(ly.conv, pass);
+                if (sb > scratch) scratch = sb;
+            }
             ly.needs_grad = true;
             break;
         }
@@ -97,6 +97,10 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
             ly.n_weights = (long long)d.fc_out * ly.inC * ly.inH * ly.inW;
             ly.n_params = ly.n_weights + d.fc_out;
             if (ly.n_weights >= (1ll << 29)) rc = CG_EUNSUPPORTED;
+            for (int pass = 0; pass < 3; ++pass) {
+                const size_t sb = fc_ws_bytes(B, ly.inC * ly.inH * ly.inW, d.fc_out, pass);
+                if (sb > scratch) scratch = sb;
+            }
             ly.needs_grad = true;
             break;
         case CG_LAYER_RELU: case CG_LAYER_DROPOUT:
@@ -213,8 +217,9 @@ extern "C" int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, 
     float *base = static_cast<float *>(ws);
     if (which == 0) *ptr = base + ly.act_off;
     else if (which == 1) *ptr = base + ly.grad_off;
+    else if (which == 2) *ptr = base + ly.aux_off;
     else return CG_EINVAL;
-    *count = ly.out_elems;
+    *count = which == 2 ? ly.aux_elems : ly.out_elems;
     return CG_OK;
 }
 
@@ -258,10 +263,11 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
         switch (d.kind) {
         case CG_LAYER_CONV:
-            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, S0);
+            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, S0);
             break;
         case CG_LAYER_FC:
-            rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, S0);
+            rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, scratch,
+                             scratch_bytes, S0);
             break;
         case CG_LAYER_RELU: rc = relu_fwd_launch(in, out, in_elems, S0); break;
         case CG_LAYER_LRN:
@@ -318,8 +324,9 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             break;
         case CG_LAYER_FC: {
             const int IN = ly.inC * ly.inH * ly.inW;
-            if (want_dx) rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, accum, S0);
-            if (rc == CG_OK) rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, S0);
+            if (want_dx) rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, accum, scratch, scratch_bytes, S0);
+            if (rc == CG_OK)
+                rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch, scratch_bytes, S0);
             break;
         }
         case CG_LAYER_RELU:

@@ -1,0 +1,146 @@
+"""Parity at the benchmark's real sizes, in the launch configuration bench.py times.
+
+The oracle cannot run a whole AlexNet-shaped iteration at B=256 in test time, so:
+ - the three fully-connected layers run at B=256 as their own net (oracle: seconds);
+ - the whole AlexNet-shaped net runs at B=16 against the oracle element by element;
+ - each AlexNet convolution layer at B=256 is checked on sampled outputs the oracle's
+   definition gives one by one, and through the adjoint identities, which hold at any size.
+"""
+import numpy as np
+import pytest
+import torch
+
+import cg_synth
+import paper_1706_00095_amd as cg
+from gpu_util import conv_bwd_data, conv_bwd_weight, conv_fwd, dev, host, max_abs_rel
+from net_util import GpuNet
+from oracle import net as onet
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+SGD = (0.01, 0.9, 5e-4, 1.0)
+
+
+def _backward_state_from_gpu_forward(orc32, gn, layers, t, acts):
+    """Backward depends on decisions taken in forward (ReLU sign, max-pool winner).  On a deep
+    net a forward value that differs in the last bit can flip such a decision, and the two
+    backward passes then differ legitimately.  So the oracle's backward is run from the GPU's own
+    forward activations: both sides take every decision in fp32 on the same numbers.  The
+    max-pool winners the GPU stored must then be exactly the oracle's."""
+    acts_g = [host(gn.act(li)).reshape(acts[li].shape) for li in range(len(layers) - 1)] + [acts[-1]]
+    aux_g = []
+    for li, ly in enumerate(layers):
+        src = ly["inputs"][0]
+        a = t["x"] if src < 0 else acts_g[src]
+        if ly["kind"] == "conv":
+            from oracle.cgo import conv_desc
+            N, C, H, W = a.shape
+            aux_g.append(conv_desc(N, C, H, W, ly["M"], ly["k"], ly["stride"], ly["pad"], ly["groups"]))
+        elif ly["kind"] == "lrn":
+            aux_g.append(orc32.lrn_fwd(a, ly["size"], ly["alpha"], ly["beta"], ly["kappa"])[1])
+        elif ly["kind"] == "maxpool":
+            am = orc32.maxpool_fwd(a, ly["k"], ly["stride"], ly["pad"])[1]
+            got = host(gn.act(li, 2)).view(np.int32).reshape(am.shape)
+            assert np.array_equal(got, am), ("max-pool winners", li)
+            aux_g.append(am)
+        elif ly["kind"] == "softmax_ce":
+            aux_g.append(orc32.softmax_ce(a.reshape(a.shape[0], -1), t["labels"])[1].reshape(a.shape))
+        else:
+            aux_g.append(None)
+    return acts_g, aux_g
+
+
+def _check_step(orc32, layers, in_shape, B, t):
+    gn = GpuNet(layers, in_shape, B, t)
+    gn.step(SGD)
+    gn.sync()
+    buckets = {k: v.copy() for k, v in t["buckets"].items()}
+    loss, acts, aux = onet.forward(orc32, layers, t["x"], buckets, t["labels"], t["masks"])
+    assert abs(float(host(gn.loss)[0]) - float(loss)) <= TOL * max(1.0, abs(float(loss)))
+    for li in range(len(layers) - 1):
+        assert max_abs_rel(host(gn.act(li)), acts[li].ravel()) <= TOL, ("activation", li, layers[li]["kind"])
+    acts_g, aux_g = _backward_state_from_gpu_forward(orc32, gn, layers, t, acts)
+    grads, dact, _ = onet.backward(orc32, layers, t["x"], buckets, t["masks"], acts_g, aux_g)
+    for li in grads:
+        assert max_abs_rel(host(gn.g[li]), grads[li]) <= TOL, ("g_local", li)
+        w, v = t["buckets"][li].copy(), np.zeros_like(t["buckets"][li])
+        orc32.grad_reduce_sgd(w, v, host(gn.g[li]), t["peers"][li], *SGD)
+        assert host(gn.w[li]).tobytes() == w.tobytes() and host(gn.v[li]).tobytes() == v.tobytes()
+    return gn
+
+
+def test_fully_connected_stack_at_b256(orc32):
+    """fc6/fc7/fc8 of the AlexNet-shaped net (9216 -> 4096 -> 4096 -> 1000) with ReLU and dropout."""
+    layers = [
+        dict(kind="relu", inputs=[-1]),      # keeps an input gradient path alive for fc6's backward-data
+        dict(kind="fc", inputs=[0], out=4096), dict(kind="relu", inputs=[1]), dict(kind="dropout", inputs=[2], p=0.5),
+        dict(kind="fc", inputs=[3], out=4096), dict(kind="relu", inputs=[4]), dict(kind="dropout", inputs=[5], p=0.5),
+        dict(kind="fc", inputs=[6], out=1000), dict(kind="softmax_ce", inputs=[7]),
+    ]
+    in_shape, B = (256, 6, 6), 256
+    t = cg_synth.net_tensors(layers, in_shape, B, 2, seed=8, num_classes=1000)
+    _check_step(orc32, layers, in_shape, B, t)
+
+
+def test_whole_alexnet_shaped_iteration_at_b16(orc32):
+    layers, in_shape = cg_synth.alexnet_layers()
+    B = 16
+    t = cg_synth.net_tensors(layers, in_shape, B, 1, seed=4, num_classes=1000)
+    _check_step(orc32, layers, in_shape, B, t)
+
+
+def _sample_fwd(x, w, b, c, n, m, oh, ow):
+    """One output element from the definition, in double."""
+    G = c["groups"]; Cg = c["C"] // G; Mg = c["M"] // G; g = m // Mg
+    acc = float(b[m])
+    for ci in range(Cg):
+        for kh in range(c["k"]):
+            ih = oh * c["stride"] - c["pad"] + kh
+            if not 0 <= ih < c["H"]:
+                continue
+            for kw in range(c["k"]):
+                iw = ow * c["stride"] - c["pad"] + kw
+                if 0 <= iw < c["H"]:
+                    acc += float(x[n, g * Cg + ci, ih, iw]) * float(w[m, ci, kh, kw])
+    return acc
+
+
+@pytest.mark.parametrize("layer", list(cg_synth.ALEXNET_CONVS))
+def test_alexnet_conv_layer_at_b256_samples_and_adjoints(layer):
+    B = 256
+    c, x, w, b, dy = cg_synth.conv_layer_tensors(layer, B, seed=1 + list(cg_synth.ALEXNET_CONVS).index(layer))
+    d = cg.conv_desc(B, c["C"], c["H"], c["H"], c["M"], c["k"], stride=c["stride"], pad=c["pad"], groups=c["groups"])
+    dx_, dw_, db_, dy_ = dev(x), dev(w), dev(b), dev(dy)
+    y = host(conv_fwd(d, dx_, dw_, db_))
+    assert np.isfinite(y).all()
+    rng = np.random.default_rng(0)
+    OH = y.shape[2]
+    scale = np.abs(y).max()
+    picks = [(0, 0, 0, 0), (B - 1, c["M"] - 1, OH - 1, OH - 1)] + \
+        [tuple(int(rng.integers(0, hi)) for hi in (B, c["M"], OH, OH)) for _ in range(40)]
+    for (n, m, oh, ow) in picks:
+        ref = _sample_fwd(x, w, b, c, n, m, oh, ow)
+        assert abs(float(y[n, m, oh, ow]) - ref) <= TOL * scale, (n, m, oh, ow)
+    # adjoint identities in double on the host: <conv(x,w), dy> = <x, bwd_data(dy,w)> = <w, bwd_weight(x,dy)>
+    y0 = y - b.reshape(1, -1, 1, 1)
+    lhs = float((y0.astype(np.float64) * dy).sum())
+    dxg = host(conv_bwd_data(d, dy_, dw_))
+    gdw, gdb = conv_bwd_weight(d, dx_, dy_)
+    gdw, gdb = host(gdw), host(gdb)
+    norm = float(np.sqrt((y0.astype(np.float64) ** 2).sum()) * np.sqrt((dy.astype(np.float64) ** 2).sum()))
+    assert abs(lhs - float((dxg.astype(np.float64) * x).sum())) <= 1e-4 * norm
+    assert abs(lhs - float((gdw.astype(np.float64) * w).sum())) <= 1e-4 * norm
+    rdb = dy.astype(np.float64).sum(axis=(0, 2, 3))
+    assert max_abs_rel(gdb, rdb) <= TOL
+    # sampled backward-weight elements straight from the definition
+    Cg = c["C"] // c["groups"]; Mg = c["M"] // c["groups"]
+    s, p = c["stride"], c["pad"]
+    wscale = np.abs(gdw).max()
+    for _ in range(6):
+        m, ci, kh, kw = (int(rng.integers(0, hi)) for hi in (c["M"], Cg, c["k"], c["k"]))
+        g = m // Mg
+        oh_lo, oh_hi = max(0, -(-(p - kh) // s)), min(OH - 1, (c["H"] - 1 + p - kh) // s)
+        ow_lo, ow_hi = max(0, -(-(p - kw) // s)), min(OH - 1, (c["H"] - 1 + p - kw) // s)
+        xs = x[:, g * Cg + ci, oh_lo * s - p + kh:oh_hi * s - p + kh + 1:s, ow_lo * s - p + kw:ow_hi * s - p + kw + 1:s]
+        ref = float((xs.astype(np.float64) * dy[:, m, oh_lo:oh_hi + 1, ow_lo:ow_hi + 1]).sum())
+        assert abs(float(gdw[m, ci, kh, kw]) - ref) <= TOL * wscale, (m, ci, kh, kw)
