@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcg.so")
+LIB_PATH = os.environ.get("CG_LIB_PATH", os.path.join(_HERE, "libcg.so"))
 
 CG_OK, CG_EINVAL, CG_ENOSPC, CG_EUNSUPPORTED, CG_EHIP = 0, -1, -2, -3, -4
 CG_PASS_FWD, CG_PASS_BWD_DATA, CG_PASS_BWD_WEIGHT = 0, 1, 2

@@ -15,11 +15,13 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # the update kernel's operation order is its rounding order: no fused multiply-add there
 PER_FILE = {"sgd.hip": ["-ffp-contract=off"]}
+EXTRA = os.environ.get("CG_EXTRA_FLAGS", "").split()
+LIB = os.environ.get("CG_LIB_OUT", LIB)
 
 
 def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *COMMON, *EXTRA, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 feature switch; that warning is harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)

@@ -11,6 +11,9 @@
 // time; the global loads of tile i+1 are issued into registers before the MFMAs of tile i and
 // written to the other LDS buffer afterwards, so one barrier per K-tile suffices.
 #include <cstdio>
+#include <cstdlib>
+#include <type_traits>
+#include <utility>
 #include "cg_internal.h"
 
 namespace cg {
@@ -19,16 +22,52 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int KT = 16;
+#ifndef CG_KT
+#define CG_KT 32
+#endif
+constexpr int KT = CG_KT;
+#ifndef CG_SIDE
+#define CG_SIDE 15   // timing experiments only: which loader step kinds run in the K loop
+#endif
+#ifndef CG_EXP
+#define CG_EXP 0   // timing experiments only: 1 = no loader steps in the K loop
+#endif
 
 // ---- tile loaders -----------------------------------------------------------------------
-// A loader moves one R x KT operand tile global -> registers (gload) -> LDS (sstore) and says
-// where the MFMA fragment of a lane lives in LDS (frag).  Two LDS layouts:
+// A loader moves one R x KT operand tile global -> registers -> LDS and says where the MFMA
+// fragment of a lane lives in LDS (frag).  Two LDS layouts:
 //   k-major  [row][k], row stride KT+4: for operands that are contiguous along k in memory;
 //   row-major [k][row], row stride R+8: for operands that are contiguous along the row index.
 // In both, lane (i = lane&31, h = lane>>5) of a wave fetches for one 8-wide k step the four
 // values k = kb + 4h + t, t = 0..3 of row i; MFMA number t of the step consumes value t.  Which
 // k a lane half holds is immaterial as long as A and B agree.
+//
+// The work of a loader is cut into single-element steps so that the K loop can place one step
+// behind each MFMA: tables() reads the index tables of a tile into registers, issue<I, SET>()
+// starts global load I into register set SET, store<I, SET>() writes it to LDS.  Whether an
+// element is a real one or zero padding is kept as a bit and applied at store time, so no
+// instruction between issue and store depends on the loaded value.
+
+template <int B, class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, B + Is>{}), ...);
+}
+template <int B, int E, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl<B>(f, std::make_integer_sequence<int, (E > B ? E - B : 0)>{});
+}
+
+#define CG_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Validity of an element as a sign mask, in vector arithmetic only (a compare that goes through
+// scalar registers costs the in-order wave more latency than the MFMA shadow hides):
+// all-ones if a or b lies outside [0, limA) x [0, limB), zero otherwise.  Coordinates and limits
+// are far below 2^30, so the sign bit of each term is exact.
+__device__ __forceinline__ int32_t invalid_mask(int32_t a, int32_t b, int32_t limA1, int32_t limB1)
+{
+    return ((limA1 - a) | (limB1 - b) | a | b) >> 31;
+}
 
 template <int MODE, int R, int NTHR> struct Loader;
 
@@ -40,34 +79,40 @@ template <int R, int NTHR> struct Loader<LD_RMAJ_S, R, NTHR> {
     static constexpr int RS = R + 8;
     static constexpr int SZ = KT * RS;
     static constexpr int RTAB = 1;
-    float v[CNT];
+    float v[2][CNT];
+    uint32_t badm[2];
+    int4 ke[2];          // ring of k-table entries: step I uses ke[I & 1] and fetches the next one
     Info ri;
     int r, kp;
 
-    __device__ void init(const Operand &op, uint32_t row0, uint32_t row_limit, int t, int4 *)
+    __device__ __forceinline__ void init(const Operand &op, uint32_t row0, uint32_t row_limit, int t, int4 *)
     {
         r = t % R;
         kp = t / R;
         ri = map_info(op.row, row0 + r, row_limit);
     }
-    __device__ void gload(const float *base, uint32_t limA, uint32_t limB, const int4 *ktab, const int4 *)
+    __device__ __forceinline__ void tables(const int4 *ktab, const int4 *) { ke[0] = ktab[kp]; }
+    template <int I, int SET>
+    __device__ __forceinline__ void issue(const float *base, uint32_t limA, uint32_t limB, const int4 *ktab,
+                                          const int4 *)
     {
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) {
-            const int4 ki = ktab[kp + i * NP];
-            const bool ok = (uint32_t)(ri.a + ki.y) < limA && (uint32_t)(ri.b + ki.z) < limB;
-            const uint32_t off = ok ? (uint32_t)(ri.off + ki.x) : 0u;
-            const float x = base[off];
-            v[i] = ok ? x : 0.f;
-        }
+        if constexpr (I + 1 < CNT) ke[(I + 1) & 1] = ktab[kp + (I + 1) * NP];
+        const int4 e = ke[I & 1];
+        const int32_t m = invalid_mask(ri.a + e.y, ri.b + e.z, (int32_t)limA - 1, (int32_t)limB - 1);
+        badm[SET] = (I == 0 ? 0u : badm[SET]) | ((uint32_t)m & (1u << I));
+        v[SET][I] = base[(uint32_t)((ri.off + e.x) & ~m)];
     }
-    __device__ void sstore(float *s) const
+    template <int I, int SET> __device__ __forceinline__ void store(float *s) const
     {
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) s[(kp + i * NP) * RS + r] = v[i];
+#if CG_SIDE & 16
+        asm volatile("" ::"v"(v[SET][I]));            // timing experiment: wait for the load, no LDS store
+#elif CG_SIDE & 32
+        s[(kp + I * NP) * RS + r] = (float)I;          // timing experiment: LDS store without the load
+#else
+        s[(kp + I * NP) * RS + r] = (badm[SET] >> I) & 1u ? 0.f : v[SET][I];
+#endif
     }
-    // fragment: 4 scalars
-    __device__ static void frag(const float *s, int row, int kb, int h, float out[4])
+    __device__ __forceinline__ static void frag(const float *s, int row, int kb, int h, float out[4])
     {
 #pragma unroll
         for (int t = 0; t < 4; ++t) out[t] = s[(kb + 4 * h + t) * RS + row];
@@ -81,42 +126,43 @@ template <int R, int NTHR> struct Loader<LD_KMAJ_S, R, NTHR> {
     static constexpr int RS = KT + 4;
     static constexpr int SZ = R * RS;
     static constexpr int RTAB = R;
-    float v[CNT];
+    float v[2][CNT];
+    uint32_t badm[2];
+    int4 ki;
+    int4 re[2];          // ring of row-table entries
     int kl, r0;
 
-    __device__ void init(const Operand &op, uint32_t row0, uint32_t row_limit, int t, int4 *rtab)
+    __device__ __forceinline__ void init(const Operand &op, uint32_t row0, uint32_t row_limit, int t, int4 *rtab)
     {
         kl = t % KT;
         r0 = t / KT;
-        for (int r = t; r < R; r += NTHR) {
-            const Info ri = map_info(op.row, row0 + r, row_limit);
-            rtab[r] = make_int4(ri.off, ri.a, ri.b, 0);
+        for (int rr = t; rr < R; rr += NTHR) {
+            const Info q = map_info(op.row, row0 + rr, row_limit);
+            rtab[rr] = make_int4(q.off, q.a, q.b, 0);
         }
     }
-    __device__ void gload(const float *base, uint32_t limA, uint32_t limB, const int4 *ktab, const int4 *rtab)
+    __device__ __forceinline__ int row_of(int i) const { return (R % RP == 0 || r0 + i * RP < R) ? r0 + i * RP : 0; }
+    __device__ __forceinline__ void tables(const int4 *ktab, const int4 *rtab)
     {
-        const int4 ki = ktab[kl];
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) {
-            const int r = r0 + i * RP;
-            if (R % RP == 0 || r < R) {
-                const int4 ri = rtab[r];
-                const bool ok = (uint32_t)(ri.y + ki.y) < limA && (uint32_t)(ri.z + ki.z) < limB;
-                const uint32_t off = ok ? (uint32_t)(ri.x + ki.x) : 0u;
-                const float x = base[off];
-                v[i] = ok ? x : 0.f;
-            }
-        }
+        ki = ktab[kl];
+        re[0] = rtab[row_of(0)];
     }
-    __device__ void sstore(float *s) const
+    template <int I, int SET>
+    __device__ __forceinline__ void issue(const float *base, uint32_t limA, uint32_t limB, const int4 *,
+                                          const int4 *rtab)
     {
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) {
-            const int r = r0 + i * RP;
-            if (R % RP == 0 || r < R) s[r * RS + kl] = v[i];
-        }
+        if constexpr (I + 1 < CNT) re[(I + 1) & 1] = rtab[row_of(I + 1)];
+        const int4 e = re[I & 1];
+        const int32_t m = invalid_mask(e.y + ki.y, e.z + ki.z, (int32_t)limA - 1, (int32_t)limB - 1);
+        badm[SET] = (I == 0 ? 0u : badm[SET]) | ((uint32_t)m & (1u << I));
+        v[SET][I] = base[(uint32_t)((e.x + ki.x) & ~m)];
     }
-    __device__ static void frag(const float *s, int row, int kb, int h, float out[4])
+    template <int I, int SET> __device__ __forceinline__ void store(float *s) const
+    {
+        const int rr = r0 + I * RP;
+        if (R % RP == 0 || rr < R) s[rr * RS + kl] = (badm[SET] >> I) & 1u ? 0.f : v[SET][I];
+    }
+    __device__ __forceinline__ static void frag(const float *s, int row, int kb, int h, float out[4])
     {
         const float4 q = *reinterpret_cast<const float4 *>(s + row * RS + kb + 4 * h);
         out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
@@ -130,42 +176,55 @@ template <int R, int NTHR> struct Loader<LD_KMAJ_V4, R, NTHR> {
     static constexpr int RS = KT + 4;
     static constexpr int SZ = R * RS;
     static constexpr int RTAB = R;
-    float4 v[CNT];
+    float4 v[2][CNT];
+    uint32_t badm[2];
+    int4 ki;
+    int4 re[2];          // ring of row-table entries
     int k4, r0;
 
-    __device__ void init(const Operand &op, uint32_t row0, uint32_t row_limit, int t, int4 *rtab)
+    __device__ __forceinline__ void init(const Operand &op, uint32_t row0, uint32_t row_limit, int t, int4 *rtab)
     {
         k4 = t % KQ;
         r0 = t / KQ;
-        for (int r = t; r < R; r += NTHR) {
-            const Info ri = map_info(op.row, row0 + r, row_limit);
-            rtab[r] = make_int4(ri.off, ri.a, ri.b, 0);
+        for (int rr = t; rr < R; rr += NTHR) {
+            const Info q = map_info(op.row, row0 + rr, row_limit);
+            rtab[rr] = make_int4(q.off, q.a, q.b, 0);
         }
     }
-    __device__ void gload(const float *base, uint32_t limA, uint32_t limB, const int4 *ktab, const int4 *rtab)
+    __device__ __forceinline__ int row_of(int i) const { return (R % RP == 0 || r0 + i * RP < R) ? r0 + i * RP : 0; }
+    __device__ __forceinline__ void tables(const int4 *ktab, const int4 *rtab)
     {
-        const int4 ki = ktab[4 * k4];
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) {
-            const int r = r0 + i * RP;
-            if (R % RP == 0 || r < R) {
-                const int4 ri = rtab[r];
-                const bool ok = (uint32_t)(ri.y + ki.y) < limA && (uint32_t)(ri.z + ki.z) < limB;
-                const uint32_t off = ok ? (uint32_t)(ri.x + ki.x) : 0u;
-                const float4 x = *reinterpret_cast<const float4 *>(base + off);
-                v[i] = ok ? x : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
+        ki = ktab[4 * k4];
+        re[0] = rtab[row_of(0)];
     }
-    __device__ void sstore(float *s) const
+    template <int I, int SET>
+    __device__ __forceinline__ void issue(const float *base, uint32_t limA, uint32_t limB, const int4 *,
+                                          const int4 *rtab)
     {
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) {
-            const int r = r0 + i * RP;
-            if (R % RP == 0 || r < R) *reinterpret_cast<float4 *>(s + r * RS + 4 * k4) = v[i];
+        if constexpr (I + 1 < CNT) re[(I + 1) & 1] = rtab[row_of(I + 1)];
+        const int4 e = re[I & 1];
+        const int32_t m = invalid_mask(e.y + ki.y, e.z + ki.z, (int32_t)limA - 1, (int32_t)limB - 1);
+        badm[SET] = (I == 0 ? 0u : badm[SET]) | ((uint32_t)m & (1u << I));
+        v[SET][I] = *reinterpret_cast<const float4 *>(base + (uint32_t)((e.x + ki.x) & ~m));
+    }
+    template <int I, int SET> __device__ __forceinline__ void store(float *s) const
+    {
+        const int rr = r0 + I * RP;
+        if (R % RP == 0 || rr < R) {
+            const int32_t keep = (badm[SET] >> I) & 1u ? 0 : -1;
+            float4 q = v[SET][I];
+            q.x = __int_as_float(__float_as_int(q.x) & keep); q.y = __int_as_float(__float_as_int(q.y) & keep);
+            q.z = __int_as_float(__float_as_int(q.z) & keep); q.w = __int_as_float(__float_as_int(q.w) & keep);
+#if CG_SIDE & 16
+            asm volatile("" ::"v"(q.x), "v"(q.y), "v"(q.z), "v"(q.w));
+#elif CG_SIDE & 32
+            *reinterpret_cast<float4 *>(s + rr * RS + 4 * k4) = make_float4(1.f, 2.f, 3.f, 4.f);
+#else
+            *reinterpret_cast<float4 *>(s + rr * RS + 4 * k4) = q;
+#endif
         }
     }
-    __device__ static void frag(const float *s, int row, int kb, int h, float out[4])
+    __device__ __forceinline__ static void frag(const float *s, int row, int kb, int h, float out[4])
     {
         const float4 q = *reinterpret_cast<const float4 *>(s + row * RS + kb + 4 * h);
         out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
@@ -174,6 +233,18 @@ template <int R, int NTHR> struct Loader<LD_KMAJ_V4, R, NTHR> {
 
 }  // namespace
 
+#if CG_EXP == 3
+__device__ long long g_trace[4][16];
+#define CG_T() __builtin_readcyclecounter()
+#endif
+
+// K loop, software-pipelined for a single wave.  While the MFMAs of tile `it` run out of LDS
+// buffer it&1, the same wave (a) issues the global loads of tile it+2 into register set it&1 and
+// (b) writes tile it+1, loaded one iteration earlier into the other register set, to LDS buffer
+// (it+1)&1.  One loader step is placed behind each MFMA and pinned there, so the matrix pipe of
+// a SIMD is kept busy by one wave alone and a global load has a whole K-tile of time to land.
+// Tiles past the end of the K range are loaded as all-padding (offset 0, stored as zeros) and
+// never consumed, which keeps the loop body free of conditions.
 template <int WM, int WN, int TM, int TN, int AMODE, int BMODE>
 __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p)
 {
@@ -181,16 +252,22 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
     constexpr int MT = WM * TM * 32, NT = WN * TN * 32;
     using LA = Loader<AMODE, MT, NTHR>;
     using LB = Loader<BMODE, NT, NTHR>;
+    constexpr int CA = LA::CNT, CB = LB::CNT;
+    constexpr int NM = (KT / 2) * TM * TN;            // MFMAs per K-tile and wave
+    // loader steps per K-tile, in issue order: B tables, A tables, CB + CA global loads, 4 stages of the k-info of tile it+3, CA + CB LDS stores
+    constexpr int J_TB = 0, J_TA = 1, J_BI = 2, J_AI = J_BI + CB, J_K = J_AI + CA, J_AS = J_K + 4,
+                  J_BS = J_AS + CA, NI = J_BS + CB;
 
     __shared__ __attribute__((aligned(16))) float sA[2][LA::SZ];
     __shared__ __attribute__((aligned(16))) float sB[2][LB::SZ];
-    __shared__ int4 kA[2][KT];
-    __shared__ int4 kB[2][KT];
+    __shared__ int4 kA[3][KT];
+    __shared__ int4 kB[3][KT];
     __shared__ int4 rA[LA::RTAB];
     __shared__ int4 rB[LB::RTAB];
 
     const int t = threadIdx.x;
-    const int lane = t & 63, wave = t >> 6;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: lives in a scalar register
     const int wm = wave / WN, wn = wave % WN;
     const int h = lane >> 5, li = lane & 31;
 
@@ -202,19 +279,47 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
 
     const float *a_base = p.A.ptr + (int64_t)g * p.A.gstride;
     const float *b_base = p.B.ptr + (int64_t)g * p.B.gstride;
+    const uint32_t a_limA = p.A.limA, a_limB = p.A.limB, b_limA = p.B.limA, b_limB = p.B.limB;
 
     LA la;
     LB lb;
     la.init(p.A, m0, p.M, t, rA);
     lb.init(p.B, n0, p.N, t, rB);
 
-    // k-info of K-tile `it` is produced by the first 2*KT threads into table (it & 1)
-    auto put_kinfo = [&](int it) {
-        if (t < 2 * KT) {
-            const uint32_t k = kbeg + (uint32_t)it * KT + (uint32_t)(t & (KT - 1));
-            const Info ki = map_info(t < KT ? p.A.k : p.B.k, k, kend);
-            (t < KT ? kA : kB)[it & 1][t & (KT - 1)] = make_int4(ki.off, ki.a, ki.b, 0);
+    // k-info of K-tile `tile` goes to table slot tile % 3.  Wave 0 produces operand A's entries,
+    // wave 1 operand B's; the choice is wave-uniform, so the selected map constants are scalar
+    // values (never a pointer into the argument block, which would put a memory wait into the
+    // K loop).  kinfo_stage<0..3> is the same computation cut into four short pieces, each of
+    // which fits behind one MFMA.
+    const bool kw0 = wave == 0;
+#define CG_KSEL(f) (kw0 ? p.A.k.f : p.B.k.f)
+    const FastDiv kd1{CG_KSEL(d1.d), CG_KSEL(d1.mul), CG_KSEL(d1.sh)}, kd2{CG_KSEL(d2.d), CG_KSEL(d2.mul), CG_KSEL(d2.sh)};
+    const int32_t ks1 = CG_KSEL(s1), ks2 = CG_KSEL(s2), ks3 = CG_KSEL(s3), ko0 = CG_KSEL(o0);
+    const int32_t ksa = CG_KSEL(sa), ka0 = CG_KSEL(a0), ksb = CG_KSEL(sb), kb0 = CG_KSEL(b0);
+#undef CG_KSEL
+    int4 (*const ktab_mine)[KT] = kw0 ? kA : kB;
+    uint32_t kq_k = 0, kq_q1 = 0, kq_r1 = 0, kq_q2 = 0, kq_r2 = 0;
+    auto kinfo_stage = [&](auto SC, int tile) {
+        constexpr int S = decltype(SC)::value;
+        if (wave < 2) {
+            if constexpr (S == 0) {
+                kq_k = kbeg + (uint32_t)tile * KT + (uint32_t)(lane & (KT - 1));
+                kq_q1 = fdiv(kq_k, kd1);
+            } else if constexpr (S == 1) {
+                kq_r1 = kq_k - kq_q1 * kd1.d;
+                kq_q2 = fdiv(kq_r1, kd2);
+            } else if constexpr (S == 2) {
+                kq_r2 = kq_r1 - kq_q2 * kd2.d;
+            } else {
+                const bool ok = kq_k < kend;
+                const int32_t off = (int32_t)kq_q1 * ks1 + (int32_t)kq_q2 * ks2 + (int32_t)kq_r2 * ks3 + ko0;
+                const int32_t a = (int32_t)kq_q2 * ksa + ka0, b = (int32_t)kq_r2 * ksb + kb0;
+                if (lane < KT) ktab_mine[tile % 3][lane] = make_int4(ok ? off : 0, ok ? a : kInvalidA, ok ? b : 0, 0);
+            }
         }
+    };
+    auto put_kinfo = [&](int tile) {
+        static_for<0, 4>([&](auto SC) { kinfo_stage(SC, tile); });
     };
 
     v16f acc[TM][TN];
@@ -225,48 +330,107 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // prologue: tile 0 -> LDS buffer 0, tile 1 -> register set 1, k-info of tile 2 ready
     put_kinfo(0);
+    put_kinfo(1);
+    put_kinfo(2);
     __syncthreads();
-    la.gload(a_base, p.A.limA, p.A.limB, kA[0], rA);
-    lb.gload(b_base, p.B.limA, p.B.limB, kB[0], rB);
-    if (n_iter > 1) put_kinfo(1);
-    la.sstore(sA[0]);
-    lb.sstore(sB[0]);
+    la.tables(kA[0], rA);
+    lb.tables(kB[0], rB);
+    static_for<0, CA>([&](auto I) { la.template issue<decltype(I)::value, 0>(a_base, a_limA, a_limB, kA[0], rA); });
+    static_for<0, CB>([&](auto I) { lb.template issue<decltype(I)::value, 0>(b_base, b_limA, b_limB, kB[0], rB); });
+    static_for<0, CA>([&](auto I) { la.template store<decltype(I)::value, 0>(sA[0]); });
+    static_for<0, CB>([&](auto I) { lb.template store<decltype(I)::value, 0>(sB[0]); });
+    la.tables(kA[1], rA);
+    lb.tables(kB[1], rB);
+    static_for<0, CA>([&](auto I) { la.template issue<decltype(I)::value, 1>(a_base, a_limA, a_limB, kA[1], rA); });
+    static_for<0, CB>([&](auto I) { lb.template issue<decltype(I)::value, 1>(b_base, b_limA, b_limB, kB[1], rB); });
     __syncthreads();
 
-    for (int it = 0; it < n_iter; ++it) {
-        const int cur = it & 1;
-        if (it + 1 < n_iter) {
-            la.gload(a_base, p.A.limA, p.A.limB, kA[cur ^ 1], rA);
-            lb.gload(b_base, p.B.limA, p.B.limB, kB[cur ^ 1], rB);
-        }
-        if (it + 2 < n_iter) put_kinfo(it + 2);
-
-        const float *a_s = sA[cur];
-        const float *b_s = sB[cur];
+#if CG_EXP == 3
+    long long tr_top = 0, tr_mfma = 0, tr_bar = 0, tr_seg[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long tr_prev = 0;
+    const long long tr_begin = CG_T();
+#endif
+    auto iteration = [&](auto PARC, int it) {
+        constexpr int PAR = decltype(PARC)::value;    // it & 1, known at compile time
+#if CG_EXP == 3
+        const long long t0 = CG_T();
+#endif
+        const float *a_s = sA[PAR];
+        const float *b_s = sB[PAR];
+        float *a_d = sA[PAR ^ 1];
+        float *b_d = sB[PAR ^ 1];
+        float af[2][TM][4], bf[2][TN][4];      // fragments of k-step ks live in ring slot ks & 1
+        // only the first k-step's fragments are fetched before the first MFMA: right after the
+        // barrier all four waves hit the LDS at once, so everything else is spread over the slots
 #pragma unroll
-        for (int kb = 0; kb < KT; kb += 8) {
-            float af[TM][4], bf[TN][4];
+        for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, 0, h, af[0][i]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, kb, h, af[i]);
+        for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, 0, h, bf[0][j]);
+        const int slot2 = (it + 2) % 3;
+        CG_SCHED_FENCE();
+#if CG_EXP == 3
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        const long long t1 = CG_T();
+        tr_prev = t1;
+        CG_SCHED_FENCE();
+#endif
+        static_for<0, NM>([&](auto MC) {
+            constexpr int mi = decltype(MC)::value;
+            constexpr int ks = mi / (4 * TM * TN), s = (mi / (TM * TN)) % 4, i = (mi / TN) % TM, j = mi % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks & 1][i][s], bf[ks & 1][j][s], acc[i][j], 0, 0, 0);
+#if CG_EXP == 3
+            if constexpr (mi > 0 && mi % (NM / 8) == 0) {
+                const long long tn = CG_T();
+                tr_seg[mi / (NM / 8) - 1] += tn - tr_prev;
+                tr_prev = tn;
+            }
+#endif
+            // the next k-step's fragments are fetched while this k-step's MFMAs run
+            if constexpr (mi % (4 * TM * TN) == 0 && ks + 1 < KT / 8) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, kb, h, bf[j]);
+                for (int i2 = 0; i2 < TM; ++i2) LA::frag(a_s, (wm * TM + i2) * 32 + li, (ks + 1) * 8, h, af[(ks + 1) & 1][i2]);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][s], bf[j][s], acc[i][j], 0, 0, 0);
-        }
-
-        if (it + 1 < n_iter) {
-            la.sstore(sA[cur ^ 1]);
-            lb.sstore(sB[cur ^ 1]);
-        }
+                for (int j2 = 0; j2 < TN; ++j2) LB::frag(b_s, (wn * TN + j2) * 32 + li, (ks + 1) * 8, h, bf[(ks + 1) & 1][j2]);
+            }
+            // loader steps lo..hi-1 ride behind this MFMA
+            constexpr int lo = (mi * NI + NM - 1) / NM, hi = ((mi + 1) * NI + NM - 1) / NM;
+            static_for<lo, hi>([&](auto JC) {
+                constexpr int jj = decltype(JC)::value;
+                if constexpr (jj == J_TB) { if constexpr (CG_SIDE & 8) lb.tables(kB[slot2], rB); }
+                else if constexpr (jj == J_TA) { if constexpr (CG_SIDE & 8) la.tables(kA[slot2], rA); }
+                else if constexpr (jj < J_AI) { if constexpr (CG_SIDE & 1) lb.template issue<jj - J_BI, PAR>(b_base, b_limA, b_limB, kB[slot2], rB); }
+                else if constexpr (jj < J_K) { if constexpr (CG_SIDE & 1) la.template issue<jj - J_AI, PAR>(a_base, a_limA, a_limB, kA[slot2], rA); }
+                else if constexpr (jj < J_AS) { if constexpr (CG_SIDE & 4) kinfo_stage(std::integral_constant<int, jj - J_K>{}, it + 3); }
+                else if constexpr (jj < J_BS) { if constexpr (CG_SIDE & 2) la.template store<jj - J_AS, PAR ^ 1>(a_d); }
+                else { if constexpr (CG_SIDE & 2) lb.template store<jj - J_BS, PAR ^ 1>(b_d); }
+            });
+            CG_SCHED_FENCE();
+        });
+#if CG_EXP == 3
+        const long long t2 = CG_T();
+        tr_seg[7] += t2 - tr_prev;
         __syncthreads();
+        const long long t3 = CG_T();
+        tr_top += t1 - t0; tr_mfma += t2 - t1; tr_bar += t3 - t2;
+#else
+        __syncthreads();
+#endif
+    };
+
+    for (int it = 0; it < n_iter; it += 2) {
+        iteration(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < n_iter) iteration(std::integral_constant<int, 1>{}, it + 1);
     }
 
+#if CG_EXP == 3
+    if (blockIdx.x == 7 && blockIdx.y == 0 && blockIdx.z == 0 && lane == 0) {
+        g_trace[wave][0] = tr_top; g_trace[wave][1] = tr_mfma; g_trace[wave][2] = tr_bar;
+        g_trace[wave][3] = CG_T() - tr_begin; g_trace[wave][4] = n_iter;
+        for (int q = 0; q < 8; ++q) g_trace[wave][8 + q] = tr_seg[q];
+    }
+#endif
     // Epilogue.  Accumulator register r of lane (h, li) holds C row 8*(r/4) + 4*h + r%4,
     // column li of its 32x32 sub-tile.
     float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
@@ -409,6 +573,13 @@ int igemm_launch(const IgemmProblem &p, hipStream_t stream)
     return CG_EUNSUPPORTED;
 }
 
+#if CG_EXP == 3
+extern "C" int cg_debug_read_trace(long long *host)
+{
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(long long) * 64) == hipSuccess ? 0 : -4;
+}
+#endif
+
 // ---- split-K: more blocks for problems whose C has few tiles ---------------------------------
 
 namespace {
@@ -452,6 +623,9 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
 SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups, int a_mode)
 {
     SplitPlan pl{1, K, 0};
+#if CG_EXP
+    if (getenv("CG_NO_SPLIT")) return pl;
+#endif
     const uint32_t mt = (uint32_t)pick_mt(M, a_mode != LD_RMAJ_S);
     const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
     if (tiles >= 512) return pl;
