@@ -23,7 +23,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 namespace {
 
 #ifndef CG_KT
-#define CG_KT 32
+#define CG_KT 16
 #endif
 constexpr int KT = CG_KT;
 #ifndef CG_SIDE
@@ -234,42 +234,46 @@ template <int R, int NTHR> struct Loader<LD_KMAJ_V4, R, NTHR> {
 }  // namespace
 
 #if CG_EXP == 3
-__device__ long long g_trace[4][16];
+__device__ long long g_trace[8][8];
 #define CG_T() __builtin_readcyclecounter()
 #endif
 
-// K loop, software-pipelined for a single wave.  While the MFMAs of tile `it` run out of LDS
-// buffer it&1, the same wave (a) issues the global loads of tile it+2 into register set it&1 and
-// (b) writes tile it+1, loaded one iteration earlier into the other register set, to LDS buffer
-// (it+1)&1.  One loader step is placed behind each MFMA and pinned there, so the matrix pipe of
-// a SIMD is kept busy by one wave alone and a global load has a whole K-tile of time to land.
-// Tiles past the end of the K range are loaded as all-padding (offset 0, stored as zeros) and
-// never consumed, which keeps the loop body free of conditions.
+// Wave-specialised K loop.  On gfx950 vector-ALU instructions of a wave do not overlap with an
+// MFMA of the SAME wave (measured: MFMA + N v_add costs 64 + 12 + 4N cycles), but an MFMA-only
+// wave runs at the full 64 cycles per v_mfma_f32_32x32x2_f32 while ANOTHER wave on its SIMD issues
+// vector-ALU, LDS and memory instructions.  So a block is 8 waves, two per SIMD:
+//   waves 0-3, consumers: LDS fragment reads and MFMAs only, each owns TM x TN 32x32 tiles;
+//   waves 4-7, producers: all address arithmetic, global loads and LDS stores of the block's
+//                         A and B tiles (the loaders above run on these 256 threads).
+// LDS holds a ring of three K-tiles.  In iteration `it` the consumers multiply tile it (and
+// prefetch the first fragments of tile it+1, complete since the previous barrier) while the
+// producers store tile it+2, loaded one iteration earlier into the other register set, and issue
+// the global loads of tile it+3.  One s_barrier per iteration; nobody waits for memory unless a
+// load takes longer than a whole iteration.  Tiles past the end of the K range are produced as
+// all padding (offset 0, stored as zeros) and never multiplied, so the loops carry no conditions.
 template <int WM, int WN, int TM, int TN, int AMODE, int BMODE>
-__global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p)
+__global__ __launch_bounds__(512) void igemm_kernel(const IgemmProblem p)
 {
-    constexpr int NTHR = WM * WN * 64;
+    static_assert(WM * WN == 4, "four consumer waves");
+    constexpr int NPROD = 256;
     constexpr int MT = WM * TM * 32, NT = WN * TN * 32;
-    using LA = Loader<AMODE, MT, NTHR>;
-    using LB = Loader<BMODE, NT, NTHR>;
+    constexpr int NKS = KT / 8;                       // 8-wide k-steps per K-tile
+    constexpr int NST = 3;                            // LDS ring depth
+    using LA = Loader<AMODE, MT, NPROD>;
+    using LB = Loader<BMODE, NT, NPROD>;
     constexpr int CA = LA::CNT, CB = LB::CNT;
-    constexpr int NM = (KT / 2) * TM * TN;            // MFMAs per K-tile and wave
-    // loader steps per K-tile, in issue order: B tables, A tables, CB + CA global loads, 4 stages of the k-info of tile it+3, CA + CB LDS stores
-    constexpr int J_TB = 0, J_TA = 1, J_BI = 2, J_AI = J_BI + CB, J_K = J_AI + CA, J_AS = J_K + 4,
-                  J_BS = J_AS + CA, NI = J_BS + CB;
 
-    __shared__ __attribute__((aligned(16))) float sA[2][LA::SZ];
-    __shared__ __attribute__((aligned(16))) float sB[2][LB::SZ];
-    __shared__ int4 kA[3][KT];
-    __shared__ int4 kB[3][KT];
-    __shared__ int4 rA[LA::RTAB];
-    __shared__ int4 rB[LB::RTAB];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *sA = reinterpret_cast<float *>(smem);                 // [NST][LA::SZ]
+    float *sB = sA + NST * LA::SZ;                               // [NST][LB::SZ]
+    int4 *kA = reinterpret_cast<int4 *>(sB + NST * LB::SZ);      // [4][KT]  k-info ring of operand A
+    int4 *kB = kA + 4 * KT;                                      // [4][KT]
+    int4 *rA = kB + 4 * KT;                                      // [LA::RTAB]
+    int4 *rB = rA + LA::RTAB;                                    // [LB::RTAB]
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: lives in a scalar register
-    const int wm = wave / WN, wn = wave % WN;
-    const int h = lane >> 5, li = lane & 31;
 
     const uint32_t m0 = blockIdx.y * MT, n0 = blockIdx.x * NT;
     const uint32_t g = blockIdx.z / p.splits, sp = blockIdx.z % p.splits;
@@ -277,51 +281,114 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
     const uint32_t kend = min(p.K, kbeg + p.k_per_split);
     const int n_iter = (int)((kend - kbeg + KT - 1) / KT);
 
-    const float *a_base = p.A.ptr + (int64_t)g * p.A.gstride;
-    const float *b_base = p.B.ptr + (int64_t)g * p.B.gstride;
-    const uint32_t a_limA = p.A.limA, a_limB = p.A.limB, b_limA = p.B.limA, b_limB = p.B.limB;
+    if (wave >= 4) {
+        // ------------------------------- producers -------------------------------------------
+        const int tp = t - NPROD;
+        const int pw = wave - 4;
+        const float *a_base = p.A.ptr + (int64_t)g * p.A.gstride;
+        const float *b_base = p.B.ptr + (int64_t)g * p.B.gstride;
+        const uint32_t a_limA = p.A.limA, a_limB = p.A.limB, b_limA = p.B.limA, b_limB = p.B.limB;
+        LA la;
+        LB lb;
+        la.init(p.A, m0, p.M, tp, rA);
+        lb.init(p.B, n0, p.N, tp, rB);
 
-    LA la;
-    LB lb;
-    la.init(p.A, m0, p.M, t, rA);
-    lb.init(p.B, n0, p.N, t, rB);
-
-    // k-info of K-tile `tile` goes to table slot tile % 3.  Wave 0 produces operand A's entries,
-    // wave 1 operand B's; the choice is wave-uniform, so the selected map constants are scalar
-    // values (never a pointer into the argument block, which would put a memory wait into the
-    // K loop).  kinfo_stage<0..3> is the same computation cut into four short pieces, each of
-    // which fits behind one MFMA.
-    const bool kw0 = wave == 0;
+        // k-info of K-tile `tile` goes to ring slot tile & 3.  Producer wave 0 makes operand A's
+        // entries, producer wave 1 operand B's; the choice is wave-uniform, so the selected map
+        // constants are scalar values (never a pointer into the argument block, which would put
+        // a memory wait into the loop).
+        const bool kw0 = pw == 0;
 #define CG_KSEL(f) (kw0 ? p.A.k.f : p.B.k.f)
-    const FastDiv kd1{CG_KSEL(d1.d), CG_KSEL(d1.mul), CG_KSEL(d1.sh)}, kd2{CG_KSEL(d2.d), CG_KSEL(d2.mul), CG_KSEL(d2.sh)};
-    const int32_t ks1 = CG_KSEL(s1), ks2 = CG_KSEL(s2), ks3 = CG_KSEL(s3), ko0 = CG_KSEL(o0);
-    const int32_t ksa = CG_KSEL(sa), ka0 = CG_KSEL(a0), ksb = CG_KSEL(sb), kb0 = CG_KSEL(b0);
+        const FastDiv kd1{CG_KSEL(d1.d), CG_KSEL(d1.mul), CG_KSEL(d1.sh)}, kd2{CG_KSEL(d2.d), CG_KSEL(d2.mul), CG_KSEL(d2.sh)};
+        const int32_t ks1 = CG_KSEL(s1), ks2 = CG_KSEL(s2), ks3 = CG_KSEL(s3), ko0 = CG_KSEL(o0);
+        const int32_t ksa = CG_KSEL(sa), ka0 = CG_KSEL(a0), ksb = CG_KSEL(sb), kb0 = CG_KSEL(b0);
 #undef CG_KSEL
-    int4 (*const ktab_mine)[KT] = kw0 ? kA : kB;
-    uint32_t kq_k = 0, kq_q1 = 0, kq_r1 = 0, kq_q2 = 0, kq_r2 = 0;
-    auto kinfo_stage = [&](auto SC, int tile) {
-        constexpr int S = decltype(SC)::value;
-        if (wave < 2) {
-            if constexpr (S == 0) {
-                kq_k = kbeg + (uint32_t)tile * KT + (uint32_t)(lane & (KT - 1));
-                kq_q1 = fdiv(kq_k, kd1);
-            } else if constexpr (S == 1) {
-                kq_r1 = kq_k - kq_q1 * kd1.d;
-                kq_q2 = fdiv(kq_r1, kd2);
-            } else if constexpr (S == 2) {
-                kq_r2 = kq_r1 - kq_q2 * kd2.d;
-            } else {
-                const bool ok = kq_k < kend;
-                const int32_t off = (int32_t)kq_q1 * ks1 + (int32_t)kq_q2 * ks2 + (int32_t)kq_r2 * ks3 + ko0;
-                const int32_t a = (int32_t)kq_q2 * ksa + ka0, b = (int32_t)kq_r2 * ksb + kb0;
-                if (lane < KT) ktab_mine[tile % 3][lane] = make_int4(ok ? off : 0, ok ? a : kInvalidA, ok ? b : 0, 0);
+        int4 *const ktab_mine = kw0 ? kA : kB;
+        auto put_kinfo = [&](int tile) {
+            if (pw < 2 && lane < KT) {
+                const uint32_t k = kbeg + (uint32_t)tile * KT + (uint32_t)lane;
+                const uint32_t q1 = fdiv(k, kd1), r1 = k - q1 * kd1.d;
+                const uint32_t q2 = fdiv(r1, kd2), r2 = r1 - q2 * kd2.d;
+                const bool ok = k < kend;
+                const int32_t off = (int32_t)q1 * ks1 + (int32_t)q2 * ks2 + (int32_t)r2 * ks3 + ko0;
+                const int32_t a = (int32_t)q2 * ksa + ka0, b = (int32_t)r2 * ksb + kb0;
+                ktab_mine[(tile & 3) * KT + lane] = make_int4(ok ? off : 0, ok ? a : kInvalidA, ok ? b : 0, 0);
+            }
+        };
+        auto issue_tile = [&](auto SETC, int tile) {
+            constexpr int SET = decltype(SETC)::value;
+            const int4 *ka = kA + (tile & 3) * KT, *kb = kB + (tile & 3) * KT;
+            la.tables(ka, rA);
+            lb.tables(kb, rB);
+            static_for<0, CB>([&](auto I) { lb.template issue<decltype(I)::value, SET>(b_base, b_limA, b_limB, kb, rB); });
+            static_for<0, CA>([&](auto I) { la.template issue<decltype(I)::value, SET>(a_base, a_limA, a_limB, ka, rA); });
+        };
+        auto store_tile = [&](auto SETC, int tile) {
+            constexpr int SET = decltype(SETC)::value;
+            float *a_d = sA + (tile % NST) * LA::SZ, *b_d = sB + (tile % NST) * LB::SZ;
+            static_for<0, CA>([&](auto I) { la.template store<decltype(I)::value, SET>(a_d); });
+            static_for<0, CB>([&](auto I) { lb.template store<decltype(I)::value, SET>(b_d); });
+        };
+        const std::integral_constant<int, 0> S0{};
+        const std::integral_constant<int, 1> S1{};
+
+        // prologue: tiles 0 and 1 in LDS, tile 2 in flight in register set 0, k-info up to tile 3
+        put_kinfo(0); put_kinfo(1); put_kinfo(2); put_kinfo(3);
+        __syncthreads();
+        issue_tile(S0, 0);
+        issue_tile(S1, 1);
+        store_tile(S0, 0);
+        store_tile(S1, 1);
+        issue_tile(S0, 2);
+        __syncthreads();
+        // iteration it: issue tile it+3 into set (it+1)&1, store tile it+2 from set it&1
+#if CG_EXP == 3
+        long long tw = 0, tb = 0, ti = 0;
+        const long long tbeg = CG_T();
+#define CG_TR_A() const long long q0 = CG_T();
+#define CG_TR_I() const long long qi = CG_T();
+#define CG_TR_B() const long long q1 = CG_T();
+#define CG_TR_C() { const long long q2 = CG_T(); ti += qi - q0; tw += q1 - qi; tb += q2 - q1; }
+#else
+#define CG_TR_A()
+#define CG_TR_I()
+#define CG_TR_B()
+#define CG_TR_C()
+#endif
+        for (int it = 0; it < n_iter; it += 2) {
+            {
+                CG_TR_A()
+                issue_tile(S1, it + 3);
+                put_kinfo(it + 4);
+                CG_TR_I()
+                store_tile(S0, it + 2);
+                CG_TR_B()
+                __syncthreads();
+                CG_TR_C()
+            }
+            if (it + 1 < n_iter) {
+                CG_TR_A()
+                issue_tile(S0, it + 4);
+                put_kinfo(it + 5);
+                CG_TR_I()
+                store_tile(S1, it + 3);
+                CG_TR_B()
+                __syncthreads();
+                CG_TR_C()
             }
         }
-    };
-    auto put_kinfo = [&](int tile) {
-        static_for<0, 4>([&](auto SC) { kinfo_stage(SC, tile); });
-    };
+#if CG_EXP == 3
+        if (blockIdx.x == 7 && blockIdx.y == 0 && blockIdx.z == 0 && lane == 0) {
+            g_trace[wave][0] = ti; g_trace[wave][1] = tw; g_trace[wave][2] = tb; g_trace[wave][3] = CG_T() - tbeg;
+            g_trace[wave][4] = n_iter;
+        }
+#endif
+        return;
+    }
 
+    // ----------------------------------- consumers -----------------------------------------------
+    const int wm = wave / WN, wn = wave % WN;
+    const int h = lane >> 5, li = lane & 31;
     v16f acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -330,107 +397,58 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // prologue: tile 0 -> LDS buffer 0, tile 1 -> register set 1, k-info of tile 2 ready
-    put_kinfo(0);
-    put_kinfo(1);
-    put_kinfo(2);
-    __syncthreads();
-    la.tables(kA[0], rA);
-    lb.tables(kB[0], rB);
-    static_for<0, CA>([&](auto I) { la.template issue<decltype(I)::value, 0>(a_base, a_limA, a_limB, kA[0], rA); });
-    static_for<0, CB>([&](auto I) { lb.template issue<decltype(I)::value, 0>(b_base, b_limA, b_limB, kB[0], rB); });
-    static_for<0, CA>([&](auto I) { la.template store<decltype(I)::value, 0>(sA[0]); });
-    static_for<0, CB>([&](auto I) { lb.template store<decltype(I)::value, 0>(sB[0]); });
-    la.tables(kA[1], rA);
-    lb.tables(kB[1], rB);
-    static_for<0, CA>([&](auto I) { la.template issue<decltype(I)::value, 1>(a_base, a_limA, a_limB, kA[1], rA); });
-    static_for<0, CB>([&](auto I) { lb.template issue<decltype(I)::value, 1>(b_base, b_limA, b_limB, kB[1], rB); });
-    __syncthreads();
-
-#if CG_EXP == 3
-    long long tr_top = 0, tr_mfma = 0, tr_bar = 0, tr_seg[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    long long tr_prev = 0;
-    const long long tr_begin = CG_T();
-#endif
-    auto iteration = [&](auto PARC, int it) {
-        constexpr int PAR = decltype(PARC)::value;    // it & 1, known at compile time
-#if CG_EXP == 3
-        const long long t0 = CG_T();
-#endif
-        const float *a_s = sA[PAR];
-        const float *b_s = sB[PAR];
-        float *a_d = sA[PAR ^ 1];
-        float *b_d = sB[PAR ^ 1];
-        float af[2][TM][4], bf[2][TN][4];      // fragments of k-step ks live in ring slot ks & 1
-        // only the first k-step's fragments are fetched before the first MFMA: right after the
-        // barrier all four waves hit the LDS at once, so everything else is spread over the slots
+    float af[2][TM][4], bf[2][TN][4];      // fragments of k-step ks live in ring slot ks & 1
+    auto fetch = [&](auto SLOTC, int tile, int ks) {
+        constexpr int SL = decltype(SLOTC)::value;
+        const float *a_s = sA + (tile % NST) * LA::SZ, *b_s = sB + (tile % NST) * LB::SZ;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, 0, h, af[0][i]);
+        for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks * 8, h, af[SL][i]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, 0, h, bf[0][j]);
-        const int slot2 = (it + 2) % 3;
-        CG_SCHED_FENCE();
+        for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, ks * 8, h, bf[SL][j]);
+    };
+    __syncthreads();     // producers: k-info ready
+    __syncthreads();     // producers: tiles 0 and 1 stored
+    fetch(std::integral_constant<int, 0>{}, 0, 0);
 #if CG_EXP == 3
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        const long long t1 = CG_T();
-        tr_prev = t1;
-        CG_SCHED_FENCE();
+    long long tw = 0, tb = 0;
+    const long long tbeg = CG_T();
 #endif
-        static_for<0, NM>([&](auto MC) {
-            constexpr int mi = decltype(MC)::value;
-            constexpr int ks = mi / (4 * TM * TN), s = (mi / (TM * TN)) % 4, i = (mi / TN) % TM, j = mi % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks & 1][i][s], bf[ks & 1][j][s], acc[i][j], 0, 0, 0);
+    for (int it = 0; it < n_iter; ++it) {
 #if CG_EXP == 3
-            if constexpr (mi > 0 && mi % (NM / 8) == 0) {
-                const long long tn = CG_T();
-                tr_seg[mi / (NM / 8) - 1] += tn - tr_prev;
-                tr_prev = tn;
-            }
+        const long long q0 = CG_T();
 #endif
-            // the next k-step's fragments are fetched while this k-step's MFMAs run
-            if constexpr (mi % (4 * TM * TN) == 0 && ks + 1 < KT / 8) {
+        static_for<0, NKS>([&](auto KS) {
+            constexpr int ks = decltype(KS)::value;
+            // next fragments first: the LDS reads run under this k-step's MFMAs.  The last k-step
+            // fetches from tile it+1, which has been complete since the previous barrier.
+            if constexpr (ks + 1 < NKS) fetch(std::integral_constant<int, (ks + 1) & 1>{}, it, ks + 1);
+            else fetch(std::integral_constant<int, 0>{}, it + 1, 0);
+            CG_SCHED_FENCE();
 #pragma unroll
-                for (int i2 = 0; i2 < TM; ++i2) LA::frag(a_s, (wm * TM + i2) * 32 + li, (ks + 1) * 8, h, af[(ks + 1) & 1][i2]);
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int j2 = 0; j2 < TN; ++j2) LB::frag(b_s, (wn * TN + j2) * 32 + li, (ks + 1) * 8, h, bf[(ks + 1) & 1][j2]);
-            }
-            // loader steps lo..hi-1 ride behind this MFMA
-            constexpr int lo = (mi * NI + NM - 1) / NM, hi = ((mi + 1) * NI + NM - 1) / NM;
-            static_for<lo, hi>([&](auto JC) {
-                constexpr int jj = decltype(JC)::value;
-                if constexpr (jj == J_TB) { if constexpr (CG_SIDE & 8) lb.tables(kB[slot2], rB); }
-                else if constexpr (jj == J_TA) { if constexpr (CG_SIDE & 8) la.tables(kA[slot2], rA); }
-                else if constexpr (jj < J_AI) { if constexpr (CG_SIDE & 1) lb.template issue<jj - J_BI, PAR>(b_base, b_limA, b_limB, kB[slot2], rB); }
-                else if constexpr (jj < J_K) { if constexpr (CG_SIDE & 1) la.template issue<jj - J_AI, PAR>(a_base, a_limA, a_limB, kA[slot2], rA); }
-                else if constexpr (jj < J_AS) { if constexpr (CG_SIDE & 4) kinfo_stage(std::integral_constant<int, jj - J_K>{}, it + 3); }
-                else if constexpr (jj < J_BS) { if constexpr (CG_SIDE & 2) la.template store<jj - J_AS, PAR ^ 1>(a_d); }
-                else { if constexpr (CG_SIDE & 2) lb.template store<jj - J_BS, PAR ^ 1>(b_d); }
-            });
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks & 1][i][s], bf[ks & 1][j][s], acc[i][j], 0, 0, 0);
             CG_SCHED_FENCE();
         });
 #if CG_EXP == 3
-        const long long t2 = CG_T();
-        tr_seg[7] += t2 - tr_prev;
+        const long long q1 = CG_T();
         __syncthreads();
-        const long long t3 = CG_T();
-        tr_top += t1 - t0; tr_mfma += t2 - t1; tr_bar += t3 - t2;
+        const long long q2 = CG_T();
+        tw += q1 - q0; tb += q2 - q1;
 #else
         __syncthreads();
 #endif
-    };
-
-    for (int it = 0; it < n_iter; it += 2) {
-        iteration(std::integral_constant<int, 0>{}, it);
-        if (it + 1 < n_iter) iteration(std::integral_constant<int, 1>{}, it + 1);
     }
-
 #if CG_EXP == 3
     if (blockIdx.x == 7 && blockIdx.y == 0 && blockIdx.z == 0 && lane == 0) {
-        g_trace[wave][0] = tr_top; g_trace[wave][1] = tr_mfma; g_trace[wave][2] = tr_bar;
-        g_trace[wave][3] = CG_T() - tr_begin; g_trace[wave][4] = n_iter;
-        for (int q = 0; q < 8; ++q) g_trace[wave][8 + q] = tr_seg[q];
+        g_trace[wave][0] = 0; g_trace[wave][1] = tw; g_trace[wave][2] = tb; g_trace[wave][3] = CG_T() - tbeg;
+        g_trace[wave][4] = n_iter;
     }
 #endif
+
     // Epilogue.  Accumulator register r of lane (h, li) holds C row 8*(r/4) + 4*h + r%4,
     // column li of its 32x32 sub-tile.
     float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
@@ -458,6 +476,14 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_kernel(const IgemmProblem p
     }
 }
 
+// LDS bytes of one block of the kernel instance (ring of three K-tiles + index tables)
+template <int WM, int WN, int TM, int TN, int AMODE, int BMODE> constexpr size_t igemm_lds_bytes()
+{
+    using LA = Loader<AMODE, WM * TM * 32, 256>;
+    using LB = Loader<BMODE, WN * TN * 32, 256>;
+    return 3 * (LA::SZ + LB::SZ) * sizeof(float) + (8 * KT + LA::RTAB + LB::RTAB) * sizeof(int4);
+}
+
 namespace {
 
 template <int WM, int WN, int TM, int TN, int AMODE, int BMODE>
@@ -472,7 +498,15 @@ int launch_cfg(const IgemmProblem &p, hipStream_t stream)
         snprintf(name, sizeof name, "igemm_kernel<%d,%d,%d,%d,%d,%d>", WM, WN, TM, TN, AMODE, BMODE);
         rec = prof_begin(name, 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
-    hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, AMODE, BMODE>), grid, dim3(WM * WN * 64), 0, stream, p);
+    constexpr size_t lds = igemm_lds_bytes<WM, WN, TM, TN, AMODE, BMODE>();
+    static_assert(lds <= 160 * 1024, "tile does not fit the LDS of a compute unit");
+    static bool attr_set = false;      // raising the dynamic-LDS limit is a per-kernel, one-time host call
+    if (!attr_set) {
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_kernel<WM, WN, TM, TN, AMODE, BMODE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, AMODE, BMODE>), grid, dim3(512), lds, stream, p);
     prof_end(rec, stream);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
@@ -572,6 +606,7 @@ int igemm_launch(const IgemmProblem &p, hipStream_t stream)
     if (am == LD_RMAJ_S && bm == LD_RMAJ_S) return launch_modes<LD_RMAJ_S, LD_RMAJ_S>(p, mt, stream);
     return CG_EUNSUPPORTED;
 }
+
 
 #if CG_EXP == 3
 extern "C" int cg_debug_read_trace(long long *host)
