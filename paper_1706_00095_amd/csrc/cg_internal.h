@@ -59,8 +59,6 @@ struct IndexMap {
 
 struct Info { int32_t off, a, b; };
 
-constexpr int32_t kInvalidA = 0x20000000;   // pushes a_row + a_k far outside any limA
-
 FastDiv make_fastdiv(uint32_t d);
 IndexMap linear_map(uint32_t count, int32_t stride);
 // idx = q*d + r  ->  off = q*sq + r*sr
@@ -71,10 +69,10 @@ __host__ __device__ inline uint32_t fdiv(uint32_t n, const FastDiv &f)
     return (uint32_t)(((uint64_t)n * f.mul) >> f.sh);
 }
 
-__host__ __device__ inline Info map_info(const IndexMap &m, uint32_t idx, uint32_t limit)
+// offset and window coordinates of index idx (any idx < 2^31; the caller checks the range)
+__host__ __device__ inline Info map_info(const IndexMap &m, uint32_t idx)
 {
     Info r;
-    if (idx >= limit) { r.off = 0; r.a = kInvalidA; r.b = 0; return r; }
     const uint32_t q1 = fdiv(idx, m.d1), r1 = idx - q1 * m.d1.d;
     const uint32_t q2 = fdiv(r1, m.d2), r2 = r1 - q2 * m.d2.d;
     r.off = (int32_t)q1 * m.s1 + (int32_t)q2 * m.s2 + (int32_t)r2 * m.s3 + m.o0;
@@ -88,16 +86,18 @@ struct Operand {
     IndexMap row, k;
     uint32_t limA, limB;
     int64_t gstride;      // elements between groups
-    int vec4_ok;          // rows and k are unit-stride in k, K % 4 == 0, 16-byte aligned
+    uint64_t elems;       // floats behind ptr (all groups): the bound of the kernel's buffer descriptor
+    int lanes_k;          // which index runs along the 64 lanes of one load, i.e. the direction that is
+                          // (nearly) contiguous in memory: 1 = the reduction index, 0 = the row index
+    int check;            // 1 = the (a, b) window test is needed (zero padding); 0 = always valid
+    int64_t shift;        // set by igemm_launch: elements moved from the maps' offsets into the base
+                          // pointer so that both per-index offsets are non-negative
 };
-
-enum { LD_KMAJ_V4 = 0, LD_KMAJ_S = 1, LD_RMAJ_S = 2 };   // how an operand tile is fetched / laid out
 
 // C[m][n] = sum_k A(m,k) * B(n,k)   (+ bias), for `groups` independent problems, the K range
 // optionally cut into `splits` slices whose partial results go to consecutive output planes.
 struct IgemmProblem {
     Operand A, B;
-    int a_mode, b_mode;
     float *c_ptr;
     int32_t c_row_stride;     // C row m lives at m * c_row_stride (+ column offset)
     IndexMap c_col;           // column n -> offset
@@ -108,18 +108,19 @@ struct IgemmProblem {
     uint32_t M, N, K;
     uint32_t groups, splits, k_per_split;
     int accumulate;           // C += result instead of C = result
+    int relu;                 // C = max(result, 0) after bias (forward passes followed by a rectifier)
 };
 
 // Validates the problem against what the kernels assume and launches it.
 int igemm_launch(const IgemmProblem &p, hipStream_t stream);
 // Host-side evaluation of one operand element: offset and validity (for tests of the maps).
-void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, uint32_t K, int64_t *off, int *valid);
+void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, int64_t *off, int *valid);
 
 // Split-K front end: when C has too few tiles to fill the chip, the K range is cut into slices
 // whose partial results go to `ws` and are then added in slice order (so results do not depend
 // on scheduling).  igemm_ws_bytes() says how much workspace igemm_run() needs for a problem.
 struct SplitPlan { uint32_t splits, k_per_split; size_t ws_bytes; };
-SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups, int a_mode);
+SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups);
 size_t igemm_ws_bytes(const IgemmProblem &p);
 int igemm_run(const IgemmProblem &p, void *ws, size_t ws_bytes, hipStream_t stream);
 // db[m] = sum over n and pixels of dy[n][m][pix]; two passes over `ws`, fixed order

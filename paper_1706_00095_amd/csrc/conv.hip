@@ -43,21 +43,6 @@ IndexMap tap_map(const cg_conv_desc &d, int Cg)
     return m;
 }
 
-// wt[g][c][ml][kh][kw] = w[g*Mg + ml][c][kh][kw]
-__global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__restrict__ w, float *__restrict__ wt,
-                                                                int G, int Mg, int Cg, int KK)
-{
-    const size_t total = (size_t)G * Mg * Cg * KK;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const int kk = (int)(i % KK);
-        size_t r = i / KK;
-        const int ml = (int)(r % Mg); r /= Mg;
-        const int c = (int)(r % Cg);
-        const int g = (int)(r / Cg);
-        wt[i] = w[(((size_t)g * Mg + ml) * Cg + c) * KK + kk];
-    }
-}
-
 // General-stride backward-data, gather form, one thread per dx element.  Only the taps with
 // (ih + p - kh) divisible by the stride contribute.
 __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_desc d, int OH, int OW,
@@ -126,14 +111,16 @@ static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const flo
     p.A.k = linear_map(Kg, 1);
     p.A.limA = p.A.limB = 1;
     p.A.gstride = (int64_t)Mg * Kg;
-    p.A.vec4_ok = (Kg % 4 == 0);
-    p.a_mode = p.A.vec4_ok ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.A.elems = (uint64_t)d.M * Kg;
+    p.A.lanes_k = 1;
     p.B.ptr = x;
     p.B.row = window_origin_map(d, OH, OW);
     p.B.k = tap_map(d, Cg);
     p.B.limA = d.H; p.B.limB = d.W;
     p.B.gstride = (int64_t)Cg * d.H * d.W;
-    p.b_mode = LD_RMAJ_S;
+    p.B.elems = (uint64_t)d.N * d.C * d.H * d.W;
+    p.B.lanes_k = 0;
+    p.B.check = (d.pad_h || d.pad_w) ? 1 : 0;
     p.c_ptr = y;
     p.c_row_stride = P;
     p.c_col = split_map((uint32_t)d.N * P, P, d.M * P, 1);
@@ -154,19 +141,20 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
     return igemm_run(fwd_problem(d, OH, OW, x, w, bias, y), ws, ws_bytes, stream);
 }
 
-static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *wt,
+static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *w,
                                      float *dx, int accumulate)
 {
     const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW, P = OH * OW;
     const int Kp = Mg * KK;
     IgemmProblem p{};
-    p.A.ptr = wt;
-    p.A.row = linear_map(Cg, Kp);
-    p.A.k = linear_map(Kp, 1);
+    // the filters read "transposed": row c, reduction index (ml, kh, kw) -> w[g*Mg + ml][c][kh][kw]
+    p.A.ptr = w;
+    p.A.row = linear_map(Cg, KK);
+    p.A.k = split_map((uint32_t)Kp, (uint32_t)KK, Cg * KK, 1);
     p.A.limA = p.A.limB = 1;
-    p.A.gstride = (int64_t)Cg * Kp;
-    p.A.vec4_ok = (Kp % 4 == 0);
-    p.a_mode = p.A.vec4_ok ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.A.gstride = (int64_t)Mg * Cg * KK;
+    p.A.elems = (uint64_t)d.M * Cg * KK;
+    p.A.lanes_k = 1;
     // dy seen from an input pixel (n, ih, iw): origin (ih + p, iw + p), taps subtract (kh, kw)
     p.B.ptr = dy;
     IndexMap pix{};
@@ -184,7 +172,9 @@ static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, cons
     p.B.row = pix; p.B.k = tap;
     p.B.limA = OH; p.B.limB = OW;
     p.B.gstride = (int64_t)Mg * P;
-    p.b_mode = LD_RMAJ_S;
+    p.B.elems = (uint64_t)d.N * d.M * P;
+    p.B.lanes_k = 0;
+    p.B.check = (KK > 1 || d.pad_h || d.pad_w) ? 1 : 0;
     const int HW = d.H * d.W;
     p.c_ptr = dx;
     p.c_row_stride = HW;
@@ -203,7 +193,6 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
-    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW;
     if (d.stride_h != 1 || d.stride_w != 1) {
         const size_t total = (size_t)d.N * d.C * d.H * d.W;
         const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
@@ -212,18 +201,7 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         CG_HIP_TRY(hipGetLastError());
         return CG_OK;
     }
-    const size_t wt_bytes = round256((size_t)d.M * Cg * KK * sizeof(float));
-    if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
-    if (!aligned16(ws)) return CG_EINVAL;
-    float *wt = static_cast<float *>(ws);
-    {
-        const size_t total = (size_t)d.M * Cg * KK;
-        const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
-        hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
-        CG_HIP_TRY(hipGetLastError());
-    }
-    return igemm_run(bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate), static_cast<char *>(ws) + wt_bytes,
-                     ws_bytes - wt_bytes, stream);
+    return igemm_run(bwd_data_problem(d, OH, OW, dy, w, dx, accumulate), ws, ws_bytes, stream);
 }
 
 static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *dy,
@@ -236,13 +214,16 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
     p.A.k = split_map((uint32_t)d.N * P, P, d.M * P, 1);
     p.A.limA = p.A.limB = 1;
     p.A.gstride = (int64_t)Mg * P;
-    p.a_mode = LD_KMAJ_S;
+    p.A.elems = (uint64_t)d.N * d.M * P;
+    p.A.lanes_k = 1;
     p.B.ptr = x;
     p.B.row = tap_map(d, Cg);
     p.B.k = window_origin_map(d, OH, OW);
     p.B.limA = d.H; p.B.limB = d.W;
     p.B.gstride = (int64_t)Cg * d.H * d.W;
-    p.b_mode = LD_KMAJ_S;
+    p.B.elems = (uint64_t)d.N * d.C * d.H * d.W;
+    p.B.lanes_k = 1;
+    p.B.check = (d.pad_h || d.pad_w) ? 1 : 0;
     p.c_ptr = dw;
     p.c_row_stride = Kg;
     p.c_col = linear_map(Kg, 1);
@@ -279,8 +260,7 @@ size_t conv_ws_bytes(const cg_conv_desc &d, int pass)
     if (pass == CG_PASS_FWD) return igemm_ws_bytes(fwd_problem(d, OH, OW, nullptr, nullptr, nullptr, nullptr));
     if (pass == CG_PASS_BWD_DATA) {
         if (d.stride_h != 1 || d.stride_w != 1) return 0;
-        return round256((size_t)d.M * (d.C / d.groups) * d.KH * d.KW * sizeof(float)) +
-               igemm_ws_bytes(bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0));
+        return igemm_ws_bytes(bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0));
     }
     if (pass == CG_PASS_BWD_WEIGHT)
         return round256(igemm_ws_bytes(bwd_weight_problem(d, OH, OW, nullptr, nullptr, nullptr))) +
@@ -294,10 +274,10 @@ static IgemmProblem fc_fwd_problem(int B, int IN, int OUT, const float *x, const
                                    float *y)
 {
     IgemmProblem p{};
-    const bool v4 = IN % 4 == 0;
-    p.A.ptr = x; p.A.row = linear_map(B, IN); p.A.k = linear_map(IN, 1); p.A.limA = p.A.limB = 1; p.A.vec4_ok = v4;
-    p.B.ptr = W; p.B.row = linear_map(OUT, IN); p.B.k = linear_map(IN, 1); p.B.limA = p.B.limB = 1; p.B.vec4_ok = v4;
-    p.a_mode = p.b_mode = v4 ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.A.ptr = x; p.A.row = linear_map(B, IN); p.A.k = linear_map(IN, 1); p.A.limA = p.A.limB = 1;
+    p.A.elems = (uint64_t)B * IN; p.A.lanes_k = 1;
+    p.B.ptr = W; p.B.row = linear_map(OUT, IN); p.B.k = linear_map(IN, 1); p.B.limA = p.B.limB = 1;
+    p.B.elems = (uint64_t)OUT * IN; p.B.lanes_k = 1;
     p.c_ptr = y; p.c_row_stride = OUT; p.c_col = linear_map(OUT, 1);
     p.bias = bias; p.bias_mode = bias ? 2 : 0;
     p.M = B; p.N = OUT; p.K = IN;
@@ -310,11 +290,10 @@ static IgemmProblem fc_bwd_data_problem(int B, int IN, int OUT, const float *dy,
                                         int accumulate)
 {
     IgemmProblem p{};
-    const bool v4 = OUT % 4 == 0;
-    p.A.ptr = dy; p.A.row = linear_map(B, OUT); p.A.k = linear_map(OUT, 1); p.A.limA = p.A.limB = 1; p.A.vec4_ok = v4;
-    p.a_mode = v4 ? LD_KMAJ_V4 : LD_KMAJ_S;
+    p.A.ptr = dy; p.A.row = linear_map(B, OUT); p.A.k = linear_map(OUT, 1); p.A.limA = p.A.limB = 1;
+    p.A.elems = (uint64_t)B * OUT; p.A.lanes_k = 1;
     p.B.ptr = W; p.B.row = linear_map(IN, 1); p.B.k = linear_map(OUT, IN); p.B.limA = p.B.limB = 1;
-    p.b_mode = LD_RMAJ_S;
+    p.B.elems = (uint64_t)OUT * IN; p.B.lanes_k = 0;
     p.c_ptr = dx; p.c_row_stride = IN; p.c_col = linear_map(IN, 1);
     p.M = B; p.N = IN; p.K = OUT;
     p.groups = 1; p.splits = 1; p.k_per_split = p.K;
@@ -327,8 +306,9 @@ static IgemmProblem fc_bwd_weight_problem(int B, int IN, int OUT, const float *x
 {
     IgemmProblem p{};
     p.A.ptr = dy; p.A.row = linear_map(OUT, 1); p.A.k = linear_map(B, OUT); p.A.limA = p.A.limB = 1;
+    p.A.elems = (uint64_t)B * OUT; p.A.lanes_k = 0;
     p.B.ptr = x; p.B.row = linear_map(IN, 1); p.B.k = linear_map(B, IN); p.B.limA = p.B.limB = 1;
-    p.a_mode = p.b_mode = LD_RMAJ_S;
+    p.B.elems = (uint64_t)B * IN; p.B.lanes_k = 0;
     p.c_ptr = dW; p.c_row_stride = IN; p.c_col = linear_map(IN, 1);
     p.M = OUT; p.N = IN; p.K = B;
     p.groups = 1; p.splits = 1; p.k_per_split = p.K;
@@ -394,7 +374,7 @@ extern "C" int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operan
     const Operand &op = operand == 0 ? p.A : p.B;
     if (row >= op.row.count || k >= p.K) return CG_EINVAL;
     int64_t off;
-    igemm_host_element(op, row, k, p.K, &off, valid);
+    igemm_host_element(op, row, k, &off, valid);
     *elem_offset = off + (int64_t)group * op.gstride;
     return CG_OK;
 }
