@@ -43,6 +43,22 @@ IndexMap tap_map(const cg_conv_desc &d, int Cg)
     return m;
 }
 
+// wt[g][c][ml][kh][kw] = w[g*Mg + ml][c][kh][kw]: the filters as the row-major matrix that
+// backward-data multiplies with (rows = input channels, reduction index = (ml, kh, kw))
+__global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__restrict__ w, float *__restrict__ wt,
+                                                                int G, int Mg, int Cg, int KK)
+{
+    const size_t total = (size_t)G * Mg * Cg * KK;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int kk = (int)(i % KK);
+        size_t r = i / KK;
+        const int ml = (int)(r % Mg); r /= Mg;
+        const int c = (int)(r % Cg);
+        const int g = (int)(r / Cg);
+        wt[i] = w[(((size_t)g * Mg + ml) * Cg + c) * KK + kk];
+    }
+}
+
 // General-stride backward-data, gather form, one thread per dx element.  Only the taps with
 // (ih + p - kh) divisible by the stride contribute.
 __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_desc d, int OH, int OW,
@@ -141,18 +157,17 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
     return igemm_run(fwd_problem(d, OH, OW, x, w, bias, y), ws, ws_bytes, stream);
 }
 
-static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *w,
+static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *wt,
                                      float *dx, int accumulate)
 {
     const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW, P = OH * OW;
     const int Kp = Mg * KK;
     IgemmProblem p{};
-    // the filters read "transposed": row c, reduction index (ml, kh, kw) -> w[g*Mg + ml][c][kh][kw]
-    p.A.ptr = w;
-    p.A.row = linear_map(Cg, KK);
-    p.A.k = split_map((uint32_t)Kp, (uint32_t)KK, Cg * KK, 1);
+    p.A.ptr = wt;
+    p.A.row = linear_map(Cg, Kp);
+    p.A.k = linear_map(Kp, 1);
     p.A.limA = p.A.limB = 1;
-    p.A.gstride = (int64_t)Mg * Cg * KK;
+    p.A.gstride = (int64_t)Cg * Kp;
     p.A.elems = (uint64_t)d.M * Cg * KK;
     p.A.lanes_k = 1;
     // dy seen from an input pixel (n, ih, iw): origin (ih + p, iw + p), taps subtract (kh, kw)
@@ -201,7 +216,19 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         CG_HIP_TRY(hipGetLastError());
         return CG_OK;
     }
-    return igemm_run(bwd_data_problem(d, OH, OW, dy, w, dx, accumulate), ws, ws_bytes, stream);
+    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW;
+    const size_t wt_bytes = round256((size_t)d.M * Cg * KK * sizeof(float));
+    if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
+    if (!aligned16(ws)) return CG_EINVAL;
+    float *wt = static_cast<float *>(ws);
+    {
+        const size_t total = (size_t)d.M * Cg * KK;
+        const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+        hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
+        CG_HIP_TRY(hipGetLastError());
+    }
+    return igemm_run(bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate), static_cast<char *>(ws) + wt_bytes,
+                     ws_bytes - wt_bytes, stream);
 }
 
 static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *dy,
@@ -260,7 +287,8 @@ size_t conv_ws_bytes(const cg_conv_desc &d, int pass)
     if (pass == CG_PASS_FWD) return igemm_ws_bytes(fwd_problem(d, OH, OW, nullptr, nullptr, nullptr, nullptr));
     if (pass == CG_PASS_BWD_DATA) {
         if (d.stride_h != 1 || d.stride_w != 1) return 0;
-        return igemm_ws_bytes(bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0));
+        return round256((size_t)d.M * (d.C / d.groups) * d.KH * d.KW * sizeof(float)) +
+               igemm_ws_bytes(bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0));
     }
     if (pass == CG_PASS_BWD_WEIGHT)
         return round256(igemm_ws_bytes(bwd_weight_problem(d, OH, OW, nullptr, nullptr, nullptr))) +

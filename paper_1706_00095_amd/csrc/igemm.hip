@@ -27,8 +27,12 @@ typedef uint32_t BufferRsrc __attribute__((ext_vector_type(4)));   // the four d
 
 namespace {
 
+#ifndef CG_EXP
+#define CG_EXP 0
+#endif
 constexpr int KT = 16;                       // reduction indices per LDS stage
 constexpr int NST = 4;                       // LDS stages
+constexpr int NPART = KT / 2;                // MFMA steps per tile = parts the loads of a tile are issued in
 // Offsets that no buffer descriptor of this library covers (descriptors span < 0x7fffff00 bytes).
 // Their sum does not wrap, and either one added to a valid offset (< 2^31) stays out of range.
 constexpr uint32_t OOB_ROW = 0x80000000u, OOB_K = 0x7fffff00u;
@@ -57,7 +61,15 @@ __device__ __forceinline__ void load_to_lds(BufferRsrc rsrc, const float *lds, u
 {
     const uint32_t lds_addr = (uint32_t)(size_t)(const lds_float *)lds;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "memory", "m0");
+}
+// 64 lanes x 16 bytes: lane l's four elements land at lds + 16*l.
+__device__ __forceinline__ void load4_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff, uint32_t soff)
+{
+    const uint32_t lds_addr = (uint32_t)(size_t)(const lds_float *)lds;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff))
                  : "memory", "m0");
 }
 #pragma clang diagnostic pop
@@ -95,23 +107,30 @@ template <int R, bool CHECK> struct RowsLoader {
             ra[c] = q.a; rb[c] = q.b;
         }
     }
-    __device__ __forceinline__ void issue(BufferRsrc rsrc, float *stage, const Operand &op, uint32_t k0,
-                                          uint32_t kend, int wave, int) const
+    // scalar info of the k this wave is loading (set by the part that issues chunk 0 of that k)
+    Info kq;
+    uint32_t ksoff;
+
+    // The loads of one tile are cut into NPART parts so that the K loop can place one part behind
+    // each MFMA step: part P issues loads [P*LPT/NPART, (P+1)*LPT/NPART), load i = (t, chunk).
+    template <int P>
+    __device__ __forceinline__ void issue_part(BufferRsrc rsrc, float *stage, const Operand &op, uint32_t k0,
+                                               uint32_t kend, int wave, int)
     {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int i = P * LPT / NPART; i < (P + 1) * LPT / NPART; ++i) {
+            const int t = i / NCH, c = i % NCH;
             const uint32_t kl = (uint32_t)(4 * wave + t), k = k0 + kl;       // wave-uniform
-            const Info q = map_info(op.k, k);
-            const uint32_t soff = k < kend ? (uint32_t)q.off * 4u : OOB_K;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                uint32_t voff = roff[c];
-                if (CHECK) {
-                    const bool ok = (uint32_t)(ra[c] + q.a) < op.limA && (uint32_t)(rb[c] + q.b) < op.limB;
-                    voff = ok ? voff : OOB_ROW;
-                }
-                load_to_lds(rsrc, stage + kl * RS + c * 64, voff, soff);
+            if (c == 0) {
+                kq = map_info(op.k, k);
+                ksoff = k < kend ? (uint32_t)kq.off * 4u : OOB_K;
             }
+            uint32_t voff = roff[c];
+            if (CHECK) {
+                const bool ok = (uint32_t)(ra[c] + kq.a) < op.limA && (uint32_t)(rb[c] + kq.b) < op.limB;
+                voff = ok ? voff : OOB_ROW;
+            }
+            load_to_lds(rsrc, stage + kl * RS + c * 64, voff, ksoff);
         }
     }
     __device__ __forceinline__ static void frag(const float *stage, int row, int ks, int h, float out[4])
@@ -141,17 +160,23 @@ template <int R, bool CHECK> struct KLoader {
             ra[j] = q.a; rb[j] = q.b;
         }
     }
-    __device__ __forceinline__ void issue(BufferRsrc rsrc, float *stage, const Operand &op, uint32_t k0,
-                                          uint32_t kend, int wave, int lane) const
+    Info kq;              // this lane's k of the tile being loaded (set by part 0)
+    uint32_t koff;
+
+    template <int P>
+    __device__ __forceinline__ void issue_part(BufferRsrc rsrc, float *stage, const Operand &op, uint32_t k0,
+                                               uint32_t kend, int wave, int lane)
     {
-        const uint32_t k = k0 + (uint32_t)(lane & 15);
-        const Info q = map_info(op.k, k);
-        const uint32_t koff = k < kend ? (uint32_t)q.off * 4u : OOB_K;
+        if (P == 0) {
+            const uint32_t k = k0 + (uint32_t)(lane & 15);
+            kq = map_info(op.k, k);
+            koff = k < kend ? (uint32_t)kq.off * 4u : OOB_K;
+        }
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
+        for (int j = P * LPT / NPART; j < (P + 1) * LPT / NPART; ++j) {
             uint32_t voff = roff[j] + koff;
             if (CHECK) {
-                const bool ok = (uint32_t)(ra[j] + q.a) < op.limA && (uint32_t)(rb[j] + q.b) < op.limB;
+                const bool ok = (uint32_t)(ra[j] + kq.a) < op.limA && (uint32_t)(rb[j] + kq.b) < op.limB;
                 voff = ok ? voff : OOB_ROW;
             }
             load_to_lds(rsrc, stage + (wave * NJ + j) * GS, voff, 0u);
@@ -160,6 +185,47 @@ template <int R, bool CHECK> struct KLoader {
     __device__ __forceinline__ static void frag(const float *stage, int row, int ks, int h, float out[4])
     {
         const float4 q = *reinterpret_cast<const float4 *>(stage + (row >> 2) * GS + (row & 3) * 16 + 8 * ks + 4 * h);
+        out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
+    }
+};
+
+// KLoader4: for an operand whose reduction index is unit-stride in memory with 16-byte aligned
+// rows (a plain row-major matrix with K % 4 == 0).  One load moves 16 rows x 16 k: lane l fetches
+// the aligned quad (l&3) ^ ((row>>2)&3) of row l>>2, so that the four quads of a row sit in its
+// 64-byte LDS line in an order that spreads a fragment read of 16 rows over all banks.  The k part
+// of the address is wave-uniform (scalar offset); nothing is computed per load.
+template <int R> struct KLoader4 {
+    static constexpr int NJ = (R + 63) / 64;     // load instructions per tile and wave
+    static constexpr int SZ = 4 * NJ * 256;      // rows beyond R are loaded as zeros
+    static constexpr int LPT = NJ;
+    uint32_t roff[NJ];
+    uint32_t kq4;                                // first k of this lane's quad inside the tile
+
+    __device__ __forceinline__ void init(const Operand &op, uint32_t row0, uint32_t nrows, int wave, int lane)
+    {
+        const uint32_t r = (uint32_t)lane >> 2;
+        kq4 = 4u * (((uint32_t)lane & 3u) ^ ((r >> 2) & 3u));
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t rl = (uint32_t)(16 * (wave * NJ + j)) + r, row = row0 + rl;
+            const Info q = map_info(op.row, row);
+            roff[j] = (rl < (uint32_t)R && row < nrows) ? ((uint32_t)q.off + kq4) * 4u : OOB_ROW;
+        }
+    }
+    template <int P>
+    __device__ __forceinline__ void issue_part(BufferRsrc rsrc, float *stage, const Operand &op, uint32_t k0,
+                                               uint32_t kend, int wave, int)
+    {
+#pragma unroll
+        for (int j = P * LPT / NPART; j < (P + 1) * LPT / NPART; ++j) {
+            const uint32_t voff = k0 + kq4 < kend ? roff[j] : OOB_ROW;
+            load4_to_lds(rsrc, stage + (wave * NJ + j) * 256, voff, (k0 * (uint32_t)op.k.s1 + (uint32_t)op.k.o0) * 4u);
+        }
+    }
+    __device__ __forceinline__ static void frag(const float *stage, int row, int ks, int h, float out[4])
+    {
+        const int unit = row * 4 + ((2 * ks + h) ^ ((row >> 2) & 3));
+        const float4 q = *reinterpret_cast<const float4 *>(stage + unit * 4);
         out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
     }
 };
@@ -210,11 +276,12 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 
     // Tiles past the end of the K range are all padding: they cost no memory traffic and keep the
     // count of outstanding loads the same in every iteration.
-    auto issue = [&](int tile) {
+    auto issue_part = [&](auto PC, int tile) {
+        constexpr int P = decltype(PC)::value;
         float *st = smem + (tile & (NST - 1)) * STAGE;
         const uint32_t k0 = kbeg + (uint32_t)tile * KT;
-        la.issue(rsrcA, st, p.A, k0, kend, wave, lane);
-        lb.issue(rsrcB, st + LA::SZ, p.B, k0, kend, wave, lane);
+        la.template issue_part<P>(rsrcA, st, p.A, k0, kend, wave, lane);
+        lb.template issue_part<P>(rsrcB, st + LA::SZ, p.B, k0, kend, wave, lane);
     };
     static_assert((NST & (NST - 1)) == 0, "ring index by mask");
 
@@ -229,30 +296,36 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
 #pragma unroll
-    for (int d = 0; d < NST - 1; ++d) issue(d);
+    for (int d = 0; d < NST - 1; ++d) static_for<0, NPART>([&](auto PC) { issue_part(PC, d); });
 
     for (int it = 0; it < n_iter; ++it) {
         // This wave's loads of tile `it` have landed (all but the NST-2 newer tiles are complete);
         // behind the barrier that holds for every wave, and everyone is done reading tile it-1,
-        // whose stage the loads issued next overwrite.
+        // whose stage the loads issued below overwrite.
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NST - 2) * LPT) : "memory");
-        issue(it + NST - 1);
         const float *a_s = smem + (it & (NST - 1)) * STAGE, *b_s = a_s + LA::SZ;
+        float af[KT / 8][TM][4], bf[KT / 8][TN][4];
 #pragma unroll
         for (int ks = 0; ks < KT / 8; ++ks) {
-            float af[TM][4], bf[TN][4];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[i]);
+            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[ks][i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, ks, h, bf[j]);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][s], bf[j][s], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, ks, h, bf[ks][j]);
         }
+        // One part of the next tile's loads behind each MFMA step: the address pipeline and the
+        // matrix pipeline both stay fed, instead of taking turns.
+        static_for<0, NPART>([&](auto PC) {
+            constexpr int P = decltype(PC)::value, ks = P / 4, s4 = P % 4;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
+#if CG_EXP != 1
+            issue_part(PC, it + NST - 1);
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+        });
     }
     // the padding tiles still in flight write into this block's LDS: let them finish before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -313,25 +386,29 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
     return CG_OK;
 }
 
-// AK / BK: lanes of the operand's loads run along k; BC: operand B needs the window test
-template <bool AK, bool BK, bool BC>
+// How an operand's tile is fetched: rows along the lanes, k along the lanes, or aligned quads of k.
+enum { LD_ROWS = 0, LD_K = 1, LD_K4 = 2 };
+template <int MODE, int R, bool CHECK>
+using LoaderOf = std::conditional_t<MODE == LD_K4, KLoader4<R>,
+                                    std::conditional_t<MODE == LD_K, KLoader<R, CHECK>, RowsLoader<R, CHECK>>>;
+
+template <int AM, int BM, bool BC>
 int launch_modes(const IgemmProblem &p, int mt, hipStream_t stream)
 {
-    static const char modes[4] = {AK ? 'k' : 'r', BK ? 'k' : 'r', BC ? 'c' : '-', 0};
+    static const char modes[4] = {"rk4"[AM], "rk4"[BM], BC ? 'c' : '-', 0};
     switch (mt) {
-    case 128:
-        return launch_cfg<2, 2, 2, 2, std::conditional_t<AK, KLoader<128, false>, RowsLoader<128, false>>,
-                          std::conditional_t<BK, KLoader<128, BC>, RowsLoader<128, BC>>>(p, modes, stream);
-    case 96:
-        return launch_cfg<1, 4, 3, 1, std::conditional_t<AK, KLoader<96, false>, RowsLoader<96, false>>,
-                          std::conditional_t<BK, KLoader<128, BC>, RowsLoader<128, BC>>>(p, modes, stream);
-    case 64:
-        return launch_cfg<1, 4, 2, 1, std::conditional_t<AK, KLoader<64, false>, RowsLoader<64, false>>,
-                          std::conditional_t<BK, KLoader<128, BC>, RowsLoader<128, BC>>>(p, modes, stream);
-    default:
-        return launch_cfg<1, 4, 1, 1, std::conditional_t<AK, KLoader<32, false>, RowsLoader<32, false>>,
-                          std::conditional_t<BK, KLoader<128, BC>, RowsLoader<128, BC>>>(p, modes, stream);
+    case 128: return launch_cfg<2, 2, 2, 2, LoaderOf<AM, 128, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 96: return launch_cfg<1, 4, 3, 1, LoaderOf<AM, 96, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 64: return launch_cfg<1, 4, 2, 1, LoaderOf<AM, 64, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    default: return launch_cfg<1, 4, 1, 1, LoaderOf<AM, 32, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
     }
+}
+
+// rows and k both plain strides, k unit-stride, everything 16-byte aligned: aligned quads can be loaded
+bool quad_ok(const Operand &o, uint32_t K)
+{
+    return o.lanes_k && !o.check && K % 4 == 0 && o.k.d1.d == 1 && o.k.d2.d == 1 && o.k.s1 == 1 && o.row.d1.d == 1 &&
+           o.row.d2.d == 1 && o.row.s1 % 4 == 0 && o.gstride % 4 == 0 && (o.row.o0 + o.k.o0 + o.shift) % 4 == 0;
 }
 
 int pick_mt(uint32_t M)
@@ -451,10 +528,15 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     if (!p.B.check) { p.B.limA = p.B.limB = 1; }
 
     const int mt = pick_mt(p.M);
-    const bool ak = p.A.lanes_k != 0, bk = p.B.lanes_k != 0, bc = p.B.check != 0;
-    if (ak && !bk) return bc ? launch_modes<true, false, true>(p, mt, stream) : launch_modes<true, false, false>(p, mt, stream);
-    if (ak && bk) return bc ? launch_modes<true, true, true>(p, mt, stream) : launch_modes<true, true, false>(p, mt, stream);
-    if (!ak && !bk && !bc) return launch_modes<false, false, false>(p, mt, stream);
+    const bool bc = p.B.check != 0;
+    const int am = quad_ok(p.A, p.K) ? LD_K4 : p.A.lanes_k ? LD_K : LD_ROWS;
+    const int bm = quad_ok(p.B, p.K) ? LD_K4 : p.B.lanes_k ? LD_K : LD_ROWS;
+    if (am == LD_K4 && bm == LD_ROWS) return bc ? launch_modes<LD_K4, LD_ROWS, true>(p, mt, stream) : launch_modes<LD_K4, LD_ROWS, false>(p, mt, stream);
+    if (am == LD_K4 && bm == LD_K4) return launch_modes<LD_K4, LD_K4, false>(p, mt, stream);
+    if (am == LD_K4 && bm == LD_K) return bc ? launch_modes<LD_K, LD_K, true>(p, mt, stream) : launch_modes<LD_K, LD_K, false>(p, mt, stream);
+    if (am == LD_K && bm == LD_ROWS) return bc ? launch_modes<LD_K, LD_ROWS, true>(p, mt, stream) : launch_modes<LD_K, LD_ROWS, false>(p, mt, stream);
+    if (am == LD_K && (bm == LD_K || bm == LD_K4)) return bc ? launch_modes<LD_K, LD_K, true>(p, mt, stream) : launch_modes<LD_K, LD_K, false>(p, mt, stream);
+    if (am == LD_ROWS && bm == LD_ROWS && !bc) return launch_modes<LD_ROWS, LD_ROWS, false>(p, mt, stream);
     return CG_EUNSUPPORTED;
 }
 

@@ -65,7 +65,7 @@ def test_entry_points_reject_null_and_misaligned_arguments_without_launching():
 def test_workspace_sizes():
     d = cg.conv_desc(256, 256, 13, 13, 384, 3, pad=1)
     assert cg.cg_conv_workspace_bytes(d, cg.CG_PASS_FWD) == 0
-    assert cg.cg_conv_workspace_bytes(d, cg.CG_PASS_BWD_DATA) == 0       # filters are read in place
+    assert cg.cg_conv_workspace_bytes(d, cg.CG_PASS_BWD_DATA) == 384 * 256 * 9 * 4      # transposed filters
     ws = cg.cg_conv_workspace_bytes(d, cg.CG_PASS_BWD_WEIGHT)
     assert ws > 2 * 384 * 256 * 9 * 4                   # at least two K slices of dw + bias partials
     small = cg.conv_desc(2, 64, 13, 13, 64, 3, pad=1)
@@ -124,10 +124,8 @@ def test_backward_data_maps_address_the_adjoint(case):
     Kp = Mg * KH * KW
     for g in range(G):
         for c, k in itertools.product(range(Cg), range(Kp)):
-            # the filters are read in place: row c, reduction index (ml, kh, kw)
             off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_DATA, 0, c, k, g)
-            ml, tap = divmod(k, KH * KW)
-            assert ok and off == ((g * Mg + ml) * Cg + c) * KH * KW + tap
+            assert ok and off == (g * Cg + c) * Kp + k
         for n, ih, iw in itertools.product(range(N), range(H), range(W)):
             row = (n * H + ih) * W + iw
             for ml, kh, kw in itertools.product(range(Mg), range(KH), range(KW)):
