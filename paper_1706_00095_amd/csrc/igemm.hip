@@ -30,8 +30,7 @@ namespace {
 #ifndef CG_EXP
 #define CG_EXP 0
 #endif
-constexpr int KT = 16;                       // reduction indices per LDS stage
-constexpr int NST = 4;                       // LDS stages
+constexpr int KT = 16;                       // reduction indices per LDS stage (a ring of NST stages)
 constexpr int NPART = KT / 2;                // MFMA steps per tile = parts the loads of a tile are issued in
 // Offsets that no buffer descriptor of this library covers (descriptors span < 0x7fffff00 bytes).
 // Their sum does not wrap, and either one added to a valid offset (< 2^31) stays out of range.
@@ -248,7 +247,7 @@ __device__ __forceinline__ BufferRsrc operand_rsrc(const Operand &op, uint32_t g
 
 }  // namespace
 
-template <int WM, int WN, int TM, int TN, class LA, class LB>
+template <int WM, int WN, int TM, int TN, int NST, class LA, class LB>
 __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 {
     static_assert(WM * WN == 4, "four waves");
@@ -278,12 +277,11 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
     // count of outstanding loads the same in every iteration.
     auto issue_part = [&](auto PC, int tile) {
         constexpr int P = decltype(PC)::value;
-        float *st = smem + (tile & (NST - 1)) * STAGE;
+        float *st = smem + (tile % NST) * STAGE;
         const uint32_t k0 = kbeg + (uint32_t)tile * KT;
         la.template issue_part<P>(rsrcA, st, p.A, k0, kend, wave, lane);
         lb.template issue_part<P>(rsrcB, st + LA::SZ, p.B, k0, kend, wave, lane);
     };
-    static_assert((NST & (NST - 1)) == 0, "ring index by mask");
 
     const int wm = wave / WN, wn = wave % WN;
     const int h = lane >> 5, li = lane & 31;
@@ -303,7 +301,7 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
         // behind the barrier that holds for every wave, and everyone is done reading tile it-1,
         // whose stage the loads issued below overwrite.
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NST - 2) * LPT) : "memory");
-        const float *a_s = smem + (it & (NST - 1)) * STAGE, *b_s = a_s + LA::SZ;
+        const float *a_s = smem + (it % NST) * STAGE, *b_s = a_s + LA::SZ;
         float af[KT / 8][TM][4], bf[KT / 8][TN][4];
 #pragma unroll
         for (int ks = 0; ks < KT / 8; ++ks) {
@@ -360,7 +358,7 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 
 namespace {
 
-template <int WM, int WN, int TM, int TN, class LA, class LB>
+template <int WM, int WN, int TM, int TN, int NST, class LA, class LB>
 int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
 {
     constexpr int MT = WM * TM * 32, NT = WN * TN * 32;
@@ -376,11 +374,11 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
     static bool attr_set = false;      // raising the dynamic-LDS limit is a per-kernel, one-time host call
     if (!attr_set) {
-        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_kernel<WM, WN, TM, TN, LA, LB>),
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_kernel<WM, WN, TM, TN, NST, LA, LB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, LA, LB>), grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, NST, LA, LB>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
@@ -397,10 +395,12 @@ int launch_modes(const IgemmProblem &p, int mt, hipStream_t stream)
 {
     static const char modes[4] = {"rk4"[AM], "rk4"[BM], BC ? 'c' : '-', 0};
     switch (mt) {
-    case 128: return launch_cfg<2, 2, 2, 2, LoaderOf<AM, 128, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
-    case 96: return launch_cfg<1, 4, 3, 1, LoaderOf<AM, 96, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
-    case 64: return launch_cfg<1, 4, 2, 1, LoaderOf<AM, 64, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
-    default: return launch_cfg<1, 4, 1, 1, LoaderOf<AM, 32, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 256: return launch_cfg<2, 2, 4, 2, 3, LoaderOf<AM, 256, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 192: return launch_cfg<2, 2, 3, 2, 3, LoaderOf<AM, 192, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 128: return launch_cfg<2, 2, 2, 2, 4, LoaderOf<AM, 128, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 96: return launch_cfg<1, 4, 3, 1, 4, LoaderOf<AM, 96, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    case 64: return launch_cfg<1, 4, 2, 1, 4, LoaderOf<AM, 64, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
+    default: return launch_cfg<1, 4, 1, 1, 4, LoaderOf<AM, 32, false>, LoaderOf<BM, 128, BC>>(p, modes, stream);
     }
 }
 
@@ -411,14 +411,27 @@ bool quad_ok(const Operand &o, uint32_t K)
            o.row.d2.d == 1 && o.row.s1 % 4 == 0 && o.gstride % 4 == 0 && (o.row.o0 + o.k.o0 + o.shift) % 4 == 0;
 }
 
-int pick_mt(uint32_t M)
+// Row-tile height for a problem.  A taller tile gathers the B operand (the costly one: one load
+// instruction per 64 elements) fewer times, but leaves fewer blocks to spread over the 256 compute
+// units, two resident per unit.  The cost model is the number of blocks the busiest unit runs (an
+// odd one out runs alone and a little slower than a pair) times a block's duration, rows + a fixed
+// per-block part; problems with few tiles are cut along K afterwards, which fills the chip for any
+// tile height, so there only the per-block efficiency counts.
+int pick_mt(uint32_t M, uint32_t N, uint32_t groups)
 {
-    const int cand[4] = {128, 96, 64, 32};
-    int best = 0;
-    uint64_t best_cost = ~0ull;
+    const int cand[6] = {256, 192, 128, 96, 64, 32};
+    int best = 32;
+    double best_cost = 1e300;
     for (int c : cand) {
-        const uint64_t cost = (uint64_t)((M + c - 1) / c) * c;
-        if (cost < best_cost) { best_cost = cost; best = c; }   // ties keep the larger tile
+        const uint64_t tiles = (uint64_t)((M + c - 1) / c) * ((N + 127) / 128) * groups;
+        double cost;
+        if (tiles < 512) {
+            cost = (double)tiles * (c + 50) / 256.0;                  // cut along K into ~4 blocks per unit
+        } else {
+            const uint64_t n = (tiles + 255) / 256;
+            cost = ((n & 1) ? (double)(n - 1) + 1.2 : (double)n) * (c + 50);
+        }
+        if (cost < best_cost * 0.999) { best_cost = cost; best = c; }   // ties keep the larger tile
     }
     return best;
 }
@@ -527,7 +540,7 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     if (!p.A.check) { p.A.limA = p.A.limB = 1; }
     if (!p.B.check) { p.B.limA = p.B.limB = 1; }
 
-    const int mt = pick_mt(p.M);
+    const int mt = pick_mt(p.M, p.N, p.groups);
     const bool bc = p.B.check != 0;
     const int am = quad_ok(p.A, p.K) ? LD_K4 : p.A.lanes_k ? LD_K : LD_ROWS;
     const int bm = quad_ok(p.B, p.K) ? LD_K4 : p.B.lanes_k ? LD_K : LD_ROWS;
@@ -584,7 +597,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
 SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups)
 {
     SplitPlan pl{1, K, 0};
-    const uint32_t mt = (uint32_t)pick_mt(M);
+    const uint32_t mt = (uint32_t)pick_mt(M, N, groups);
     const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
     if (tiles >= 512) return pl;
     uint64_t want = (1024 + tiles - 1) / tiles;      // aim at ~4 resident blocks per compute unit
