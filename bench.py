@@ -27,13 +27,14 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_net(cg, torch, B, K, seed, n_batches=16):
+def build_net(cg, torch, B, K, seed, n_batches=32):
     import cg_synth
     layers, in_shape = cg_synth.alexnet_layers()
     gen = torch.Generator(device="cuda").manual_seed(seed)
     net = cg.Net(layers, B, in_shape)
-    # a small pool of resident batches, visited round-robin: training on one fixed batch memorises
-    # it within ten steps and then diverges, which says nothing about speed but ends in NaNs
+    # a pool of resident batches, one per step of the run where memory allows: random images with
+    # random labels can only be memorised, and a net that has memorised a small pool then diverges
+    # under this learning rate, which says nothing about speed but ends in NaNs
     xs = [torch.randn((B,) + tuple(in_shape), device="cuda", generator=gen) for _ in range(n_batches)]
     ls = [torch.randint(0, 1000, (B,), device="cuda", generator=gen, dtype=torch.int32) for _ in range(n_batches)]
     st = dict(net=net, layers=layers, xs=xs, ls=ls, it=0, w={}, v={}, g={}, peers={}, masks={})
@@ -162,7 +163,7 @@ def main():
     B, K = args.batch, args.peers
     sgd = cg.cg_sgd(0.01, 0.9, 5e-4, 1.0)
     flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
-    st = build_net(cg, torch, B, K, seed=4)
+    st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps)))
     torch.cuda.synchronize()
     run_steps(cg, torch, st, sgd, args.warmup, flags)
     sync(torch, st)

@@ -144,6 +144,12 @@ int cg_net_destroy(cg_net *net);
  * 0 for layers without parameters, negative on error. */
 long long cg_net_param_count(const cg_net *net, int layer);
 
+/* 1 if the layer's own output is not materialised: a convolution or
+ * fully-connected layer whose only consumer is a rectifier stores max(., 0)
+ * directly, and which = 0 of cg_net_tensor() then names the rectifier's output
+ * for both layers.  0 otherwise, negative on error. */
+int cg_net_layer_fused(const cg_net *net, int layer);
+
 /* Attach the caller-owned buffers of a parameter layer: model w, history v,
  * this worker's gradient g_local (written by every step), and K peer gradient
  * buckets (HOST array of K device pointers, copied), each param_count floats. */
@@ -175,8 +181,8 @@ int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                   float *loss_dev, int flags);
 
 /* Where a layer's output (which = 0), the gradient with respect to its output
- * (which = 1) or its saved forward state (which = 2: the LRN scale as floats,
- * the max-pool argmax as int32 flat indices ih*W+iw; empty for other layers)
+ * (which = 1) or its saved forward state (which = 2: the max-pool argmax as
+ * int32 flat indices ih*W+iw; empty for other layers)
  * lives inside a workspace of base address ws after a step; for inspection by
  * tests.  count receives the number of 4-byte elements. */
 int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count);

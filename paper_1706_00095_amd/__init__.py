@@ -22,7 +22,7 @@ LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc":
 
 EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight",
-    "cg_grad_reduce_sgd", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_bind",
+    "cg_grad_reduce_sgd", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
     "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
@@ -79,6 +79,8 @@ def lib():
         L.cg_net_destroy.argtypes = [vp]
         L.cg_net_param_count.argtypes = [vp, C.c_int]
         L.cg_net_param_count.restype = C.c_longlong
+        L.cg_net_layer_fused.argtypes = [vp, C.c_int]
+        L.cg_net_layer_fused.restype = C.c_int
         L.cg_net_bind.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(vp), C.c_int]
         L.cg_net_workspace_bytes.argtypes = [vp]
         L.cg_net_workspace_bytes.restype = sz
@@ -243,6 +245,13 @@ def cg_net_param_count(net, layer):
     if n < 0:
         raise CgError(int(n), "cg_net_param_count")
     return int(n)
+
+
+def cg_net_layer_fused(net, layer):
+    r = lib().cg_net_layer_fused(net.handle, layer)
+    if r < 0:
+        raise CgError(int(r), "cg_net_layer_fused")
+    return bool(r)
 
 
 def cg_net_bind(net, layer, w, v, g_local, g_peers):

@@ -133,14 +133,15 @@ int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, 
 int conv_check(const cg_conv_desc *d, int *OH, int *OW);
 size_t conv_ws_bytes(const cg_conv_desc &d, int pass);
 size_t fc_ws_bytes(int B, int IN, int OUT, int pass);
+// relu != 0: y = max(conv + bias, 0), the rectifier that follows folded into the store
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, hipStream_t stream);
+                  size_t ws_bytes, int relu, hipStream_t stream);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream);
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
                          void *ws, size_t ws_bytes, hipStream_t stream);
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
-                size_t ws_bytes, hipStream_t stream);
+                size_t ws_bytes, int relu, hipStream_t stream);
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate, void *ws,
                      size_t ws_bytes, hipStream_t stream);
 int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
@@ -159,10 +160,11 @@ int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, 
                        hipStream_t st);
 int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, int N, int C, int H, int W, int k, int s,
                        int p, int accumulate, hipStream_t st);
-int lrn_fwd_launch(const float *x, float *y, float *scale, int N, int C, int HW, int size, float alpha, float beta,
-                   float kappa, hipStream_t st);
-int lrn_bwd_launch(const float *x, const float *y, const float *scale, const float *dy, float *dx, int N, int C,
-                   int HW, int size, float alpha, float beta, int accumulate, hipStream_t st);
+int lrn_fwd_launch(const float *x, float *y, int N, int C, int HW, int size, float alpha, float beta, float kappa,
+                   hipStream_t st);
+// recomputes the scales from x; nothing saved by forward is read
+int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int HW, int size, float alpha, float beta,
+                   float kappa, int accumulate, hipStream_t st);
 int avgpool_fwd_launch(const float *x, float *y, int NC, int HW, hipStream_t st);
 int avgpool_bwd_launch(const float *dy, float *dx, int NC, int HW, int accumulate, hipStream_t st);
 int dropout_launch(const float *x, const uint8_t *mask, float *y, size_t n, float p, int accumulate, hipStream_t st);

@@ -148,13 +148,15 @@ static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const flo
 }
 
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, hipStream_t stream)
+                  size_t ws_bytes, int relu, hipStream_t stream)
 {
     ProfTag tag("conv_fwd", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
-    return igemm_run(fwd_problem(d, OH, OW, x, w, bias, y), ws, ws_bytes, stream);
+    IgemmProblem p = fwd_problem(d, OH, OW, x, w, bias, y);
+    p.relu = relu;
+    return igemm_run(p, ws, ws_bytes, stream);
 }
 
 static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *wt,
@@ -344,11 +346,13 @@ static IgemmProblem fc_bwd_weight_problem(int B, int IN, int OUT, const float *x
 }
 
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
-                size_t ws_bytes, hipStream_t stream)
+                size_t ws_bytes, int relu, hipStream_t stream)
 {
     ProfTag tag("fc_fwd", -1);
     if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
-    return igemm_run(fc_fwd_problem(B, IN, OUT, x, W, bias, y), ws, ws_bytes, stream);
+    IgemmProblem p = fc_fwd_problem(B, IN, OUT, x, W, bias, y);
+    p.relu = relu;
+    return igemm_run(p, ws, ws_bytes, stream);
 }
 
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate, void *ws,
@@ -422,7 +426,7 @@ extern "C" int cg_conv_fwd(const cg_conv_desc *d, const float *x, const float *w
 {
     if (!d || !x || !w || !y) return CG_EINVAL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return CG_EINVAL;
-    return conv_fwd_impl(*d, x, w, bias, y, ws, ws_bytes, static_cast<hipStream_t>(stream));
+    return conv_fwd_impl(*d, x, w, bias, y, ws, ws_bytes, 0, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,

@@ -19,32 +19,61 @@ inline unsigned grid_for(size_t n, unsigned cap = 16384)
     return (unsigned)b;
 }
 
+// Element-wise kernels move 16 bytes per lane; `n4` counts whole float4 groups, the last n % 4
+// elements are handled by the first lanes of block 0.
 __global__ __launch_bounds__(TB) void relu_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, size_t n)
 {
-    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < n; i += (size_t)gridDim.x * TB) {
-        const float a = x[i];
-        y[i] = a > 0.f ? a : 0.f;
+    const size_t n4 = n / 4;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    float4 *y4 = reinterpret_cast<float4 *>(y);
+    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < n4; i += (size_t)gridDim.x * TB) {
+        float4 a = x4[i];
+        a.x = a.x > 0.f ? a.x : 0.f; a.y = a.y > 0.f ? a.y : 0.f;
+        a.z = a.z > 0.f ? a.z : 0.f; a.w = a.w > 0.f ? a.w : 0.f;
+        y4[i] = a;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n % 4) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        y[i] = x[i] > 0.f ? x[i] : 0.f;
     }
 }
 
+// x may be the rectifier's input or its output: only the sign is used, and both have the same
+template <int ACC>
 __global__ __launch_bounds__(TB) void relu_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
-                                                      float *__restrict__ dx, size_t n, int accumulate)
+                                                      float *__restrict__ dx, size_t n)
 {
-    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < n; i += (size_t)gridDim.x * TB) {
+    const size_t n4 = n / 4;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    const float4 *g4 = reinterpret_cast<const float4 *>(dy);
+    float4 *d4 = reinterpret_cast<float4 *>(dx);
+    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < n4; i += (size_t)gridDim.x * TB) {
+        const float4 a = x4[i], g = g4[i];
+        float4 r;
+        r.x = a.x > 0.f ? g.x : 0.f; r.y = a.y > 0.f ? g.y : 0.f;
+        r.z = a.z > 0.f ? g.z : 0.f; r.w = a.w > 0.f ? g.w : 0.f;
+        if (ACC) { const float4 o = d4[i]; r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w; }
+        d4[i] = r;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n % 4) {
+        const size_t i = n4 * 4 + threadIdx.x;
         const float gval = x[i] > 0.f ? dy[i] : 0.f;
-        dx[i] = accumulate ? dx[i] + gval : gval;
+        dx[i] = ACC ? dx[i] + gval : gval;
     }
 }
 
+// Pooling kernels: a block owns `ppb` consecutive (n, c) planes, so that all index arithmetic is
+// 32-bit and local to a plane.
 __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
-                                                         int32_t *__restrict__ argmax, size_t total, int H, int W,
-                                                         int OH, int OW, int k, int s, int p)
+                                                         int32_t *__restrict__ argmax, uint32_t planes, int ppb, int H,
+                                                         int W, int OH, int OW, int k, int s, int p)
 {
-    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < total; i += (size_t)gridDim.x * TB) {
-        const int ow = (int)(i % OW);
-        size_t r = i / OW;
-        const int oh = (int)(r % OH);
-        const size_t nc = r / OH;
+    const uint32_t P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
+    const uint32_t np = min((uint32_t)ppb, planes - plane0);
+    for (uint32_t j = threadIdx.x; j < np * P; j += TB) {
+        const uint32_t pl = j / P, o = j - pl * P;
+        const int oh = (int)(o / (uint32_t)OW), ow = (int)(o - (uint32_t)oh * OW);
+        const size_t nc = (size_t)plane0 + pl;
         const float *xp = x + nc * H * W;
         int best = -1;
         float bv = 0.f;
@@ -58,23 +87,24 @@ __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict
                 if (best < 0 || val > bv) { best = ih * W + iw; bv = val; }
             }
         }
-        y[i] = bv;
-        argmax[i] = best;
+        y[nc * P + o] = bv;
+        argmax[nc * P + o] = best;
     }
 }
 
 // Gather form: an input element collects dy from every window that covers it and elected it.
+template <int ACC>
 __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict__ dy,
                                                          const int32_t *__restrict__ argmax, float *__restrict__ dx,
-                                                         size_t total, int H, int W, int OH, int OW, int k, int s,
-                                                         int p, int accumulate)
+                                                         uint32_t planes, int ppb, int H, int W, int OH, int OW, int k,
+                                                         int s, int p)
 {
-    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < total; i += (size_t)gridDim.x * TB) {
-        const int iw = (int)(i % W);
-        size_t r = i / W;
-        const int ih = (int)(r % H);
-        const size_t nc = r / H;
-        const int me = ih * W + iw;
+    const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
+    const uint32_t np = min((uint32_t)ppb, planes - plane0);
+    for (uint32_t j = threadIdx.x; j < np * Q; j += TB) {
+        const uint32_t pl = j / Q, me = j - pl * Q;
+        const int ih = (int)(me / (uint32_t)W), iw = (int)(me - (uint32_t)ih * W);
+        const size_t nc = (size_t)plane0 + pl;
         // windows oh with oh*s - p <= ih <= oh*s - p + k - 1
         int oh_lo = ih + p - k + 1;
         oh_lo = oh_lo <= 0 ? 0 : (oh_lo + s - 1) / s;
@@ -84,19 +114,126 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict
         ow_lo = ow_lo <= 0 ? 0 : (ow_lo + s - 1) / s;
         int ow_hi = (iw + p) / s;
         if (ow_hi > OW - 1) ow_hi = OW - 1;
+        const int32_t *ap = argmax + nc * P;
+        const float *gp = dy + nc * P;
         float acc = 0.f;
         for (int oh = oh_lo; oh <= oh_hi; ++oh)
             for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-                const size_t o = (nc * OH + oh) * OW + ow;
-                if (argmax[o] == me) acc += dy[o];
+                const int o = oh * OW + ow;
+                if (ap[o] == (int32_t)me) acc += gp[o];
             }
-        dx[i] = accumulate ? dx[i] + acc : acc;
+        float *dst = dx + nc * Q + me;
+        *dst = ACC ? *dst + acc : acc;
     }
 }
 
-__global__ __launch_bounds__(TB) void lrn_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
-                                                     float *__restrict__ scale, size_t total, int C, int HW, int size,
-                                                     float alpha_over_size, float beta, float kappa)
+// ---- local response normalisation across channels ---------------------------------------------
+//   scale_c = kappa + (alpha/size) * sum_{j in win(c)} x_j^2,  y_c = x_c * scale_c^-beta,
+//   win(c) = [c - half, c - half + size - 1], half = (size-1)/2.
+// A thread owns one pixel and walks along the channels of a chunk with the window in registers:
+// every x is read once (plus a halo of size-1 per chunk), nothing but y is written, and backward
+// recomputes the scales from x instead of reading them back.
+
+__device__ __forceinline__ float pow_neg(float sc, float beta)      // sc^-beta, sc > 0
+{
+    if (beta == 0.75f) { const float r = rsqrtf(sc); return r * sqrtf(r); }
+    return exp2f(-beta * log2f(sc));
+}
+
+constexpr int LRN_CH = 48;        // channels per chunk
+
+template <int SIZE>
+__global__ __launch_bounds__(TB) void lrn_fwd_stream_kernel(const float *__restrict__ x, float *__restrict__ y, int C,
+                                                            int HW, int nchunk, float aos, float beta, float kappa)
+{
+    constexpr int half = (SIZE - 1) / 2;
+    const int pix = blockIdx.x * TB + threadIdx.x;
+    if (pix >= HW) return;
+    const int n = blockIdx.y / nchunk, c0 = (blockIdx.y % nchunk) * LRN_CH;
+    const int c1 = min(C, c0 + LRN_CH);
+    const float *xp = x + (size_t)n * C * HW + pix;
+    float *yp = y + (size_t)n * C * HW + pix;
+    float win[SIZE];               // x[c - half .. c - half + SIZE - 1] once the step's element has entered
+#pragma unroll
+    for (int d = 0; d < SIZE - 1; ++d) {
+        const int cc = c0 - half + d;
+        win[d + 1] = (cc >= 0 && cc < C) ? xp[(size_t)cc * HW] : 0.f;
+    }
+#pragma unroll 4
+    for (int c = c0; c < c1; ++c) {
+        const int e = c - half + SIZE - 1;
+#pragma unroll
+        for (int d = 0; d < SIZE - 1; ++d) win[d] = win[d + 1];
+        win[SIZE - 1] = e < C ? xp[(size_t)e * HW] : 0.f;
+        float ss = 0.f;
+#pragma unroll
+        for (int d = 0; d < SIZE; ++d) ss += win[d] * win[d];
+        yp[(size_t)c * HW] = win[half] * pow_neg(kappa + aos * ss, beta);
+    }
+}
+
+//   dx_c = dy_c * scale_c^-beta - (2 alpha beta / size) * x_c * sum_{j : c in win(j)} dy_j x_j scale_j^(-beta-1)
+// Step c (from c0 - (SIZE-1), the first SIZE-1 steps only fill the rings) lets x_e enter, e = c + SIZE - 1,
+// computes scale and t = dy x scale^(-beta-1) of channel j = c + half, whose window is now complete,
+// and emits dx_c, whose sum over j in [c - (SIZE-1-half), c + half] is the whole t ring.
+template <int SIZE, int ACC>
+__global__ __launch_bounds__(TB) void lrn_bwd_stream_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                                            float *__restrict__ dx, int C, int HW, int nchunk,
+                                                            float aos, float coef, float beta, float kappa)
+{
+    constexpr int half = (SIZE - 1) / 2;
+    const int pix = blockIdx.x * TB + threadIdx.x;
+    if (pix >= HW) return;
+    const int n = blockIdx.y / nchunk, c0 = (blockIdx.y % nchunk) * LRN_CH;
+    const int c1 = min(C, c0 + LRN_CH);
+    const size_t img = (size_t)n * C * HW + pix;
+    const float *xp = x + img, *gp = dy + img;
+    float *dp = dx + img;
+    float win[SIZE], tr[SIZE], q[half + 1];      // x window, t ring, dy*scale^-beta of the last half+1 channels
+#pragma unroll
+    for (int d = 0; d < SIZE; ++d) tr[d] = 0.f;
+#pragma unroll
+    for (int d = 0; d <= half; ++d) q[d] = 0.f;
+    const int cs = c0 - (SIZE - 1);
+#pragma unroll
+    for (int d = 0; d < SIZE - 1; ++d) {
+        const int cc = cs + d;                   // ring holds x[e-SIZE+1 .. e-1] before step cs, e = cs + SIZE - 1
+        win[d + 1] = (cc >= 0 && cc < C) ? xp[(size_t)cc * HW] : 0.f;
+    }
+#pragma unroll 4
+    for (int c = cs; c < c1; ++c) {
+        const int e = c + SIZE - 1, j = c + half;
+#pragma unroll
+        for (int d = 0; d < SIZE - 1; ++d) { win[d] = win[d + 1]; tr[d] = tr[d + 1]; }
+#pragma unroll
+        for (int d = 0; d < half; ++d) q[d] = q[d + 1];
+        win[SIZE - 1] = (e >= 0 && e < C) ? xp[(size_t)e * HW] : 0.f;
+        float t = 0.f, qq = 0.f;
+        if (j >= 0 && j < C) {
+            float ss = 0.f;
+#pragma unroll
+            for (int d = 0; d < SIZE; ++d) ss += win[d] * win[d];
+            const float sc = kappa + aos * ss, pw = pow_neg(sc, beta), g = gp[(size_t)j * HW];
+            qq = g * pw;
+            t = qq * win[half] / sc;             // x_j sits at position half of its own window
+        }
+        tr[SIZE - 1] = t;
+        q[half] = qq;
+        if (c >= c0) {
+            float cross = 0.f;
+#pragma unroll
+            for (int d = 0; d < SIZE; ++d) cross += tr[d];
+            const float gval = q[0] - coef * win[0] * cross;     // x_c = x_{e-SIZE+1}: the oldest ring entry
+            float *dst = dp + (size_t)c * HW;
+            *dst = ACC ? *dst + gval : gval;
+        }
+    }
+}
+
+// any window size: the definition, term by term (scales recomputed per term)
+__global__ __launch_bounds__(TB) void lrn_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, size_t total,
+                                                     int C, int HW, int size, float alpha_over_size, float beta,
+                                                     float kappa)
 {
     const int half = (size - 1) / 2;
     for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < total; i += (size_t)gridDim.x * TB) {
@@ -108,16 +245,27 @@ __global__ __launch_bounds__(TB) void lrn_fwd_kernel(const float *__restrict__ x
             const float xv = x[(ptrdiff_t)i + (ptrdiff_t)d * HW];
             ss += xv * xv;
         }
-        const float sc = kappa + alpha_over_size * ss;
-        scale[i] = sc;
-        y[i] = x[i] * powf(sc, -beta);
+        y[i] = x[i] * pow_neg(kappa + alpha_over_size * ss, beta);
     }
 }
 
-__global__ __launch_bounds__(TB) void lrn_bwd_kernel(const float *__restrict__ x, const float *__restrict__ y,
-                                                     const float *__restrict__ scale, const float *__restrict__ dy,
+__device__ __forceinline__ float lrn_scale_at(const float *__restrict__ x, ptrdiff_t i, int c, int C, int HW, int size,
+                                              float aos, float kappa)
+{
+    const int half = (size - 1) / 2;
+    float ss = 0.f;
+    for (int d = -half; d <= -half + size - 1; ++d) {
+        const int cc = c + d;
+        if (cc < 0 || cc >= C) continue;
+        const float xv = x[i + (ptrdiff_t)d * HW];
+        ss += xv * xv;
+    }
+    return kappa + aos * ss;
+}
+
+__global__ __launch_bounds__(TB) void lrn_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                                      float *__restrict__ dx, size_t total, int C, int HW, int size,
-                                                     float coef, float beta, int accumulate)
+                                                     float aos, float coef, float beta, float kappa, int accumulate)
 {
     const int half = (size - 1) / 2;
     for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < total; i += (size_t)gridDim.x * TB) {
@@ -127,10 +275,12 @@ __global__ __launch_bounds__(TB) void lrn_bwd_kernel(const float *__restrict__ x
         for (int d = half - size + 1; d <= half; ++d) {
             const int j = c + d;
             if (j < 0 || j >= C) continue;
-            const ptrdiff_t q = (ptrdiff_t)i + (ptrdiff_t)d * HW;
-            cross += dy[q] * y[q] / scale[q];
+            const ptrdiff_t qi = (ptrdiff_t)i + (ptrdiff_t)d * HW;
+            const float sc = lrn_scale_at(x, qi, j, C, HW, size, aos, kappa);
+            cross += dy[qi] * x[qi] * pow_neg(sc, beta) / sc;
         }
-        const float gval = dy[i] * powf(scale[i], -beta) - coef * x[i] * cross;
+        const float sc = lrn_scale_at(x, (ptrdiff_t)i, c, C, HW, size, aos, kappa);
+        const float gval = dy[i] * pow_neg(sc, beta) - coef * x[i] * cross;
         dx[i] = accumulate ? dx[i] + gval : gval;
     }
 }
@@ -155,12 +305,26 @@ __global__ __launch_bounds__(TB) void avgpool_bwd_kernel(const float *__restrict
     }
 }
 
+template <int ACC>
 __global__ __launch_bounds__(TB) void dropout_kernel(const float *__restrict__ x, const uint8_t *__restrict__ mask,
-                                                     float *__restrict__ y, size_t n, float f, int accumulate)
+                                                     float *__restrict__ y, size_t n, float f)
 {
-    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < n; i += (size_t)gridDim.x * TB) {
+    const size_t n4 = n / 4;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    const uchar4 *m4 = reinterpret_cast<const uchar4 *>(mask);
+    float4 *y4 = reinterpret_cast<float4 *>(y);
+    for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < n4; i += (size_t)gridDim.x * TB) {
+        const float4 a = x4[i];
+        const uchar4 m = m4[i];
+        float4 r;
+        r.x = m.x ? a.x * f : 0.f; r.y = m.y ? a.y * f : 0.f; r.z = m.z ? a.z * f : 0.f; r.w = m.w ? a.w * f : 0.f;
+        if (ACC) { const float4 o = y4[i]; r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w; }
+        y4[i] = r;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n % 4) {
+        const size_t i = n4 * 4 + threadIdx.x;
         const float gval = mask[i] ? x[i] * f : 0.f;
-        y[i] = accumulate ? y[i] + gval : gval;
+        y[i] = ACC ? y[i] + gval : gval;
     }
 }
 
@@ -229,14 +393,24 @@ __global__ __launch_bounds__(TB) void concat_copy_kernel(const float *__restrict
     }
 }
 
+// db[o] = sum_b dy[b][o]: a block owns 32 outputs, its 8 thread rows sum interleaved samples, and
+// the 8 partial sums are added in row order
 __global__ __launch_bounds__(TB) void fc_bias_grad_kernel(const float *__restrict__ dy, int B, int OUT,
                                                           float *__restrict__ db)
 {
-    const int o = blockIdx.x * TB + threadIdx.x;
-    if (o >= OUT) return;
+    __shared__ float part[8][32];
+    const int ol = threadIdx.x & 31, r = threadIdx.x >> 5, o = blockIdx.x * 32 + ol;
     float s = 0.f;
-    for (int b = 0; b < B; ++b) s += dy[(size_t)b * OUT + o];
-    db[o] = s;
+    if (o < OUT)
+        for (int b = r; b < B; b += 8) s += dy[(size_t)b * OUT + o];
+    part[r][ol] = s;
+    __syncthreads();
+    if (r == 0 && o < OUT) {
+        float t = part[0][ol];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) t += part[k][ol];
+        db[o] = t;
+    }
 }
 
 }  // namespace
@@ -246,6 +420,13 @@ __global__ __launch_bounds__(TB) void fc_bias_grad_kernel(const float *__restric
         CG_HIP_TRY(hipGetLastError());     \
         return CG_OK;                      \
     } while (0)
+
+// planes per block of the pooling kernels: about four elements per thread
+static int pool_planes_per_block(int plane_elems)
+{
+    const int ppb = 1024 / (plane_elems > 0 ? plane_elems : 1);
+    return ppb < 1 ? 1 : ppb;
+}
 
 int pool_out_size(int H, int k, int s, int p)
 {
@@ -258,21 +439,24 @@ int pool_out_size(int H, int k, int s, int p)
 
 int fc_bias_grad_launch(const float *dy, int B, int OUT, float *db, hipStream_t st)
 {
-    hipLaunchKernelGGL(fc_bias_grad_kernel, dim3((OUT + TB - 1) / TB), dim3(TB), 0, st, dy, B, OUT, db);
+    hipLaunchKernelGGL(fc_bias_grad_kernel, dim3((OUT + 31) / 32), dim3(TB), 0, st, dy, B, OUT, db);
     CG_LAUNCH_CHECK();
 }
 
 int relu_fwd_launch(const float *x, float *y, size_t n, hipStream_t st)
 {
     if (n == 0) return CG_OK;
-    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid_for(n)), dim3(TB), 0, st, x, y, n);
+    if (!aligned16(x) || !aligned16(y)) return CG_EINVAL;
+    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, y, n);
     CG_LAUNCH_CHECK();
 }
 
 int relu_bwd_launch(const float *x, const float *dy, float *dx, size_t n, int accumulate, hipStream_t st)
 {
     if (n == 0) return CG_OK;
-    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid_for(n)), dim3(TB), 0, st, x, dy, dx, n, accumulate);
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return CG_EINVAL;
+    if (accumulate) hipLaunchKernelGGL(relu_bwd_kernel<1>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, dy, dx, n);
+    else hipLaunchKernelGGL(relu_bwd_kernel<0>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, dy, dx, n);
     CG_LAUNCH_CHECK();
 }
 
@@ -281,9 +465,11 @@ int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, 
 {
     const int OH = pool_out_size(H, k, s, p), OW = pool_out_size(W, k, s, p);
     if (OH <= 0 || OW <= 0 || p >= k) return CG_EINVAL;
-    const size_t total = (size_t)N * C * OH * OW;
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, x, y, argmax, total, H, W, OH, OW,
-                       k, s, p);
+    if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
+    const uint32_t planes = (uint32_t)N * C;
+    const int ppb = pool_planes_per_block(OH * OW);
+    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3((planes + ppb - 1) / ppb), dim3(TB), 0, st, x, y, argmax, planes, ppb, H,
+                       W, OH, OW, k, s, p);
     CG_LAUNCH_CHECK();
 }
 
@@ -292,28 +478,67 @@ int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, int N,
 {
     const int OH = pool_out_size(H, k, s, p), OW = pool_out_size(W, k, s, p);
     if (OH <= 0 || OW <= 0) return CG_EINVAL;
-    const size_t total = (size_t)N * C * H * W;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, dy, argmax, dx, total, H, W, OH, OW,
-                       k, s, p, accumulate);
+    if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
+    const uint32_t planes = (uint32_t)N * C;
+    const int ppb = pool_planes_per_block(H * W);
+    if (accumulate)
+        hipLaunchKernelGGL(maxpool_bwd_kernel<1>, dim3((planes + ppb - 1) / ppb), dim3(TB), 0, st, dy, argmax, dx, planes,
+                           ppb, H, W, OH, OW, k, s, p);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_kernel<0>, dim3((planes + ppb - 1) / ppb), dim3(TB), 0, st, dy, argmax, dx, planes,
+                           ppb, H, W, OH, OW, k, s, p);
     CG_LAUNCH_CHECK();
 }
 
-int lrn_fwd_launch(const float *x, float *y, float *scale, int N, int C, int HW, int size, float alpha, float beta,
-                   float kappa, hipStream_t st)
+int lrn_fwd_launch(const float *x, float *y, int N, int C, int HW, int size, float alpha, float beta, float kappa,
+                   hipStream_t st)
 {
-    if (size <= 0) return CG_EINVAL;
-    const size_t total = (size_t)N * C * HW;
-    hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, x, y, scale, total, C, HW, size,
-                       alpha / (float)size, beta, kappa);
+    if (size <= 0 || N <= 0 || C <= 0 || HW <= 0) return CG_EINVAL;
+    const float aos = alpha / (float)size;
+    const int nchunk = (C + LRN_CH - 1) / LRN_CH;
+    const dim3 grid((HW + TB - 1) / TB, (unsigned)(N * nchunk));
+    if (grid.y > 65535u && (size == 3 || size == 5 || size == 7)) return CG_EUNSUPPORTED;
+    switch (size) {
+    case 3: hipLaunchKernelGGL(lrn_fwd_stream_kernel<3>, grid, dim3(TB), 0, st, x, y, C, HW, nchunk, aos, beta, kappa); break;
+    case 5: hipLaunchKernelGGL(lrn_fwd_stream_kernel<5>, grid, dim3(TB), 0, st, x, y, C, HW, nchunk, aos, beta, kappa); break;
+    case 7: hipLaunchKernelGGL(lrn_fwd_stream_kernel<7>, grid, dim3(TB), 0, st, x, y, C, HW, nchunk, aos, beta, kappa); break;
+    default: {
+        const size_t total = (size_t)N * C * HW;
+        hipLaunchKernelGGL(lrn_fwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, x, y, total, C, HW, size, aos, beta,
+                           kappa);
+    }
+    }
     CG_LAUNCH_CHECK();
 }
 
-int lrn_bwd_launch(const float *x, const float *y, const float *scale, const float *dy, float *dx, int N, int C,
-                   int HW, int size, float alpha, float beta, int accumulate, hipStream_t st)
+int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int HW, int size, float alpha, float beta,
+                   float kappa, int accumulate, hipStream_t st)
 {
-    const size_t total = (size_t)N * C * HW;
-    hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, x, y, scale, dy, dx, total, C, HW, size,
-                       2.f * alpha * beta / (float)size, beta, accumulate);
+    if (size <= 0 || N <= 0 || C <= 0 || HW <= 0) return CG_EINVAL;
+    const float aos = alpha / (float)size, coef = 2.f * alpha * beta / (float)size;
+    const int nchunk = (C + LRN_CH - 1) / LRN_CH;
+    const dim3 grid((HW + TB - 1) / TB, (unsigned)(N * nchunk));
+    if (grid.y > 65535u && (size == 3 || size == 5 || size == 7)) return CG_EUNSUPPORTED;
+#define CG_LRN_BWD(SZ)                                                                                                \
+    do {                                                                                                              \
+        if (accumulate)                                                                                               \
+            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 1>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk, aos,  \
+                               coef, beta, kappa);                                                                    \
+        else                                                                                                          \
+            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 0>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk, aos,  \
+                               coef, beta, kappa);                                                                    \
+    } while (0)
+    switch (size) {
+    case 3: CG_LRN_BWD(3); break;
+    case 5: CG_LRN_BWD(5); break;
+    case 7: CG_LRN_BWD(7); break;
+    default: {
+        const size_t total = (size_t)N * C * HW;
+        hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, x, dy, dx, total, C, HW, size, aos,
+                           coef, beta, kappa, accumulate);
+    }
+    }
+#undef CG_LRN_BWD
     CG_LAUNCH_CHECK();
 }
 
@@ -333,7 +558,10 @@ int avgpool_bwd_launch(const float *dy, float *dx, int NC, int HW, int accumulat
 int dropout_launch(const float *x, const uint8_t *mask, float *y, size_t n, float p, int accumulate, hipStream_t st)
 {
     if (!mask || p < 0.f || p >= 1.f) return CG_EINVAL;
-    hipLaunchKernelGGL(dropout_kernel, dim3(grid_for(n)), dim3(TB), 0, st, x, mask, y, n, 1.f / (1.f - p), accumulate);
+    if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(mask) & 3u)) return CG_EINVAL;
+    const float f = 1.f / (1.f - p);
+    if (accumulate) hipLaunchKernelGGL(dropout_kernel<1>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, mask, y, n, f);
+    else hipLaunchKernelGGL(dropout_kernel<0>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, mask, y, n, f);
     CG_LAUNCH_CHECK();
 }
 

@@ -30,6 +30,12 @@ struct cg_net {
         bool upd_pending = false;             // an update of this layer was enqueued by a previous step
         bool grad_written = false;            // per step: has anything been written to this layer's gradient?
         bool needs_grad = false;              // false when no parameter lies upstream of this output
+        // A rectifier that is the only consumer of a convolution or fully-connected layer is folded
+        // into that layer's store: the producer (fused_relu) writes max(., 0) and the rectifier
+        // (alias_of = producer) shares its output buffer and launches nothing in forward.  Its
+        // backward needs only the sign, which the rectified output still carries.
+        bool fused_relu = false;
+        int alias_of = -1;
     };
     int B = 0, C = 0, H = 0, W = 0;
     std::vector<Layer> layers;
@@ -110,7 +116,6 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
         case CG_LAYER_LRN:
             ly.C = ly.inC; ly.H = ly.inH; ly.W = ly.inW;
             if (d.lrn_size <= 0 || d.lrn_size > ly.inC + 64) rc = CG_EINVAL;
-            ly.aux_elems = (size_t)B * ly.C * ly.H * ly.W;      // scale
             break;
         case CG_LAYER_MAXPOOL:
             if (d.k <= 0 || d.stride <= 0 || d.pad < 0 || d.pad >= d.k) { rc = CG_EINVAL; break; }
@@ -144,7 +149,19 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
         if (rc) break;
         ly.out_elems = (size_t)B * ly.C * ly.H * ly.W;
         if (ly.out_elems >= (1ull << 29)) { rc = CG_EUNSUPPORTED; break; }
-        ly.act_off = off; off += round_up(ly.out_elems, 64);
+        if (d.kind == CG_LAYER_RELU && d.inputs[0] >= 0) {
+            Layer &src = net->layers[d.inputs[0]];
+            int consumers = 0;
+            for (int j = 0; j < L; ++j)
+                for (int k = 0; k < descs[j].n_inputs && k < 4; ++k)
+                    if (descs[j].inputs[k] == d.inputs[0]) ++consumers;
+            if ((src.d.kind == CG_LAYER_CONV || src.d.kind == CG_LAYER_FC) && consumers == 1) {
+                src.fused_relu = true;
+                ly.alias_of = d.inputs[0];
+            }
+        }
+        if (ly.alias_of >= 0) ly.act_off = net->layers[ly.alias_of].act_off;
+        else { ly.act_off = off; off += round_up(ly.out_elems, 64); }
         ly.grad_off = off; off += round_up(ly.out_elems, 64);
         ly.aux_off = off; off += round_up(ly.aux_elems, 64);
     }
@@ -187,6 +204,12 @@ extern "C" long long cg_net_param_count(const cg_net *net, int layer)
 {
     if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
     return net->layers[layer].n_params;
+}
+
+extern "C" int cg_net_layer_fused(const cg_net *net, int layer)
+{
+    if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
+    return net->layers[layer].fused_relu ? 1 : 0;
 }
 
 extern "C" int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local, const float *const *g_peers,
@@ -263,16 +286,17 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
         switch (d.kind) {
         case CG_LAYER_CONV:
-            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, S0);
+            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, ly.fused_relu, S0);
             break;
         case CG_LAYER_FC:
             rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, scratch,
-                             scratch_bytes, S0);
+                             scratch_bytes, ly.fused_relu, S0);
             break;
-        case CG_LAYER_RELU: rc = relu_fwd_launch(in, out, in_elems, S0); break;
+        case CG_LAYER_RELU:
+            if (ly.alias_of < 0) rc = relu_fwd_launch(in, out, in_elems, S0);
+            break;
         case CG_LAYER_LRN:
-            rc = lrn_fwd_launch(in, out, base + ly.aux_off, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha,
-                                d.lrn_beta, d.lrn_kappa, S0);
+            rc = lrn_fwd_launch(in, out, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha, d.lrn_beta, d.lrn_kappa, S0);
             break;
         case CG_LAYER_MAXPOOL:
             rc = maxpool_fwd_launch(in, out, reinterpret_cast<int32_t *>(base + ly.aux_off), B, ly.inC, ly.inH,
@@ -334,8 +358,8 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             break;
         case CG_LAYER_LRN:
             if (want_dx)
-                rc = lrn_bwd_launch(in, base + ly.act_off, base + ly.aux_off, dy, dx, B, ly.C, ly.H * ly.W,
-                                    d.lrn_size, d.lrn_alpha, d.lrn_beta, accum, S0);
+                rc = lrn_bwd_launch(in, dy, dx, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha, d.lrn_beta,
+                                    d.lrn_kappa, accum, S0);
             break;
         case CG_LAYER_MAXPOOL:
             if (want_dx)

@@ -33,5 +33,10 @@ class GpuNet:
     def sync(self):
         self.s0.synchronize(); self.s1.synchronize(); torch.cuda.synchronize()
 
+    def fused(self, layer):
+        """True if this layer's own output is not materialised (the rectifier that follows is folded
+        into its store; its buffer then holds the rectifier's output)."""
+        return cg.cg_net_layer_fused(self.net, layer)
+
     def act(self, layer, which=0):
         return cg.cg_net_tensor(self.net, layer, which, self.ws)

@@ -42,6 +42,8 @@ def test_one_iteration_matches_oracle(orc32, name):
     grads, dact, _ = onet.backward(orc32, layers, t["x"], buckets, t["masks"], acts, aux)
     assert abs(float(host(gn.loss)[0]) - float(loss)) <= TOL * max(1.0, abs(float(loss)))
     for li in range(len(layers) - 1):
+        if gn.fused(li):
+            continue        # not materialised: the rectifier's output, checked at its own index, stands for it
         assert max_abs_rel(host(gn.act(li)), acts[li].ravel()) <= TOL, ("activation", li, layers[li]["kind"])
     # the library skips gradients that reach no parameter (e.g. a pool applied to the net input)
     needs = []
