@@ -144,10 +144,15 @@ int cg_net_destroy(cg_net *net);
  * 0 for layers without parameters, negative on error. */
 long long cg_net_param_count(const cg_net *net, int layer);
 
-/* 1 if the layer's own output is not materialised: a convolution or
- * fully-connected layer whose only consumer is a rectifier stores max(., 0)
- * directly, and which = 0 of cg_net_tensor() then names the rectifier's output
- * for both layers.  0 otherwise, negative on error. */
+/* Which tensors of a layer are not materialised (bit flags, 0 = all are;
+ * negative on error):
+ *  1: the layer's own output.  A convolution or fully-connected layer whose
+ *     only consumer is a rectifier stores max(., 0) directly, and which = 0 of
+ *     cg_net_tensor() then names the rectifier's output for both layers.
+ *  2: the gradient with respect to the layer's output.  The backward of a
+ *     rectifier whose only consumer is a convolution, fully-connected, LRN,
+ *     max-pool or dropout layer is folded into that consumer's backward kernel,
+ *     which writes the gradient of the rectifier's input directly. */
 int cg_net_layer_fused(const cg_net *net, int layer);
 
 /* Attach the caller-owned buffers of a parameter layer: model w, history v,

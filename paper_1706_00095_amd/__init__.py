@@ -251,7 +251,7 @@ def cg_net_layer_fused(net, layer):
     r = lib().cg_net_layer_fused(net.handle, layer)
     if r < 0:
         raise CgError(int(r), "cg_net_layer_fused")
-    return bool(r)
+    return int(r)
 
 
 def cg_net_bind(net, layer, w, v, g_local, g_peers):

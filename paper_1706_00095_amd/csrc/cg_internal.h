@@ -109,6 +109,8 @@ struct IgemmProblem {
     uint32_t groups, splits, k_per_split;
     int accumulate;           // C += result instead of C = result
     int relu;                 // C = max(result, 0) after bias (forward passes followed by a rectifier)
+    const float *gate;        // same layout as C, or NULL: result = 0 where gate <= 0 (backward-data into a
+                              // rectifier: the gradient with respect to the rectifier's input), before accumulate
 };
 
 // Validates the problem against what the kernels assume and launches it.
@@ -136,14 +138,14 @@ size_t fc_ws_bytes(int B, int IN, int OUT, int pass);
 // relu != 0: y = max(conv + bias, 0), the rectifier that follows folded into the store
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
                   size_t ws_bytes, int relu, hipStream_t stream);
-int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
+int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream);
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
                          void *ws, size_t ws_bytes, hipStream_t stream);
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
                 size_t ws_bytes, int relu, hipStream_t stream);
-int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate, void *ws,
-                     size_t ws_bytes, hipStream_t stream);
+int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, const float *gate,
+                     int accumulate, void *ws, size_t ws_bytes, hipStream_t stream);
 int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
                        size_t ws_bytes, hipStream_t stream);
 
@@ -158,16 +160,20 @@ int relu_bwd_launch(const float *x, const float *dy, float *dx, size_t n, int ac
 int pool_out_size(int H, int k, int s, int p);
 int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, int H, int W, int k, int s, int p,
                        hipStream_t st);
-int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, int N, int C, int H, int W, int k, int s,
-                       int p, int accumulate, hipStream_t st);
+// `gate` (maxpool, dropout: a pointer or NULL; LRN: a flag, the gate being its own input x): the
+// layer's input is the output of a rectifier, and dx is the gradient with respect to that
+// rectifier's input, i.e. zero wherever the gate is not positive.
+int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, const float *gate, int N, int C, int H, int W,
+                       int k, int s, int p, int accumulate, hipStream_t st);
 int lrn_fwd_launch(const float *x, float *y, int N, int C, int HW, int size, float alpha, float beta, float kappa,
                    hipStream_t st);
 // recomputes the scales from x; nothing saved by forward is read
 int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int HW, int size, float alpha, float beta,
-                   float kappa, int accumulate, hipStream_t st);
+                   float kappa, int accumulate, int gate, hipStream_t st);
 int avgpool_fwd_launch(const float *x, float *y, int NC, int HW, hipStream_t st);
 int avgpool_bwd_launch(const float *dy, float *dx, int NC, int HW, int accumulate, hipStream_t st);
-int dropout_launch(const float *x, const uint8_t *mask, float *y, size_t n, float p, int accumulate, hipStream_t st);
+int dropout_launch(const float *x, const uint8_t *mask, float *y, const float *gate, size_t n, float p, int accumulate,
+                   hipStream_t st);
 // per_sample: B floats of scratch
 int softmax_ce_launch(const float *z, const int32_t *labels, float *loss, float *dz, float *per_sample, int B, int C,
                       hipStream_t st);

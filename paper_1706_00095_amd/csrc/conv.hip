@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__r
 __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_desc d, int OH, int OW,
                                                                const float *__restrict__ dy,
                                                                const float *__restrict__ w, float *__restrict__ dx,
-                                                               int accumulate)
+                                                               const float *__restrict__ gate, int accumulate)
 {
     const int Cg = d.C / d.groups, Mg = d.M / d.groups;
     const size_t total = (size_t)d.N * d.C * d.H * d.W;
@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_des
                 }
             }
         }
+        if (gate && !(gate[i] > 0.f)) s = 0.f;
         dx[i] = accumulate ? dx[i] + s : s;
     }
 }
@@ -203,7 +204,7 @@ static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, cons
     return p;
 }
 
-int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, void *ws,
+int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream)
 {
     ProfTag tag("conv_bwd_data", -1);
@@ -213,7 +214,7 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     if (d.stride_h != 1 || d.stride_w != 1) {
         const size_t total = (size_t)d.N * d.C * d.H * d.W;
         const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
-        hipLaunchKernelGGL(bwd_data_strided_kernel, dim3(blocks), dim3(256), 0, stream, d, OH, OW, dy, w, dx,
+        hipLaunchKernelGGL(bwd_data_strided_kernel, dim3(blocks), dim3(256), 0, stream, d, OH, OW, dy, w, dx, gate,
                            accumulate);
         CG_HIP_TRY(hipGetLastError());
         return CG_OK;
@@ -229,8 +230,9 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
         CG_HIP_TRY(hipGetLastError());
     }
-    return igemm_run(bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate), static_cast<char *>(ws) + wt_bytes,
-                     ws_bytes - wt_bytes, stream);
+    IgemmProblem p = bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate);
+    p.gate = gate;
+    return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
 }
 
 static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *dy,
@@ -355,12 +357,14 @@ int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const fl
     return igemm_run(p, ws, ws_bytes, stream);
 }
 
-int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, int accumulate, void *ws,
-                     size_t ws_bytes, hipStream_t stream)
+int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, const float *gate,
+                     int accumulate, void *ws, size_t ws_bytes, hipStream_t stream)
 {
     ProfTag tag("fc_bwd_data", -1);
     if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
-    return igemm_run(fc_bwd_data_problem(B, IN, OUT, dy, W, dx, accumulate), ws, ws_bytes, stream);
+    IgemmProblem p = fc_bwd_data_problem(B, IN, OUT, dy, W, dx, accumulate);
+    p.gate = gate;
+    return igemm_run(p, ws, ws_bytes, stream);
 }
 
 int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
@@ -434,7 +438,7 @@ extern "C" int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const fl
 {
     if (!d || !dy || !w || !dx) return CG_EINVAL;
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return CG_EINVAL;
-    return conv_bwd_data_impl(*d, dy, w, dx, ws, ws_bytes, 0, static_cast<hipStream_t>(stream));
+    return conv_bwd_data_impl(*d, dy, w, dx, nullptr, ws, ws_bytes, 0, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const float *dy, float *dw, float *dbias,

@@ -332,6 +332,7 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
     // column li of its 32x32 sub-tile.
     float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
     const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
+    const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const uint32_t n = n0 + (uint32_t)((wn * TN + j) * 32 + li);
@@ -347,7 +348,9 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
                     float val = acc[i][j][r] + bcol;
                     if (p.bias_mode == 1) val += bias[m];
                     if (p.relu) val = fmaxf(val, 0.f);
-                    float *dst = c_base + ((int32_t)m * p.c_row_stride + coff);
+                    const int32_t idx = (int32_t)m * p.c_row_stride + coff;
+                    if (gate && !(gate[idx] > 0.f)) val = 0.f;
+                    float *dst = c_base + idx;
                     if (p.accumulate) val += *dst;
                     *dst = val;
                 }
@@ -571,6 +574,7 @@ struct FinishArgs {
     uint32_t M, N;
     FastDiv divN, divMN;
     int accumulate, relu;
+    const float *gate;
     uint32_t total;           // groups * M * N
 };
 
@@ -586,7 +590,9 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
         else if (a.bias_mode == 2) s += a.bias[(int64_t)g * a.bias_gstride + n];
         if (a.relu) s = fmaxf(s, 0.f);
         const Info ci = map_info(a.c_col, n);
-        float *dst = a.c_ptr + (int64_t)g * a.c_gstride + ((int32_t)m * a.c_row_stride + ci.off);
+        const int64_t idx = (int64_t)g * a.c_gstride + ((int32_t)m * a.c_row_stride + ci.off);
+        if (a.gate && !(a.gate[idx] > 0.f)) s = 0.f;
+        float *dst = a.c_ptr + idx;
         if (a.accumulate) s += *dst;
         *dst = s;
     }
@@ -637,7 +643,7 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
     p.c_col = linear_map(p0.N, 1);
     p.c_gstride = (int64_t)p0.M * p0.N;
     p.c_split_stride = (int64_t)p0.groups * p0.M * p0.N;
-    p.bias = nullptr; p.bias_mode = 0; p.accumulate = 0; p.relu = 0;
+    p.bias = nullptr; p.bias_mode = 0; p.accumulate = 0; p.relu = 0; p.gate = nullptr;
     p.splits = pl.splits; p.k_per_split = pl.k_per_split;
     const int rc = igemm_launch(p, stream);
     if (rc) return rc;
@@ -650,7 +656,7 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
     a.M = p0.M; a.N = p0.N;
     a.divN = make_fastdiv(p0.N);
     a.divMN = make_fastdiv(p0.M * p0.N);
-    a.accumulate = p0.accumulate; a.relu = p0.relu;
+    a.accumulate = p0.accumulate; a.relu = p0.relu; a.gate = p0.gate;
     a.total = p0.groups * p0.M * p0.N;
     const unsigned blocks = (a.total + 255) / 256 < 8192 ? (a.total + 255) / 256 : 8192;
     hipLaunchKernelGGL(splitk_finish_kernel, dim3(blocks), dim3(256), 0, stream, a);

@@ -63,11 +63,14 @@ __global__ __launch_bounds__(TB) void relu_bwd_kernel(const float *__restrict__ 
 }
 
 // Pooling kernels: a block owns `ppb` consecutive (n, c) planes, so that all index arithmetic is
-// 32-bit and local to a plane.
+// 32-bit and local to a plane.  KT/ST are the window and stride when known at compile time (the
+// divisions by the stride are most of the arithmetic otherwise), 0 = use the run-time values.
+template <int KT, int ST>
 __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                          int32_t *__restrict__ argmax, uint32_t planes, int ppb, int H,
-                                                         int W, int OH, int OW, int k, int s, int p)
+                                                         int W, int OH, int OW, int k_rt, int s_rt, int p)
 {
+    const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
     const uint32_t P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
     const uint32_t np = min((uint32_t)ppb, planes - plane0);
     for (uint32_t j = threadIdx.x; j < np * P; j += TB) {
@@ -93,26 +96,29 @@ __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict
 }
 
 // Gather form: an input element collects dy from every window that covers it and elected it.
-template <int ACC>
+// `gate`, if given, is the output of the rectifier that produced this layer's input: the result
+// is then the gradient with respect to the rectifier's INPUT (zero where the gate is not positive).
+template <int KT, int ST, int ACC>
 __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict__ dy,
                                                          const int32_t *__restrict__ argmax, float *__restrict__ dx,
-                                                         uint32_t planes, int ppb, int H, int W, int OH, int OW, int k,
-                                                         int s, int p)
+                                                         const float *__restrict__ gate, uint32_t planes, int ppb,
+                                                         int H, int W, int OH, int OW, int k_rt, int s_rt, int p)
 {
+    const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
     const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
     const uint32_t np = min((uint32_t)ppb, planes - plane0);
     for (uint32_t j = threadIdx.x; j < np * Q; j += TB) {
         const uint32_t pl = j / Q, me = j - pl * Q;
         const int ih = (int)(me / (uint32_t)W), iw = (int)(me - (uint32_t)ih * W);
         const size_t nc = (size_t)plane0 + pl;
-        // windows oh with oh*s - p <= ih <= oh*s - p + k - 1
+        // windows oh with oh*s - p <= ih <= oh*s - p + k - 1  (numerators below are >= 0 where divided)
         int oh_lo = ih + p - k + 1;
-        oh_lo = oh_lo <= 0 ? 0 : (oh_lo + s - 1) / s;
-        int oh_hi = (ih + p) / s;
+        oh_lo = oh_lo <= 0 ? 0 : (int)((uint32_t)(oh_lo + s - 1) / (uint32_t)s);
+        int oh_hi = (int)((uint32_t)(ih + p) / (uint32_t)s);
         if (oh_hi > OH - 1) oh_hi = OH - 1;
         int ow_lo = iw + p - k + 1;
-        ow_lo = ow_lo <= 0 ? 0 : (ow_lo + s - 1) / s;
-        int ow_hi = (iw + p) / s;
+        ow_lo = ow_lo <= 0 ? 0 : (int)((uint32_t)(ow_lo + s - 1) / (uint32_t)s);
+        int ow_hi = (int)((uint32_t)(iw + p) / (uint32_t)s);
         if (ow_hi > OW - 1) ow_hi = OW - 1;
         const int32_t *ap = argmax + nc * P;
         const float *gp = dy + nc * P;
@@ -122,6 +128,7 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict
                 const int o = oh * OW + ow;
                 if (ap[o] == (int32_t)me) acc += gp[o];
             }
+        if (gate && !(gate[nc * Q + me] > 0.f)) acc = 0.f;
         float *dst = dx + nc * Q + me;
         *dst = ACC ? *dst + acc : acc;
     }
@@ -176,7 +183,8 @@ __global__ __launch_bounds__(TB) void lrn_fwd_stream_kernel(const float *__restr
 // Step c (from c0 - (SIZE-1), the first SIZE-1 steps only fill the rings) lets x_e enter, e = c + SIZE - 1,
 // computes scale and t = dy x scale^(-beta-1) of channel j = c + half, whose window is now complete,
 // and emits dx_c, whose sum over j in [c - (SIZE-1-half), c + half] is the whole t ring.
-template <int SIZE, int ACC>
+// GATE: x is the output of a rectifier and dx the gradient with respect to that rectifier's input.
+template <int SIZE, int ACC, int GATE>
 __global__ __launch_bounds__(TB) void lrn_bwd_stream_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                                             float *__restrict__ dx, int C, int HW, int nchunk,
                                                             float aos, float coef, float beta, float kappa)
@@ -223,7 +231,8 @@ __global__ __launch_bounds__(TB) void lrn_bwd_stream_kernel(const float *__restr
             float cross = 0.f;
 #pragma unroll
             for (int d = 0; d < SIZE; ++d) cross += tr[d];
-            const float gval = q[0] - coef * win[0] * cross;     // x_c = x_{e-SIZE+1}: the oldest ring entry
+            float gval = q[0] - coef * win[0] * cross;           // x_c = x_{e-SIZE+1}: the oldest ring entry
+            if (GATE && !(win[0] > 0.f)) gval = 0.f;
             float *dst = dp + (size_t)c * HW;
             *dst = ACC ? *dst + gval : gval;
         }
@@ -265,7 +274,8 @@ __device__ __forceinline__ float lrn_scale_at(const float *__restrict__ x, ptrdi
 
 __global__ __launch_bounds__(TB) void lrn_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                                      float *__restrict__ dx, size_t total, int C, int HW, int size,
-                                                     float aos, float coef, float beta, float kappa, int accumulate)
+                                                     float aos, float coef, float beta, float kappa, int accumulate,
+                                                     int gate)
 {
     const int half = (size - 1) / 2;
     for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < total; i += (size_t)gridDim.x * TB) {
@@ -280,7 +290,8 @@ __global__ __launch_bounds__(TB) void lrn_bwd_kernel(const float *__restrict__ x
             cross += dy[qi] * x[qi] * pow_neg(sc, beta) / sc;
         }
         const float sc = lrn_scale_at(x, (ptrdiff_t)i, c, C, HW, size, aos, kappa);
-        const float gval = dy[i] * pow_neg(sc, beta) - coef * x[i] * cross;
+        float gval = dy[i] * pow_neg(sc, beta) - coef * x[i] * cross;
+        if (gate && !(x[i] > 0.f)) gval = 0.f;
         dx[i] = accumulate ? dx[i] + gval : gval;
     }
 }
@@ -305,9 +316,11 @@ __global__ __launch_bounds__(TB) void avgpool_bwd_kernel(const float *__restrict
     }
 }
 
+// `gate` (backward only): output of the rectifier that produced the layer's input; see maxpool_bwd_kernel
 template <int ACC>
 __global__ __launch_bounds__(TB) void dropout_kernel(const float *__restrict__ x, const uint8_t *__restrict__ mask,
-                                                     float *__restrict__ y, size_t n, float f)
+                                                     float *__restrict__ y, const float *__restrict__ gate, size_t n,
+                                                     float f)
 {
     const size_t n4 = n / 4;
     const float4 *x4 = reinterpret_cast<const float4 *>(x);
@@ -318,12 +331,17 @@ __global__ __launch_bounds__(TB) void dropout_kernel(const float *__restrict__ x
         const uchar4 m = m4[i];
         float4 r;
         r.x = m.x ? a.x * f : 0.f; r.y = m.y ? a.y * f : 0.f; r.z = m.z ? a.z * f : 0.f; r.w = m.w ? a.w * f : 0.f;
+        if (gate) {
+            const float4 g = reinterpret_cast<const float4 *>(gate)[i];
+            r.x = g.x > 0.f ? r.x : 0.f; r.y = g.y > 0.f ? r.y : 0.f; r.z = g.z > 0.f ? r.z : 0.f; r.w = g.w > 0.f ? r.w : 0.f;
+        }
         if (ACC) { const float4 o = y4[i]; r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w; }
         y4[i] = r;
     }
     if (blockIdx.x == 0 && threadIdx.x < n % 4) {
         const size_t i = n4 * 4 + threadIdx.x;
-        const float gval = mask[i] ? x[i] * f : 0.f;
+        float gval = mask[i] ? x[i] * f : 0.f;
+        if (gate && !(gate[i] > 0.f)) gval = 0.f;
         y[i] = ACC ? y[i] + gval : gval;
     }
 }
@@ -468,25 +486,41 @@ int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, 
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
     const int ppb = pool_planes_per_block(OH * OW);
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3((planes + ppb - 1) / ppb), dim3(TB), 0, st, x, y, argmax, planes, ppb, H,
-                       W, OH, OW, k, s, p);
+    const dim3 grid((planes + ppb - 1) / ppb);
+#define CG_POOL_FWD(K_, S_)                                                                                          \
+    hipLaunchKernelGGL((maxpool_fwd_kernel<K_, S_>), grid, dim3(TB), 0, st, x, y, argmax, planes, ppb, H, W, OH, OW, k, \
+                       s, p)
+    if (k == 3 && s == 2) CG_POOL_FWD(3, 2);
+    else if (k == 3 && s == 1) CG_POOL_FWD(3, 1);
+    else if (k == 2 && s == 2) CG_POOL_FWD(2, 2);
+    else CG_POOL_FWD(0, 0);
+#undef CG_POOL_FWD
     CG_LAUNCH_CHECK();
 }
 
-int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, int N, int C, int H, int W, int k, int s,
-                       int p, int accumulate, hipStream_t st)
+int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, const float *gate, int N, int C, int H, int W,
+                       int k, int s, int p, int accumulate, hipStream_t st)
 {
     const int OH = pool_out_size(H, k, s, p), OW = pool_out_size(W, k, s, p);
     if (OH <= 0 || OW <= 0) return CG_EINVAL;
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
     const int ppb = pool_planes_per_block(H * W);
-    if (accumulate)
-        hipLaunchKernelGGL(maxpool_bwd_kernel<1>, dim3((planes + ppb - 1) / ppb), dim3(TB), 0, st, dy, argmax, dx, planes,
-                           ppb, H, W, OH, OW, k, s, p);
-    else
-        hipLaunchKernelGGL(maxpool_bwd_kernel<0>, dim3((planes + ppb - 1) / ppb), dim3(TB), 0, st, dy, argmax, dx, planes,
-                           ppb, H, W, OH, OW, k, s, p);
+    const dim3 grid((planes + ppb - 1) / ppb);
+#define CG_POOL_BWD(K_, S_)                                                                                          \
+    do {                                                                                                             \
+        if (accumulate)                                                                                              \
+            hipLaunchKernelGGL((maxpool_bwd_kernel<K_, S_, 1>), grid, dim3(TB), 0, st, dy, argmax, dx, gate, planes,  \
+                               ppb, H, W, OH, OW, k, s, p);                                                          \
+        else                                                                                                         \
+            hipLaunchKernelGGL((maxpool_bwd_kernel<K_, S_, 0>), grid, dim3(TB), 0, st, dy, argmax, dx, gate, planes,  \
+                               ppb, H, W, OH, OW, k, s, p);                                                          \
+    } while (0)
+    if (k == 3 && s == 2) CG_POOL_BWD(3, 2);
+    else if (k == 3 && s == 1) CG_POOL_BWD(3, 1);
+    else if (k == 2 && s == 2) CG_POOL_BWD(2, 2);
+    else CG_POOL_BWD(0, 0);
+#undef CG_POOL_BWD
     CG_LAUNCH_CHECK();
 }
 
@@ -512,7 +546,7 @@ int lrn_fwd_launch(const float *x, float *y, int N, int C, int HW, int size, flo
 }
 
 int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int HW, int size, float alpha, float beta,
-                   float kappa, int accumulate, hipStream_t st)
+                   float kappa, int accumulate, int gate, hipStream_t st)
 {
     if (size <= 0 || N <= 0 || C <= 0 || HW <= 0) return CG_EINVAL;
     const float aos = alpha / (float)size, coef = 2.f * alpha * beta / (float)size;
@@ -521,12 +555,18 @@ int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int
     if (grid.y > 65535u && (size == 3 || size == 5 || size == 7)) return CG_EUNSUPPORTED;
 #define CG_LRN_BWD(SZ)                                                                                                \
     do {                                                                                                              \
-        if (accumulate)                                                                                               \
-            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 1>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk, aos,  \
-                               coef, beta, kappa);                                                                    \
+        if (accumulate && gate)                                                                                       \
+            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 1, 1>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk,    \
+                               aos, coef, beta, kappa);                                                               \
+        else if (accumulate)                                                                                          \
+            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 1, 0>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk,    \
+                               aos, coef, beta, kappa);                                                               \
+        else if (gate)                                                                                                \
+            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 0, 1>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk,    \
+                               aos, coef, beta, kappa);                                                               \
         else                                                                                                          \
-            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 0>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk, aos,  \
-                               coef, beta, kappa);                                                                    \
+            hipLaunchKernelGGL((lrn_bwd_stream_kernel<SZ, 0, 0>), grid, dim3(TB), 0, st, x, dy, dx, C, HW, nchunk,    \
+                               aos, coef, beta, kappa);                                                               \
     } while (0)
     switch (size) {
     case 3: CG_LRN_BWD(3); break;
@@ -535,7 +575,7 @@ int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int
     default: {
         const size_t total = (size_t)N * C * HW;
         hipLaunchKernelGGL(lrn_bwd_kernel, dim3(grid_for(total)), dim3(TB), 0, st, x, dy, dx, total, C, HW, size, aos,
-                           coef, beta, kappa, accumulate);
+                           coef, beta, kappa, accumulate, gate);
     }
     }
 #undef CG_LRN_BWD
@@ -555,13 +595,15 @@ int avgpool_bwd_launch(const float *dy, float *dx, int NC, int HW, int accumulat
     CG_LAUNCH_CHECK();
 }
 
-int dropout_launch(const float *x, const uint8_t *mask, float *y, size_t n, float p, int accumulate, hipStream_t st)
+int dropout_launch(const float *x, const uint8_t *mask, float *y, const float *gate, size_t n, float p, int accumulate,
+                   hipStream_t st)
 {
     if (!mask || p < 0.f || p >= 1.f) return CG_EINVAL;
     if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(mask) & 3u)) return CG_EINVAL;
     const float f = 1.f / (1.f - p);
-    if (accumulate) hipLaunchKernelGGL(dropout_kernel<1>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, mask, y, n, f);
-    else hipLaunchKernelGGL(dropout_kernel<0>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, mask, y, n, f);
+    if (gate && !aligned16(gate)) return CG_EINVAL;
+    if (accumulate) hipLaunchKernelGGL(dropout_kernel<1>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, mask, y, gate, n, f);
+    else hipLaunchKernelGGL(dropout_kernel<0>, dim3(grid_for(n / 4 + 1)), dim3(TB), 0, st, x, mask, y, gate, n, f);
     CG_LAUNCH_CHECK();
 }
 

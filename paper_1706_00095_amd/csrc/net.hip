@@ -36,6 +36,13 @@ struct cg_net {
         // backward needs only the sign, which the rectified output still carries.
         bool fused_relu = false;
         int alias_of = -1;
+        // Backward of a rectifier whose only consumer is a convolution, fully-connected, LRN,
+        // max-pool or dropout layer is folded into that consumer's backward kernel, which gates its
+        // result with the rectifier's output and writes the gradient of the rectifier's INPUT: the
+        // gradient with respect to the rectifier's output is never materialised (bwd_folded), and
+        // the consumer knows the rectifier by gate_from.
+        bool bwd_folded = false;
+        int gate_from = -1;
     };
     int B = 0, C = 0, H = 0, W = 0;
     std::vector<Layer> layers;
@@ -165,6 +172,23 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
         ly.grad_off = off; off += round_up(ly.out_elems, 64);
         ly.aux_off = off; off += round_up(ly.aux_elems, 64);
     }
+    if (rc == CG_OK) {
+        for (int r = 0; r < L; ++r) {
+            Layer &rl = net->layers[r];
+            if (rl.d.kind != CG_LAYER_RELU || rl.d.inputs[0] < 0 || !net->layers[rl.d.inputs[0]].needs_grad) continue;
+            int consumers = 0, who = -1;
+            for (int j = r + 1; j < L; ++j)
+                for (int k = 0; k < net->layers[j].d.n_inputs; ++k)
+                    if (net->layers[j].d.inputs[k] == r) { ++consumers; who = j; }
+            if (consumers != 1) continue;
+            const int kind = net->layers[who].d.kind;
+            const bool can = kind == CG_LAYER_CONV || kind == CG_LAYER_FC || kind == CG_LAYER_LRN ||
+                             kind == CG_LAYER_MAXPOOL || kind == CG_LAYER_DROPOUT;
+            if (!can) continue;
+            rl.bwd_folded = true;
+            net->layers[who].gate_from = r;
+        }
+    }
     if (rc == CG_OK && net->layers[L - 1].d.kind != CG_LAYER_SOFTMAX_CE) rc = CG_EINVAL;
     if (rc == CG_OK) {
         // the logits feed the loss only: its gradient is written by the loss kernel
@@ -209,7 +233,7 @@ extern "C" long long cg_net_param_count(const cg_net *net, int layer)
 extern "C" int cg_net_layer_fused(const cg_net *net, int layer)
 {
     if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
-    return net->layers[layer].fused_relu ? 1 : 0;
+    return (net->layers[layer].fused_relu ? 1 : 0) | (net->layers[layer].bwd_folded ? 2 : 0);
 }
 
 extern "C" int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local, const float *const *g_peers,
@@ -303,7 +327,7 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                                     ly.inW, d.k, d.stride, d.pad, S0);
             break;
         case CG_LAYER_AVGPOOL: rc = avgpool_fwd_launch(in, out, B * ly.inC, ly.inH * ly.inW, S0); break;
-        case CG_LAYER_DROPOUT: rc = dropout_launch(in, masks[i], out, in_elems, d.drop_p, 0, S0); break;
+        case CG_LAYER_DROPOUT: rc = dropout_launch(in, masks[i], out, nullptr, in_elems, d.drop_p, 0, S0); break;
         case CG_LAYER_CONCAT: {
             int c_off = 0;
             for (int k = 0; k < d.n_inputs && rc == CG_OK; ++k) {
@@ -330,25 +354,29 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         Layer &ly = net->layers[i];
         const cg_layer_desc &d = ly.d;
         if (!ly.needs_grad) continue;                // no parameter upstream of or inside this layer
+        if (ly.bwd_folded) continue;                 // its consumer has already written the gradient of its input
         if (!ly.grad_written) return CG_EINVAL;      // an output nobody consumed
         ProfTag tag("", i);
         const float *dy = base + ly.grad_off;
         const float *in = act(d.inputs[0]);
         const int s0 = d.inputs[0];
-        // gradient with respect to the (first) input, if anything upstream needs it
+        // gradient with respect to the (first) input, if anything upstream needs it; through a folded
+        // rectifier the target is the gradient of the rectifier's input, gated by its output
         const bool want_dx = s0 >= 0 && net->layers[s0].needs_grad;
-        float *dx = want_dx ? base + net->layers[s0].grad_off : nullptr;
-        const int accum = want_dx && net->layers[s0].grad_written ? 1 : 0;
+        const int tgt = want_dx && ly.gate_from >= 0 ? net->layers[s0].d.inputs[0] : s0;
+        const float *gate = want_dx && ly.gate_from >= 0 ? act(s0) : nullptr;
+        float *dx = want_dx ? base + net->layers[tgt].grad_off : nullptr;
+        const int accum = want_dx && net->layers[tgt].grad_written ? 1 : 0;
         const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
         switch (d.kind) {
         case CG_LAYER_CONV:
-            if (want_dx) rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, scratch, scratch_bytes, accum, S0);
+            if (want_dx) rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0);
             if (rc == CG_OK)
                 rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch, scratch_bytes, S0);
             break;
         case CG_LAYER_FC: {
             const int IN = ly.inC * ly.inH * ly.inW;
-            if (want_dx) rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, accum, scratch, scratch_bytes, S0);
+            if (want_dx) rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0);
             if (rc == CG_OK)
                 rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch, scratch_bytes, S0);
             break;
@@ -359,18 +387,18 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         case CG_LAYER_LRN:
             if (want_dx)
                 rc = lrn_bwd_launch(in, dy, dx, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha, d.lrn_beta,
-                                    d.lrn_kappa, accum, S0);
+                                    d.lrn_kappa, accum, gate != nullptr, S0);
             break;
         case CG_LAYER_MAXPOOL:
             if (want_dx)
-                rc = maxpool_bwd_launch(dy, reinterpret_cast<const int32_t *>(base + ly.aux_off), dx, B, ly.inC,
+                rc = maxpool_bwd_launch(dy, reinterpret_cast<const int32_t *>(base + ly.aux_off), dx, gate, B, ly.inC,
                                         ly.inH, ly.inW, d.k, d.stride, d.pad, accum, S0);
             break;
         case CG_LAYER_AVGPOOL:
             if (want_dx) rc = avgpool_bwd_launch(dy, dx, B * ly.inC, ly.inH * ly.inW, accum, S0);
             break;
         case CG_LAYER_DROPOUT:
-            if (want_dx) rc = dropout_launch(dy, masks[i], dx, in_elems, d.drop_p, accum, S0);
+            if (want_dx) rc = dropout_launch(dy, masks[i], dx, gate, in_elems, d.drop_p, accum, S0);
             break;
         case CG_LAYER_CONCAT: {
             int c_off = 0;
@@ -391,7 +419,7 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         default: break;
         }
         if (rc) return rc;
-        if (want_dx && d.kind != CG_LAYER_CONCAT) net->layers[s0].grad_written = true;
+        if (want_dx && d.kind != CG_LAYER_CONCAT) net->layers[tgt].grad_written = true;
 
         if (ly.n_params) {
             // the turn's second half: aggregate this layer's gradient over the ranks and update its model

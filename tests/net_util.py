@@ -36,7 +36,12 @@ class GpuNet:
     def fused(self, layer):
         """True if this layer's own output is not materialised (the rectifier that follows is folded
         into its store; its buffer then holds the rectifier's output)."""
-        return cg.cg_net_layer_fused(self.net, layer)
+        return bool(cg.cg_net_layer_fused(self.net, layer) & 1)
+
+    def grad_folded(self, layer):
+        """True if the gradient with respect to this layer's output is not materialised (a rectifier
+        whose backward is folded into its consumer's backward kernel)."""
+        return bool(cg.cg_net_layer_fused(self.net, layer) & 2)
 
     def act(self, layer, which=0):
         return cg.cg_net_tensor(self.net, layer, which, self.ws)

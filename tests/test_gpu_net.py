@@ -50,7 +50,7 @@ def test_one_iteration_matches_oracle(orc32, name):
     for ly in layers:
         needs.append(ly["kind"] in ("conv", "fc") or any(i >= 0 and needs[i] for i in ly["inputs"]))
     for li, dref in dact.items():
-        if li == len(layers) - 1 or not needs[li]:
+        if li == len(layers) - 1 or not needs[li] or gn.grad_folded(li):
             continue
         assert max_abs_rel(host(gn.act(li, 1)), dref.ravel()) <= TOL, ("gradient", li, layers[li]["kind"])
     for li in grads:
