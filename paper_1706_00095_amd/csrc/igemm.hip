@@ -578,23 +578,52 @@ struct FinishArgs {
     uint32_t total;           // groups * M * N
 };
 
-// C = (sum over K slices, in slice order) + bias, written through the problem's output map.
-__global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
+// C = (sum over the K slices) + bias, written through the problem's output map.  With few slices a
+// thread adds them in slice order.  With many (ROWS = 8) a block owns 32 consecutive elements, its
+// 8 thread rows add interleaved slices (row r: slices r, r+8, ...), and the 8 row sums are added
+// in row order.  Either way the association is fixed by the number of slices alone, so the result
+// does not depend on scheduling.
+__device__ __forceinline__ void finish_store(const FinishArgs &a, uint32_t i, float s)
 {
-    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < a.total; i += gridDim.x * 256) {
-        float s = a.part[i];
-        for (int k = 1; k < a.splits; ++k) s += a.part[(int64_t)k * a.plane + i];
-        const uint32_t g = fdiv(i, a.divMN), r = i - g * a.divMN.d;
-        const uint32_t m = fdiv(r, a.divN), n = r - m * a.divN.d;
-        if (a.bias_mode == 1) s += a.bias[(int64_t)g * a.bias_gstride + m];
-        else if (a.bias_mode == 2) s += a.bias[(int64_t)g * a.bias_gstride + n];
-        if (a.relu) s = fmaxf(s, 0.f);
-        const Info ci = map_info(a.c_col, n);
-        const int64_t idx = (int64_t)g * a.c_gstride + ((int32_t)m * a.c_row_stride + ci.off);
-        if (a.gate && !(a.gate[idx] > 0.f)) s = 0.f;
-        float *dst = a.c_ptr + idx;
-        if (a.accumulate) s += *dst;
-        *dst = s;
+    const uint32_t g = fdiv(i, a.divMN), rem = i - g * a.divMN.d;
+    const uint32_t m = fdiv(rem, a.divN), n = rem - m * a.divN.d;
+    if (a.bias_mode == 1) s += a.bias[(int64_t)g * a.bias_gstride + m];
+    else if (a.bias_mode == 2) s += a.bias[(int64_t)g * a.bias_gstride + n];
+    if (a.relu) s = fmaxf(s, 0.f);
+    const Info ci = map_info(a.c_col, n);
+    const int64_t idx = (int64_t)g * a.c_gstride + ((int32_t)m * a.c_row_stride + ci.off);
+    if (a.gate && !(a.gate[idx] > 0.f)) s = 0.f;
+    float *dst = a.c_ptr + idx;
+    if (a.accumulate) s += *dst;
+    *dst = s;
+}
+
+template <int ROWS> __global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
+{
+    if (ROWS == 1) {
+        for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < a.total; i += gridDim.x * 256) {
+            float s = a.part[i];
+            for (int k = 1; k < a.splits; ++k) s += a.part[(int64_t)k * a.plane + i];
+            finish_store(a, i, s);
+        }
+        return;
+    }
+    __shared__ float part[8][33];
+    const int el = threadIdx.x & 31, r = threadIdx.x >> 5;
+    for (uint32_t i0 = blockIdx.x * 32; i0 < a.total; i0 += gridDim.x * 32) {
+        const uint32_t i = i0 + el;
+        float s = 0.f;
+        if (i < a.total)
+            for (int k = r; k < a.splits; k += 8) s += a.part[(int64_t)k * a.plane + i];
+        part[r][el] = s;
+        __syncthreads();
+        if (r == 0 && i < a.total) {
+            s = part[0][el];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) s += part[k][el];
+            finish_store(a, i, s);
+        }
+        __syncthreads();
     }
 }
 
@@ -658,8 +687,13 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
     a.divMN = make_fastdiv(p0.M * p0.N);
     a.accumulate = p0.accumulate; a.relu = p0.relu; a.gate = p0.gate;
     a.total = p0.groups * p0.M * p0.N;
-    const unsigned blocks = (a.total + 255) / 256 < 8192 ? (a.total + 255) / 256 : 8192;
-    hipLaunchKernelGGL(splitk_finish_kernel, dim3(blocks), dim3(256), 0, stream, a);
+    if (pl.splits >= 16) {
+        const unsigned blocks = (a.total + 31) / 32 < 65536 ? (a.total + 31) / 32 : 65536;
+        hipLaunchKernelGGL(splitk_finish_kernel<8>, dim3(blocks), dim3(256), 0, stream, a);
+    } else {
+        const unsigned blocks = (a.total + 255) / 256 < 16384 ? (a.total + 255) / 256 : 16384;
+        hipLaunchKernelGGL(splitk_finish_kernel<1>, dim3(blocks), dim3(256), 0, stream, a);
+    }
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }

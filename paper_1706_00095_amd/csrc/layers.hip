@@ -62,22 +62,30 @@ __global__ __launch_bounds__(TB) void relu_bwd_kernel(const float *__restrict__ 
     }
 }
 
-// Pooling kernels: a block owns `ppb` consecutive (n, c) planes, so that all index arithmetic is
-// 32-bit and local to a plane.  KT/ST are the window and stride when known at compile time (the
-// divisions by the stride are most of the arithmetic otherwise), 0 = use the run-time values.
+// Pooling kernels: a block owns `ppb` consecutive (n, c) planes and first copies what it reads
+// (forward: the input planes; backward: dy and the winners) into LDS with coalesced loads, so
+// that the window gathers, whose addresses depend on loaded data in backward, never go to global
+// memory.  All index arithmetic is 32-bit and local to a plane.  KT/ST are the window and stride
+// when known at compile time (the divisions by the stride are most of the arithmetic otherwise),
+// 0 = use the run-time values.
+constexpr int POOL_LDS = 8192;         // elements of LDS staging per block (floats, or float + int pairs)
+
 template <int KT, int ST>
 __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                          int32_t *__restrict__ argmax, uint32_t planes, int ppb, int H,
                                                          int W, int OH, int OW, int k_rt, int s_rt, int p)
 {
+    __shared__ float xs[POOL_LDS];
     const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
-    const uint32_t P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
+    const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
     const uint32_t np = min((uint32_t)ppb, planes - plane0);
+    const float *xg = x + (size_t)plane0 * Q;
+    for (uint32_t j = threadIdx.x; j < np * Q; j += TB) xs[j] = xg[j];
+    __syncthreads();
     for (uint32_t j = threadIdx.x; j < np * P; j += TB) {
         const uint32_t pl = j / P, o = j - pl * P;
         const int oh = (int)(o / (uint32_t)OW), ow = (int)(o - (uint32_t)oh * OW);
-        const size_t nc = (size_t)plane0 + pl;
-        const float *xp = x + nc * H * W;
+        const float *xp = xs + pl * Q;
         int best = -1;
         float bv = 0.f;
         for (int kh = 0; kh < k; ++kh) {
@@ -90,8 +98,8 @@ __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict
                 if (best < 0 || val > bv) { best = ih * W + iw; bv = val; }
             }
         }
-        y[nc * P + o] = bv;
-        argmax[nc * P + o] = best;
+        y[(size_t)plane0 * P + j] = bv;
+        argmax[(size_t)plane0 * P + j] = best;
     }
 }
 
@@ -104,13 +112,19 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict
                                                          const float *__restrict__ gate, uint32_t planes, int ppb,
                                                          int H, int W, int OH, int OW, int k_rt, int s_rt, int p)
 {
+    __shared__ float gs[POOL_LDS / 2];
+    __shared__ int32_t as[POOL_LDS / 2];
     const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
     const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
     const uint32_t np = min((uint32_t)ppb, planes - plane0);
+    for (uint32_t j = threadIdx.x; j < np * P; j += TB) {
+        gs[j] = dy[(size_t)plane0 * P + j];
+        as[j] = argmax[(size_t)plane0 * P + j];
+    }
+    __syncthreads();
     for (uint32_t j = threadIdx.x; j < np * Q; j += TB) {
         const uint32_t pl = j / Q, me = j - pl * Q;
         const int ih = (int)(me / (uint32_t)W), iw = (int)(me - (uint32_t)ih * W);
-        const size_t nc = (size_t)plane0 + pl;
         // windows oh with oh*s - p <= ih <= oh*s - p + k - 1  (numerators below are >= 0 where divided)
         int oh_lo = ih + p - k + 1;
         oh_lo = oh_lo <= 0 ? 0 : (int)((uint32_t)(oh_lo + s - 1) / (uint32_t)s);
@@ -120,17 +134,17 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict
         ow_lo = ow_lo <= 0 ? 0 : (int)((uint32_t)(ow_lo + s - 1) / (uint32_t)s);
         int ow_hi = (int)((uint32_t)(iw + p) / (uint32_t)s);
         if (ow_hi > OW - 1) ow_hi = OW - 1;
-        const int32_t *ap = argmax + nc * P;
-        const float *gp = dy + nc * P;
+        const int32_t *ap = as + pl * P;
+        const float *gp = gs + pl * P;
         float acc = 0.f;
         for (int oh = oh_lo; oh <= oh_hi; ++oh)
             for (int ow = ow_lo; ow <= ow_hi; ++ow) {
                 const int o = oh * OW + ow;
                 if (ap[o] == (int32_t)me) acc += gp[o];
             }
-        if (gate && !(gate[nc * Q + me] > 0.f)) acc = 0.f;
-        float *dst = dx + nc * Q + me;
-        *dst = ACC ? *dst + acc : acc;
+        const size_t gi = (size_t)plane0 * Q + j;
+        if (gate && !(gate[gi] > 0.f)) acc = 0.f;
+        dx[gi] = ACC ? dx[gi] + acc : acc;
     }
 }
 
@@ -439,11 +453,14 @@ __global__ __launch_bounds__(TB) void fc_bias_grad_kernel(const float *__restric
         return CG_OK;                      \
     } while (0)
 
-// planes per block of the pooling kernels: about four elements per thread
-static int pool_planes_per_block(int plane_elems)
+// planes per block of the pooling kernels: about four elements per thread (`work` per plane),
+// and no more than fit the LDS staging (`staged` elements per plane of at most `cap`)
+static int pool_planes_per_block(int work, int staged, int cap)
 {
-    const int ppb = 1024 / (plane_elems > 0 ? plane_elems : 1);
-    return ppb < 1 ? 1 : ppb;
+    int ppb = 1024 / (work > 0 ? work : 1);
+    if (ppb < 1) ppb = 1;
+    while (ppb > 1 && ppb * staged > cap) --ppb;
+    return ppb;
 }
 
 int pool_out_size(int H, int k, int s, int p)
@@ -485,7 +502,8 @@ int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, 
     if (OH <= 0 || OW <= 0 || p >= k) return CG_EINVAL;
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
-    const int ppb = pool_planes_per_block(OH * OW);
+    if (H * W > POOL_LDS) return CG_EUNSUPPORTED;        // one input plane must fit the LDS staging
+    const int ppb = pool_planes_per_block(OH * OW, H * W, POOL_LDS);
     const dim3 grid((planes + ppb - 1) / ppb);
 #define CG_POOL_FWD(K_, S_)                                                                                          \
     hipLaunchKernelGGL((maxpool_fwd_kernel<K_, S_>), grid, dim3(TB), 0, st, x, y, argmax, planes, ppb, H, W, OH, OW, k, \
@@ -505,7 +523,8 @@ int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, const 
     if (OH <= 0 || OW <= 0) return CG_EINVAL;
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
-    const int ppb = pool_planes_per_block(H * W);
+    if (OH * OW > POOL_LDS / 2) return CG_EUNSUPPORTED;
+    const int ppb = pool_planes_per_block(H * W, OH * OW, POOL_LDS / 2);
     const dim3 grid((planes + ppb - 1) / ppb);
 #define CG_POOL_BWD(K_, S_)                                                                                          \
     do {                                                                                                             \
