@@ -94,6 +94,31 @@ struct Operand {
                           // pointer so that both per-index offsets are non-negative
 };
 
+// Operand B of a convolution seen as raw image patches instead of gathered im2col rows.  The N
+// rows of B are output pixels (img, oy, ox) of a grid OHo x OWo; the reduction index is
+// (tap t = ky*KW + kx, channel c), tap-major, with Cred % 16 == 0 channels per group; element
+// (pixel, t, c) is src[img][group*Cred + c][oy*s + oy0 + py(t)][ox*s + ox0 + px(t)] or zero outside
+// the Hs x Ws plane, where (py, px) = (ky, kx) in forward and (KH-1-ky, KW-1-kx) in backward-data.
+// The kernel keeps, per block of 128 pixels and 16 channels, the padded source rows those pixels'
+// windows touch in LDS and reads each tap's operand fragment from there at a per-tap offset.
+struct PatchGeom {
+    const float *src;
+    uint64_t src_elems;       // floats behind src
+    int64_t gstride;          // elements between groups: Cred * Hs * Ws
+    uint32_t Cred;
+    int32_t Hs, Ws, chan_stride;
+    int32_t img_stride;       // Ctot * Hs * Ws (elements)
+    int32_t OHo, OWo, s, oy0, ox0, KH, KW;
+    int32_t Wp;               // padded patch width: (OWo-1)*s + KW
+    int32_t Rfull;            // slots of a whole image: ((OHo-1)*s + KH) * Wp
+    int32_t flip;             // 0: (py, px) = (ky, kx); 1: mirrored taps
+    FastDiv divP, divOW, divWp, divRfull;
+    int32_t nsl;              // 64-slot chunks per channel the kernel instance stages (4 or 5); 0 = not usable
+    int32_t tiles_per_img;    // 0: blocks own 128 consecutive pixels across image boundaries; > 0: every image is
+                              // cut into this many blocks of its own (smaller patches for large images)
+    FastDiv divTpi;
+};
+
 // C[m][n] = sum_k A(m,k) * B(n,k)   (+ bias), for `groups` independent problems, the K range
 // optionally cut into `splits` slices whose partial results go to consecutive output planes.
 struct IgemmProblem {
@@ -111,7 +136,13 @@ struct IgemmProblem {
     int relu;                 // C = max(result, 0) after bias (forward passes followed by a rectifier)
     const float *gate;        // same layout as C, or NULL: result = 0 where gate <= 0 (backward-data into a
                               // rectifier: the gradient with respect to the rectifier's input), before accumulate
+    int use_patch;            // B is described by `patch` (and A is the matching tap-major matrix); B unused
+    PatchGeom patch;
 };
+
+// Fills the derived fields of a patch description (Wp, Rfull, dividers) and decides whether the
+// patch kernel can run it for N output pixels and M rows: sets g.nsl, returns true if usable.
+bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups);
 
 // Validates the problem against what the kernels assume and launches it.
 int igemm_launch(const IgemmProblem &p, hipStream_t stream);

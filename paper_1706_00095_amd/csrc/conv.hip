@@ -59,6 +59,25 @@ __global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__r
     }
 }
 
+// Filters as the tap-major matrix the patch kernel multiplies with: dst[g][r][t][c], t = kh*KW + kw.
+// Forward (bwd = 0): r = output channel, c = input channel: dst = w[g*Mg + r][c][t].
+// Backward-data (bwd = 1): r = input channel, c = output channel: dst = w[g*Mg + c][r][t].
+__global__ __launch_bounds__(256) void permute_filters_kernel(const float *__restrict__ w, float *__restrict__ dst,
+                                                              int G, int Mg, int Cg, int KK, int bwd)
+{
+    const int R = bwd ? Cg : Mg, Cr = bwd ? Mg : Cg;
+    const size_t total = (size_t)G * Mg * Cg * KK;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int c = (int)(i % Cr);
+        size_t q = i / Cr;
+        const int t = (int)(q % KK); q /= KK;
+        const int r = (int)(q % R);
+        const int g = (int)(q / R);
+        const int m = bwd ? c : r, ci = bwd ? r : c;
+        dst[i] = w[(((size_t)g * Mg + m) * Cg + ci) * KK + t];
+    }
+}
+
 // General-stride backward-data, gather form, one thread per dx element.  Only the taps with
 // (ih + p - kh) divisible by the stride contribute.
 __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_desc d, int OH, int OW,
@@ -148,6 +167,58 @@ static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const flo
     return p;
 }
 
+// Describes x as the patch operand of the forward pass; true if the patch kernel can run it.
+static bool fwd_patch(const cg_conv_desc &d, int OH, int OW, const float *x, IgemmProblem &p)
+{
+    if (d.stride_h != d.stride_w) return false;
+    const int G = d.groups, Cg = d.C / G;
+    PatchGeom g{};
+    g.src = x; g.src_elems = (uint64_t)d.N * d.C * d.H * d.W;
+    g.gstride = (int64_t)Cg * d.H * d.W;
+    g.Cred = (uint32_t)Cg; g.Hs = d.H; g.Ws = d.W; g.chan_stride = d.H * d.W; g.img_stride = d.C * d.H * d.W;
+    g.OHo = OH; g.OWo = OW; g.s = d.stride_h; g.oy0 = -d.pad_h; g.ox0 = -d.pad_w; g.KH = d.KH; g.KW = d.KW; g.flip = 0;
+    if (!patch_plan(g, (uint32_t)(d.M / G), (uint32_t)d.N * OH * OW, (uint32_t)G)) return false;
+    p.patch = g; p.use_patch = 1;
+    return true;
+}
+
+// dy as the patch operand of backward-data at stride 1 (pixels = input positions, mirrored taps)
+static bool bwd_data_patch(const cg_conv_desc &d, int OH, int OW, const float *dy, IgemmProblem &p)
+{
+    const int G = d.groups, Mg = d.M / G;
+    PatchGeom g{};
+    g.src = dy; g.src_elems = (uint64_t)d.N * d.M * OH * OW;
+    g.gstride = (int64_t)Mg * OH * OW;
+    g.Cred = (uint32_t)Mg; g.Hs = OH; g.Ws = OW; g.chan_stride = OH * OW; g.img_stride = d.M * OH * OW;
+    g.OHo = d.H; g.OWo = d.W; g.s = 1; g.oy0 = d.pad_h - (d.KH - 1); g.ox0 = d.pad_w - (d.KW - 1);
+    g.KH = d.KH; g.KW = d.KW; g.flip = 1;
+    if (!patch_plan(g, (uint32_t)(d.C / G), (uint32_t)d.N * d.H * d.W, (uint32_t)G)) return false;
+    p.patch = g; p.use_patch = 1;
+    return true;
+}
+
+static int permute_filters(const float *w, float *dst, int G, int Mg, int Cg, int KK, int bwd, hipStream_t stream)
+{
+    const size_t total = (size_t)G * Mg * Cg * KK;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(permute_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, dst, G, Mg, Cg, KK, bwd);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
+// operand A = a plain row-major [rows][K] matrix per group
+static void tap_major_filters(IgemmProblem &p, const float *m, int rows, int K, uint64_t elems)
+{
+    p.A = Operand{};
+    p.A.ptr = m;
+    p.A.row = linear_map((uint32_t)rows, K);
+    p.A.k = linear_map((uint32_t)K, 1);
+    p.A.limA = p.A.limB = 1;
+    p.A.gstride = (int64_t)rows * K;
+    p.A.elems = elems;
+    p.A.lanes_k = 1;
+}
+
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
                   size_t ws_bytes, int relu, hipStream_t stream)
 {
@@ -157,6 +228,16 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
     if (rc) return rc;
     IgemmProblem p = fwd_problem(d, OH, OW, x, w, bias, y);
     p.relu = relu;
+    if (fwd_patch(d, OH, OW, x, p)) {
+        const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW;
+        const size_t wt_bytes = round256((size_t)d.M * Cg * KK * sizeof(float));
+        if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
+        if (!aligned16(ws)) return CG_EINVAL;
+        const int rc2 = permute_filters(w, static_cast<float *>(ws), G, Mg, Cg, KK, 0, stream);
+        if (rc2) return rc2;
+        tap_major_filters(p, static_cast<const float *>(ws), Mg, Cg * KK, (uint64_t)d.M * Cg * KK);
+        return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
+    }
     return igemm_run(p, ws, ws_bytes, stream);
 }
 
@@ -225,6 +306,16 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     if (!aligned16(ws)) return CG_EINVAL;
     float *wt = static_cast<float *>(ws);
     {
+        IgemmProblem pp = bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate);
+        pp.gate = gate;
+        if (bwd_data_patch(d, OH, OW, dy, pp)) {
+            const int rc2 = permute_filters(w, wt, G, Mg, Cg, KK, 1, stream);
+            if (rc2) return rc2;
+            tap_major_filters(pp, wt, Cg, Mg * KK, (uint64_t)d.M * Cg * KK);
+            return igemm_run(pp, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
+        }
+    }
+    {
         const size_t total = (size_t)d.M * Cg * KK;
         const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
         hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
@@ -288,7 +379,11 @@ size_t conv_ws_bytes(const cg_conv_desc &d, int pass)
 {
     int OH, OW;
     if (conv_check(&d, &OH, &OW)) return 0;
-    if (pass == CG_PASS_FWD) return igemm_ws_bytes(fwd_problem(d, OH, OW, nullptr, nullptr, nullptr, nullptr));
+    if (pass == CG_PASS_FWD) {
+        IgemmProblem p = fwd_problem(d, OH, OW, nullptr, nullptr, nullptr, nullptr);
+        if (fwd_patch(d, OH, OW, nullptr, p)) return round256((size_t)d.M * (d.C / d.groups) * d.KH * d.KW * sizeof(float));
+        return igemm_ws_bytes(p);
+    }
     if (pass == CG_PASS_BWD_DATA) {
         if (d.stride_h != 1 || d.stride_w != 1) return 0;
         return round256((size_t)d.M * (d.C / d.groups) * d.KH * d.KW * sizeof(float)) +

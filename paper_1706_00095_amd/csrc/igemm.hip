@@ -245,6 +245,42 @@ __device__ __forceinline__ BufferRsrc operand_rsrc(const Operand &op, uint32_t g
     return r;
 }
 
+// Epilogue of both kernels: a wave's TM x TN accumulator tiles, whose first row / column are
+// (mw, nw), go to C (columns below n_end) with bias, rectifier, gate and accumulation applied.  Accumulator register r of
+// lane (h, li) holds C row 8*(r/4) + 4*h + r%4, column li of its 32x32 sub-tile.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&acc)[TM][TN], uint32_t g, uint32_t sp,
+                                           uint32_t mw, uint32_t nw, uint32_t n_end, int h, int li)
+{
+    float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
+    const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
+    const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const uint32_t n = nw + (uint32_t)(j * 32 + li);
+        if (n >= n_end) continue;
+        const int32_t coff = map_info(p.c_col, n).off;
+        const float bcol = p.bias_mode == 2 ? bias[n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t m = mw + (uint32_t)(i * 32 + (r >> 2) * 8 + h * 4 + (r & 3));
+                if (m < p.M) {
+                    float val = acc[i][j][r] + bcol;
+                    if (p.bias_mode == 1) val += bias[m];
+                    if (p.relu) val = fmaxf(val, 0.f);
+                    const int32_t idx = (int32_t)m * p.c_row_stride + coff;
+                    if (gate && !(gate[idx] > 0.f)) val = 0.f;
+                    float *dst = c_base + idx;
+                    if (p.accumulate) val += *dst;
+                    *dst = val;
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 template <int WM, int WN, int TM, int TN, int NST, class LA, class LB>
@@ -328,35 +364,188 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
     // the padding tiles still in flight write into this block's LDS: let them finish before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // Epilogue.  Accumulator register r of lane (h, li) holds C row 8*(r/4) + 4*h + r%4,
-    // column li of its 32x32 sub-tile.
-    float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
-    const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
-    const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
+    store_tile<TM, TN>(p, acc, g, sp, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), p.N, h, li);
+}
+
+// ---- patch kernel: convolutions whose B operand is staged as raw padded image rows ---------------
+//
+// The gathered im2col tile of the kernel above re-reads every input element once per filter tap
+// (9 or 25 times), and the address pipeline, one load instruction per 64 elements, is what limits
+// it.  Here a block keeps, for its 128 output pixels and 16 reduction channels at a time, the
+// zero-padded source rows those pixels' windows touch ("patch", PatchGeom in cg_internal.h) in
+// LDS, loaded once per channel block, and multiplies tap after tap from it: the B fragment of
+// pixel p, tap t, channel c is  patch[c][sigma(p) + tapoff(t)],  sigma fixed per lane for the
+// whole kernel and tapoff uniform per tap.  The reduction runs tap-major inside a channel block:
+// K-tile number cb*KK + t holds tap t of channels 16cb..16cb+15, and operand A is the filter
+// matrix permuted to [row][tap][channel], whose tiles the aligned-quad loader fetches.
+//
+// Pipeline: A tiles in a ring of NSTA stages as above.  The patch is double buffered; the loads
+// of channel block cb+1 are issued during the first K-tile (t = 0) of channel block cb, part by
+// part behind the MFMA steps and so interleaved with the loads of A tile t + NSTA-1.  The count a
+// wave may leave outstanding at a tile's barrier is (NSTA-2) A tiles, plus the patch loads while
+// the awaited A tile is older than all of them, t = 1..NSTA-2; from t = NSTA-1 on the wait covers
+// the patch too, long before the next channel block starts (KK >= 5 > NSTA-1).
+
+template <int NSL> struct PatchB {
+    static constexpr int CS = NSL * 64 + 8;          // LDS floats between channels (+8: lane halves on different banks)
+    static constexpr int BUF = 16 * CS;              // one buffer: 16 channels
+    static constexpr int NB = 4 * NSL;               // load instructions per wave and channel block
+};
+
+template <int WM, int WN, int TM, int TN, int NSTA, int NSL>
+__global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem p)
+{
+    static_assert(WM * WN == 4 && WN * TN == 4, "four waves, 128 pixels per block");
+    constexpr int MT = WM * TM * 32, NT = 128;
+    using LA = KLoader4<MT>;
+    using PB = PatchB<NSL>;
+    constexpr int LAW = LA::LPT, NB = PB::NB;
+    static_assert((NSTA - 1) * LAW + NB <= 63, "the vector-memory counter holds 63 loads");
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];     // [NSTA][LA::SZ] then [2][PB::BUF]
+    float *const sB = smem + NSTA * LA::SZ;
+
+    const PatchGeom &pg = p.patch;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t m0 = blockIdx.y * MT, g = blockIdx.z;
+    const int KK = pg.KH * pg.KW, ncb = (int)(pg.Cred / 16), n_iter = ncb * KK;
+    // this block's pixels n0..n1
+    const uint32_t P = pg.divP.d;
+    uint32_t n0, n1;
+    if (pg.tiles_per_img) {
+        const uint32_t b = fdiv(blockIdx.x, pg.divTpi), ti = blockIdx.x - b * pg.divTpi.d;
+        n0 = b * P + ti * NT;
+        n1 = min(n0 + NT - 1, (b + 1) * P - 1);
+    } else {
+        n0 = blockIdx.x * NT;
+        n1 = min(n0 + NT - 1, p.N - 1);
+    }
+
+    const BufferRsrc rsrcA = operand_rsrc(p.A, g);
+    BufferRsrc rsrcB;
+    {
+        const uint64_t base = (uint64_t)reinterpret_cast<uintptr_t>(pg.src) + (uint64_t)((int64_t)g * pg.gstride * 4);
+        rsrcB.x = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        rsrcB.y = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+        rsrcB.z = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)pg.src_elems - (int64_t)g * pg.gstride) * 4));
+        rsrcB.w = 0x00020000u;
+    }
+    LA la;
+    la.init(p.A, m0, p.M, wave, lane);
+
+    // ---- where this block's pixels sit: images bA..bB, pixel rows oyA (in bA) .. oyB (in bB) -------
+    const uint32_t bA = fdiv(n0, pg.divP), oyA = fdiv(n0 - bA * P, pg.divOW);
+    const uint32_t bB = fdiv(n1, pg.divP), oyB = fdiv(n1 - bB * P, pg.divOW);
+    // slots of the first image's segment; later images start at R0 + (d-1)*Rfull
+    const int32_t R0 = (int32_t)((((bA == bB) ? oyB : (uint32_t)pg.OHo - 1) - oyA) * pg.s + pg.KH) * pg.Wp;
+
+    // global byte offset of every patch slot this lane loads (or out of range: padding, unused slots)
+    uint32_t voff[NSL];
+#pragma unroll
+    for (int e = 0; e < NSL; ++e) {
+        const int32_t j = e * 64 + lane;
+        const uint32_t d = j < R0 ? 0u : 1u + fdiv((uint32_t)(j - R0), pg.divRfull);
+        const int32_t local = j - (d == 0 ? 0 : R0 + (int32_t)(d - 1) * pg.Rfull);
+        const uint32_t r = fdiv((uint32_t)local, pg.divWp), c = (uint32_t)local - r * (uint32_t)pg.Wp;
+        const uint32_t b = bA + d, oylo = d == 0 ? oyA : 0u;
+        const uint32_t oyhi = b == bB ? oyB : (uint32_t)pg.OHo - 1;
+        const int32_t sy = (int32_t)(oylo * pg.s) + pg.oy0 + (int32_t)r, sx = pg.ox0 + (int32_t)c;
+        const bool ok = b <= bB && r < (oyhi - oylo) * pg.s + pg.KH && (uint32_t)sy < (uint32_t)pg.Hs &&
+                        (uint32_t)sx < (uint32_t)pg.Ws;
+        voff[e] = ok ? (uint32_t)((int32_t)b * pg.img_stride + sy * pg.Ws + sx) * 4u : OOB_ROW;
+    }
+
+    const int wm = wave / WN, wn = wave % WN;
+    const int h = lane >> 5, li = lane & 31;
+    // sigma of this lane's pixels (floats into a patch buffer), with the lane half's channel offset folded in
+    int32_t sig[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const uint32_t n = n0 + (uint32_t)((wn * TN + j) * 32 + li);
-        if (n >= p.N) continue;
-        const int32_t coff = map_info(p.c_col, n).off;
-        const float bcol = p.bias_mode == 2 ? bias[n] : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint32_t m = m0 + (uint32_t)((wm * TM + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3));
-                if (m < p.M) {
-                    float val = acc[i][j][r] + bcol;
-                    if (p.bias_mode == 1) val += bias[m];
-                    if (p.relu) val = fmaxf(val, 0.f);
-                    const int32_t idx = (int32_t)m * p.c_row_stride + coff;
-                    if (gate && !(gate[idx] > 0.f)) val = 0.f;
-                    float *dst = c_base + idx;
-                    if (p.accumulate) val += *dst;
-                    *dst = val;
-                }
-            }
+        int32_t sg = 0;
+        if (n <= n1) {
+            const uint32_t b = fdiv(n, pg.divP), rem = n - b * P, oy = fdiv(rem, pg.divOW), ox = rem - oy * pg.divOW.d;
+            const uint32_t d = b - bA, oylo = d == 0 ? oyA : 0u;
+            sg = (d == 0 ? 0 : R0 + (int32_t)(d - 1) * pg.Rfull) + (int32_t)((oy - oylo) * pg.s) * pg.Wp + (int32_t)(ox * pg.s);
         }
+        sig[j] = sg + 4 * h * PB::CS;
     }
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // part P of the patch loads of channel block cb: load q = (channel wave + 4*(q/NSL), chunk q%NSL)
+    auto issue_patch_part = [&](auto PC, int cb) {
+        constexpr int Pn = decltype(PC)::value;
+        float *buf = sB + (cb & 1) * PB::BUF;
+#pragma unroll
+        for (int q = Pn * NB / NPART; q < (Pn + 1) * NB / NPART; ++q) {
+            const int cl = wave + 4 * (q / NSL), e = q % NSL;
+            load_to_lds(rsrcB, buf + cl * PB::CS + e * 64, voff[e], (uint32_t)((cb * 16 + cl) * pg.chan_stride) * 4u);
+        }
+    };
+    // part P of the A loads of K-tile `tile` = (cb, t); tiles past the end are all padding
+    auto issue_a_part = [&](auto PC, int tile, int cb, int t) {
+        constexpr int Pn = decltype(PC)::value;
+        const uint32_t k0 = (uint32_t)t * pg.Cred + (uint32_t)cb * 16u;
+        la.template issue_part<Pn>(rsrcA, smem + (tile % NSTA) * LA::SZ, p.A, k0, tile < n_iter ? p.K : 0u, wave, lane);
+    };
+
+    // prologue: the first patch, then A tiles 0..NSTA-2
+    static_for<0, NPART>([&](auto PC) { issue_patch_part(PC, 0); });
+    int icb = 0, it_ = 0;                       // (cb, t) of the next A tile to issue
+    auto advance_issue = [&]() { if (++it_ == KK) { it_ = 0; ++icb; } };
+#pragma unroll
+    for (int d = 0; d < NSTA - 1; ++d) {
+        static_for<0, NPART>([&](auto PC) { issue_a_part(PC, d, icb, it_); });
+        advance_issue();
+    }
+
+    int ccb = 0, ct = 0, cky = 0, ckx = 0;      // (cb, t = cky*KW + ckx) of the tile being multiplied
+    for (int it = 0; it < n_iter; ++it) {
+        const bool burst = ccb + 1 < ncb;       // this channel block issues the next one's patch in its tile 0
+        if (burst && ct >= 1 && ct <= NSTA - 2)
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTA - 2) * LAW + NB) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTA - 2) * LAW) : "memory");
+        const float *a_s = smem + (it % NSTA) * LA::SZ;
+        const int py = pg.flip ? pg.KH - 1 - cky : cky, px = pg.flip ? pg.KW - 1 - ckx : ckx;
+        const float *b_s = sB + (ccb & 1) * PB::BUF + (py * pg.Wp + px);
+        float af[KT / 8][TM][4], bf[KT / 8][TN][4];
+#pragma unroll
+        for (int ks = 0; ks < KT / 8; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[ks][i]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) bf[ks][j][t] = b_s[sig[j] + (8 * ks + t) * PB::CS];
+        }
+        const bool do_patch = burst && ct == 0;
+        static_for<0, NPART>([&](auto PC) {
+            constexpr int Pn = decltype(PC)::value, ks = Pn / 4, s4 = Pn % 4;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
+            issue_a_part(PC, it + NSTA - 1, icb, it_);
+            if (do_patch) issue_patch_part(PC, ccb + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        advance_issue();
+        if (++ckx == pg.KW) { ckx = 0; ++cky; }
+        if (++ct == KK) { ct = 0; cky = 0; ++ccb; }
+    }
+    // the padding tiles still in flight write into this block's LDS: let them finish before it is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    store_tile<TM, TN>(p, acc, g, 0u, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), n1 + 1, h, li);
 }
 
 namespace {
@@ -484,6 +673,107 @@ int normalise_operand(Operand &o, uint32_t groups)
 
 }  // namespace
 
+namespace {
+
+template <int TM, int NSTA, int NSL>
+int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
+{
+    constexpr int MT = 2 * TM * 32;
+    using LA = KLoader4<MT>;
+    const uint32_t P = p.patch.divP.d;
+    dim3 grid(p.patch.tiles_per_img ? (p.N / P) * (uint32_t)p.patch.tiles_per_img : (p.N + 127) / 128, (p.M + MT - 1) / MT,
+              p.groups);
+    if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
+    int rec = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof name, "igemm_patch_kernel<%dx128,%d>", MT, NSL);
+        rec = prof_begin(name, 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
+    }
+    constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL>::BUF) * sizeof(float);
+    static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL>), grid, dim3(256), lds, stream, p);
+    prof_end(rec, stream);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
+// row-tile height of the patch kernel: 64, 128 or 192 rows
+int patch_mt(uint32_t M, uint32_t N, uint32_t groups)
+{
+    const int mt = pick_mt(M, N, groups);
+    return mt >= 192 && mt != 256 ? 192 : mt >= 96 ? 128 : 64;
+}
+
+int patch_launch(const IgemmProblem &p, hipStream_t stream)
+{
+    const int mt = patch_mt(p.M, p.N, p.groups);
+    if (p.patch.nsl == 4) {
+        if (mt == 192) return launch_patch_cfg<3, 3, 4>(p, stream);
+        if (mt == 128) return launch_patch_cfg<2, 4, 4>(p, stream);
+        return launch_patch_cfg<1, 4, 4>(p, stream);
+    }
+    if (mt == 192) return launch_patch_cfg<3, 3, 5>(p, stream);
+    if (mt == 128) return launch_patch_cfg<2, 4, 5>(p, stream);
+    return launch_patch_cfg<1, 4, 5>(p, stream);
+}
+
+}  // namespace
+
+bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
+{
+    g.nsl = 0;
+    const int KK = g.KH * g.KW;
+    if (g.Cred == 0 || g.Cred % 16 || KK < 5 || g.s <= 0 || g.OHo <= 0 || g.OWo <= 0) return false;
+    if (g.src_elems * 4 > kMaxBufferBytes || N >= (1u << 30)) return false;
+    g.Wp = (g.OWo - 1) * g.s + g.KW;
+    const int64_t rfull = (int64_t)((g.OHo - 1) * g.s + g.KH) * g.Wp;
+    if (rfull >= (1 << 24)) return false;
+    g.Rfull = (int32_t)rfull;
+    const uint32_t P = (uint32_t)g.OHo * (uint32_t)g.OWo;
+    g.divP = make_fastdiv(P);
+    g.divOW = make_fastdiv((uint32_t)g.OWo);
+    g.divWp = make_fastdiv((uint32_t)g.Wp);
+    g.divRfull = make_fastdiv((uint32_t)g.Rfull);
+    // enough tiles to fill the chip without cutting K (the patch kernel has no K slices)
+    const int mt = patch_mt(M, N, groups);
+    if ((uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups < 512) return false;
+    // The largest patch any block needs: a fragment read reaches (KH-1)*Wp + KW-1 beyond sigma, and
+    // sigma + that stays below the slot count of the block's segments, which is what is counted.
+    auto slots = [&](uint32_t n0, uint32_t n1) {
+        const uint32_t bA = n0 / P, oyA = (n0 % P) / (uint32_t)g.OWo, bB = n1 / P, oyB = (n1 % P) / (uint32_t)g.OWo;
+        if (bA == bB) return (int64_t)((oyB - oyA) * g.s + g.KH) * g.Wp;
+        return (int64_t)(((uint32_t)g.OHo - 1 - oyA) * g.s + g.KH) * g.Wp + (int64_t)(bB - bA - 1) * g.Rfull +
+               (int64_t)(oyB * g.s + g.KH) * g.Wp;
+    };
+    int64_t smax = 0;
+    for (uint32_t n0 = 0; n0 < N; n0 += 128) {
+        const int64_t sl = slots(n0, (n0 + 127 < N - 1) ? n0 + 127 : N - 1);
+        if (sl > smax) smax = sl;
+    }
+    g.tiles_per_img = 0;
+    g.divTpi = make_fastdiv(1);
+    if (smax <= 4 * 64) { g.nsl = 4; return true; }
+    // large images: blocks that stay inside one image need smaller patches (every image is the same)
+    if (N % P) return false;
+    int64_t amax = 0;
+    for (uint32_t n0 = 0; n0 < P; n0 += 128) {
+        const int64_t sl = slots(n0, (n0 + 127 < P - 1) ? n0 + 127 : P - 1);
+        if (sl > amax) amax = sl;
+    }
+    if (amax > 5 * 64) return false;
+    g.nsl = 5;
+    g.tiles_per_img = (int32_t)((P + 127) / 128);
+    g.divTpi = make_fastdiv((uint32_t)g.tiles_per_img);
+    return true;
+}
+
 FastDiv make_fastdiv(uint32_t d)
 {
     // mul = ceil(2^(31+L) / d) with L = ceil(log2 d): exact quotients for all n < 2^31.
@@ -530,7 +820,6 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     if (!p.c_ptr || !aligned16(p.c_ptr)) return CG_EINVAL;
     if (p.M == 0 || p.N == 0 || p.K == 0 || p.groups == 0 || p.splits == 0) return CG_EINVAL;
     if (p.M >= (1u << 30) || p.N >= (1u << 30) || p.K >= (1u << 30)) return CG_EUNSUPPORTED;
-    if (p.A.row.count != p.M || p.B.row.count != p.N || p.A.k.count != p.K || p.B.k.count != p.K) return CG_EINVAL;
     if (p.splits > 1 && (p.k_per_split % KT != 0)) return CG_EINVAL;
     if ((uint64_t)p.k_per_split * p.splits < p.K || (uint64_t)p.k_per_split * (p.splits - 1) >= p.K) return CG_EINVAL;
     if (p.bias_mode && !p.bias) return CG_EINVAL;
@@ -538,6 +827,13 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     p.A.shift = p.B.shift = 0;
     int rc = normalise_operand(p.A, p.groups);
     if (rc) return rc;
+    if (p.use_patch) {
+        if (!p.patch.src || !aligned16(p.patch.src) || p.patch.nsl == 0 || p.splits != 1 || !quad_ok(p.A, p.K) ||
+            p.K != p.patch.Cred * (uint32_t)(p.patch.KH * p.patch.KW))
+            return CG_EINVAL;
+        return patch_launch(p, stream);
+    }
+    if (p.A.row.count != p.M || p.B.row.count != p.N || p.A.k.count != p.K || p.B.k.count != p.K) return CG_EINVAL;
     rc = normalise_operand(p.B, p.groups);
     if (rc) return rc;
     if (!p.A.check) { p.A.limA = p.A.limB = 1; }
@@ -652,12 +948,12 @@ SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups)
 
 size_t igemm_ws_bytes(const IgemmProblem &p)
 {
-    return plan_split(p.M, p.N, p.K, p.groups).ws_bytes;
+    return p.use_patch ? 0 : plan_split(p.M, p.N, p.K, p.groups).ws_bytes;
 }
 
 int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    const SplitPlan pl = plan_split(p0.M, p0.N, p0.K, p0.groups);
+    const SplitPlan pl = p0.use_patch ? SplitPlan{1, p0.K, 0} : plan_split(p0.M, p0.N, p0.K, p0.groups);
     if (pl.splits <= 1) {
         IgemmProblem p = p0;
         p.splits = 1; p.k_per_split = p.K;
