@@ -101,25 +101,26 @@ def grad_update_standalone(cg, torch, steps, warmup):
         bufs.append(dict(n=n, w=w, v=torch.zeros(n, device="cuda"),
                          g=[torch.empty(n, device="cuda").normal_(0, 1e-3, generator=gen) for _ in range(17)]))
     for K in (4, 8, 16):
+        # one launch for the eight buckets (the five convolution buckets are launch-bound one by one)
         def one():
-            for b in bufs:
-                cg.cg_grad_reduce_sgd(b["w"], b["v"], b["g"][0], b["g"][1:K + 1], b["n"], sgd)
+            cg.cg_grad_reduce_sgd_multi([b["w"] for b in bufs], [b["v"] for b in bufs], [b["g"][0] for b in bufs],
+                                        [b["g"][1:K + 1] for b in bufs], [b["n"] for b in bufs], sgd)
         for _ in range(warmup):
             one()
         torch.cuda.synchronize()
-        cg.cg_profile_enable(True)
-        t0 = time.perf_counter()
+        # `steps` launches back to back between two events on the launch stream: the per-launch time
+        # includes the gaps between launches but not the event markers' own latency, which at a few
+        # hundred microseconds per launch would otherwise cost several percent
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(steps):
             one()
+        e1.record()
         torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) / steps
-        cg.cg_profile_enable(False)
-        agg = collect_profile(cg)
-        ms = sum(a["ms"] for a in agg.values()) / steps
-        by = sum(a["bytes"] for a in agg.values()) / steps
-        big = max((p for a in agg.values() for p in [a]), key=lambda a: a["bytes"])
-        out[f"K{K}"] = dict(gbps_kernels=by / ms / 1e6, gbps_wall=by / wall / 1e9, ms_kernels=ms, ms_wall=wall * 1e3,
-                            bytes=by)
+        ms = e0.elapsed_time(e1) / steps
+        by = (4.0 * K + 20.0) * sum(sizes)
+        out[f"K{K}"] = dict(gbps=by / ms / 1e6, ms_per_launch=ms, bytes=by, frac_of_peak=by / ms / 1e6 / PEAK_HBM_GBS,
+                            launches_per_update=1, buckets=len(sizes))
     return out
 
 

@@ -104,6 +104,18 @@ int cg_grad_reduce_sgd(float *w, float *v, const float *g_local,
                        const float *const *g_peers, int K, size_t n,
                        const cg_sgd *sgd, void *stream);
 
+/* The same update for nb layer buckets in one launch per eight buckets (the
+ * small layers of a net are launch-bound one by one; the layer-wise update of
+ * section 3 does not care how many layers a launch carries).  w, v, g_local, n:
+ * HOST arrays of nb entries (device pointers / element counts); g_peers: HOST
+ * array of nb HOST arrays of K device pointers.  All buckets share K and sgd.
+ * Element for element the result is that of nb calls of cg_grad_reduce_sgd.
+ * Buckets must not overlap.  Entries with n[i] == 0 are skipped. */
+int cg_grad_reduce_sgd_multi(int nb, float *const *w, float *const *v,
+                             const float *const *g_local,
+                             const float *const *const *g_peers, int K,
+                             const size_t *n, const cg_sgd *sgd, void *stream);
+
 /* ---- whole iteration ------------------------------------------------------ */
 
 enum {

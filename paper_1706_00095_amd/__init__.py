@@ -22,7 +22,7 @@ LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc":
 
 EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight",
-    "cg_grad_reduce_sgd", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
+    "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
     "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
@@ -74,6 +74,8 @@ def lib():
         L.cg_conv_bwd_data.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.cg_conv_bwd_weight.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.cg_grad_reduce_sgd.argtypes = [vp, vp, vp, C.POINTER(vp), C.c_int, sz, C.POINTER(cg_sgd), vp]
+        L.cg_grad_reduce_sgd_multi.argtypes = [C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                               C.POINTER(C.POINTER(vp)), C.c_int, C.POINTER(sz), C.POINTER(cg_sgd), vp]
         L.cg_net_create.argtypes = [C.POINTER(cg_layer_desc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.POINTER(vp)]
         L.cg_net_destroy.argtypes = [vp]
@@ -170,6 +172,21 @@ def cg_grad_reduce_sgd(w, v, g_local, g_peers, n, sgd, stream=None):
     K = len(g_peers)
     _check(lib().cg_grad_reduce_sgd(_ptr(w), _ptr(v), _ptr(g_local), _ptr_array(g_peers), K, n, C.byref(sgd),
                                     _stream(stream)), "cg_grad_reduce_sgd")
+
+
+def cg_grad_reduce_sgd_multi(ws, vs, gs, peers, ns, sgd, stream=None):
+    """One launch for several buckets: ws, vs, gs sequences of device tensors, peers a sequence of
+    sequences of K device tensors each, ns the element counts."""
+    nb = len(ws)
+    K = len(peers[0]) if nb else 0
+    assert all(len(p) == K for p in peers)
+    rows = [_ptr_array(p) for p in peers]
+    table = (C.POINTER(C.c_void_p) * max(nb, 1))()
+    for i, r in enumerate(rows):
+        table[i] = C.cast(r, C.POINTER(C.c_void_p))
+    counts = (C.c_size_t * max(nb, 1))(*ns)
+    _check(lib().cg_grad_reduce_sgd_multi(nb, _ptr_array(ws), _ptr_array(vs), _ptr_array(gs), table, K, counts,
+                                          C.byref(sgd), _stream(stream)), "cg_grad_reduce_sgd_multi")
 
 
 def cg_debug_conv_operand(d, which_pass, operand, row, k, group):

@@ -26,29 +26,92 @@ __device__ __forceinline__ float upd(float w, float v, float s, const cg_sgd c, 
     return w - vn;
 }
 
-// K known at compile time: the K+1 gradient loads of a f4 group are issued back to back.
-// KRT > 0 means "K is a run-time value" (K > 16).
+// One launch serves up to MAXB buckets: block b belongs to the bucket whose [first, first + blocks)
+// range contains it and updates 2 x 256 consecutive float4 groups there, every load of a group
+// issued before the first use.  No loop: one short-lived block per 8 KB of each stream keeps far
+// more loads in flight than a persistent grid does, which is what the memory system rewards here.
+constexpr int MAXB = 8;          // buckets per launch
+constexpr int KMAX_TAB = 16;     // peers per bucket in the table (more: the run-time-K kernel)
+constexpr int UNR = 2;
+
+struct Bucket {
+    float *w, *v;
+    const float *g;
+    const float *peer[KMAX_TAB];
+    unsigned long long n;        // elements
+    unsigned first_block;        // of this bucket in the launch
+};
+struct BucketTable {
+    int nb;
+    Bucket b[MAXB];
+};
+
 template <int KC>
-__global__ __launch_bounds__(256) void reduce_sgd_kernel(float *__restrict__ w, float *__restrict__ v,
-                                                         const float *__restrict__ g, const PeerTable peers,
-                                                         int K_rt, size_t n4, size_t n, const cg_sgd c)
+__global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, const cg_sgd c)
 {
-    const int K = KC >= 0 ? KC : K_rt;
+    int bi = 0;
+#pragma unroll
+    for (int j = 1; j < MAXB; ++j)
+        if (j < tab.nb && blockIdx.x >= tab.b[j].first_block) bi = j;
+    const Bucket &bk = tab.b[bi];
+    const size_t n = bk.n, n4 = n / 4;
+    const size_t i0 = (size_t)(blockIdx.x - bk.first_block) * (256 * UNR) + threadIdx.x;
+    const f4 *g4 = reinterpret_cast<const f4 *>(bk.g);
+    f4 *w4 = reinterpret_cast<f4 *>(bk.w), *v4 = reinterpret_cast<f4 *>(bk.v);
+    f4 s[UNR], q[UNR][KC > 0 ? KC : 1], wi[UNR], vi[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const size_t i = i0 + (size_t)u * 256;
+        if (i < n4) {
+            s[u] = __builtin_nontemporal_load(g4 + i);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) q[u][k] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(bk.peer[k]) + i);
+            wi[u] = w4[i];
+            vi[u] = v4[i];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        const size_t i = i0 + (size_t)u * 256;
+        if (i < n4) {
+            f4 t = s[u];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) { t.x = t.x + q[u][k].x; t.y = t.y + q[u][k].y; t.z = t.z + q[u][k].z; t.w = t.w + q[u][k].w; }
+            f4 wo, vo;
+            float v0, v1, v2, v3;
+            wo.x = upd(wi[u].x, vi[u].x, t.x, c, v0);
+            wo.y = upd(wi[u].y, vi[u].y, t.y, c, v1);
+            wo.z = upd(wi[u].z, vi[u].z, t.z, c, v2);
+            wo.w = upd(wi[u].w, vi[u].w, t.w, c, v3);
+            vo.x = v0; vo.y = v1; vo.z = v2; vo.w = v3;
+            w4[i] = wo;
+            v4[i] = vo;
+        }
+    }
+    // ragged tail (n % 4 elements), handled by the first threads of the bucket's first block
+    const size_t tail = n4 * 4 + threadIdx.x;
+    if (blockIdx.x == bk.first_block && tail < n) {
+        float t = bk.g[tail];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) t = t + bk.peer[k][tail];
+        float vn;
+        const float wn = upd(bk.w[tail], bk.v[tail], t, c, vn);
+        bk.w[tail] = wn;
+        bk.v[tail] = vn;
+    }
+}
+
+// any K up to CG_MAX_PEERS: one bucket, grid-stride
+__global__ __launch_bounds__(256) void reduce_sgd_anyk_kernel(float *__restrict__ w, float *__restrict__ v,
+                                                              const float *__restrict__ g, const PeerTable peers,
+                                                              int K, size_t n4, size_t n, const cg_sgd c)
+{
     const size_t stride = (size_t)gridDim.x * 256;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
         f4 s = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g) + i);
-        if constexpr (KC >= 0) {
-            f4 q[KC > 0 ? KC : 1];
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-                q[k] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(peers.p[k]) + i);
-#pragma unroll
-            for (int k = 0; k < KC; ++k) { s.x = s.x + q[k].x; s.y = s.y + q[k].y; s.z = s.z + q[k].z; s.w = s.w + q[k].w; }
-        } else {
-            for (int k = 0; k < K; ++k) {
-                const f4 q = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(peers.p[k]) + i);
-                s.x = s.x + q.x; s.y = s.y + q.y; s.z = s.z + q.z; s.w = s.w + q.w;
-            }
+        for (int k = 0; k < K; ++k) {
+            const f4 q = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(peers.p[k]) + i);
+            s.x = s.x + q.x; s.y = s.y + q.y; s.z = s.z + q.z; s.w = s.w + q.w;
         }
         const f4 wi = reinterpret_cast<const f4 *>(w)[i];
         const f4 vi = reinterpret_cast<const f4 *>(v)[i];
@@ -62,7 +125,6 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(float *__restrict__ w, 
         reinterpret_cast<f4 *>(w)[i] = wo;
         reinterpret_cast<f4 *>(v)[i] = vo;
     }
-    // ragged tail (n % 4 elements), handled by the first threads of block 0
     const size_t tail = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0 && tail < n) {
         float s = g[tail];
@@ -76,51 +138,100 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(float *__restrict__ w, 
 
 namespace {
 
-template <int KC>
-void launch(float *w, float *v, const float *g, const PeerTable &pt, int K, size_t n, const cg_sgd &c,
-            unsigned blocks, hipStream_t stream)
+int check_bucket(const float *w, const float *v, const float *g, const float *const *peers, int K)
 {
-    hipLaunchKernelGGL((reduce_sgd_kernel<KC>), dim3(blocks), dim3(256), 0, stream, w, v, g, pt, K, n / 4, n, c);
+    if (!w || !v || !g || (K > 0 && !peers)) return CG_EINVAL;
+    if (!aligned16(w) || !aligned16(v) || !aligned16(g) || w == v) return CG_EINVAL;
+    for (int k = 0; k < K; ++k)
+        if (!peers[k] || !aligned16(peers[k])) return CG_EINVAL;
+    return CG_OK;
+}
+
+void launch_table(const BucketTable &tab, unsigned blocks, int K, const cg_sgd &c, hipStream_t stream)
+{
+    switch (K) {
+#define CG_CASE(k) case k: hipLaunchKernelGGL((reduce_sgd_kernel<k>), dim3(blocks), dim3(256), 0, stream, tab, c); break;
+        CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7) CG_CASE(8)
+        CG_CASE(9) CG_CASE(10) CG_CASE(11) CG_CASE(12) CG_CASE(13) CG_CASE(14) CG_CASE(15) CG_CASE(16)
+#undef CG_CASE
+    default: break;
+    }
 }
 
 }  // namespace
 
+// nb buckets with the same K and constants; launches ceil(nb / MAXB) kernels
+int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const float *const *g_local,
+                               const float *const *const *g_peers, int K, const size_t *n, const cg_sgd &sgd,
+                               hipStream_t stream)
+{
+    if (K < 0 || K > CG_MAX_PEERS || nb < 0) return CG_EINVAL;
+    if (nb == 0) return CG_OK;
+    if (!w || !v || !g_local || !n || (K > 0 && !g_peers)) return CG_EINVAL;
+    for (int i = 0; i < nb; ++i) {
+        if (n[i] == 0) continue;
+        const int rc = check_bucket(w[i], v[i], g_local[i], K > 0 ? g_peers[i] : nullptr, K);
+        if (rc) return rc;
+        if (n[i] >= (1ull << 40)) return CG_EUNSUPPORTED;
+    }
+    ProfTag tag("reduce_sgd", -1);
+    if (K > KMAX_TAB) {
+        for (int i = 0; i < nb; ++i) {
+            if (n[i] == 0) continue;
+            PeerTable pt{};
+            for (int k = 0; k < K; ++k) pt.p[k] = g_peers[i][k];
+            size_t blocks = (n[i] / 4 + 255) / 256;
+            if (blocks > 4096) blocks = 4096;
+            if (blocks == 0) blocks = 1;
+            const int rec = prof_on() ? prof_begin("reduce_sgd_kernel<any>", 0.0, (4.0 * K + 20.0) * (double)n[i], stream) : -1;
+            hipLaunchKernelGGL(reduce_sgd_anyk_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w[i], v[i], g_local[i],
+                               pt, K, n[i] / 4, n[i], sgd);
+            prof_end(rec, stream);
+        }
+        CG_HIP_TRY(hipGetLastError());
+        return CG_OK;
+    }
+    int i = 0;
+    while (i < nb) {
+        BucketTable tab{};
+        unsigned long long blocks = 0;
+        double bytes = 0.0;
+        while (i < nb && tab.nb < MAXB) {
+            if (n[i] == 0) { ++i; continue; }
+            const unsigned long long bb = (n[i] / 4 + 256 * UNR - 1) / (256 * UNR);
+            const unsigned long long need = bb ? bb : 1;           // a bucket of 1..3 elements still needs its tail block
+            if (blocks + need >= (1ull << 31)) break;
+            Bucket &bk = tab.b[tab.nb++];
+            bk.w = w[i]; bk.v = v[i]; bk.g = g_local[i];
+            for (int k = 0; k < K; ++k) bk.peer[k] = g_peers[i][k];
+            bk.n = n[i];
+            bk.first_block = (unsigned)blocks;
+            blocks += need;
+            bytes += (4.0 * K + 20.0) * (double)n[i];
+            ++i;
+        }
+        if (tab.nb == 0) {
+            if (i < nb) return CG_EUNSUPPORTED;     // a single bucket too large for one grid
+            break;
+        }
+        int rec = -1;
+        if (prof_on()) {
+            char name[64];
+            snprintf(name, sizeof name, "reduce_sgd_kernel<%d>", K);
+            rec = prof_begin(name, 0.0, bytes, stream);
+        }
+        launch_table(tab, (unsigned)blocks, K, sgd, stream);
+        prof_end(rec, stream);
+        CG_HIP_TRY(hipGetLastError());
+    }
+    return CG_OK;
+}
+
 int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *const *g_peers, int K, size_t n,
                          const cg_sgd &sgd, hipStream_t stream)
 {
-    if (K < 0 || K > CG_MAX_PEERS) return CG_EINVAL;
-    if (n == 0) return CG_OK;
-    if (!w || !v || !g_local || (K > 0 && !g_peers)) return CG_EINVAL;
-    if (!aligned16(w) || !aligned16(v) || !aligned16(g_local)) return CG_EINVAL;
-    if (w == v) return CG_EINVAL;
-    PeerTable pt{};
-    for (int k = 0; k < K; ++k) {
-        if (!g_peers[k] || !aligned16(g_peers[k])) return CG_EINVAL;
-        pt.p[k] = g_peers[k];
-    }
-    // 256 compute units x 8 resident blocks saturate HBM; small buckets get one f4 per thread
-    const size_t n4 = n / 4;
-    size_t blocks = (n4 + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    if (blocks == 0) blocks = 1;
-    const unsigned b = (unsigned)blocks;
-    int rec = -1;
-    if (prof_on()) {
-        ProfTag tag("reduce_sgd", -1);
-        char name[64];
-        snprintf(name, sizeof name, "reduce_sgd_kernel<%d>", K <= 16 ? K : -1);
-        rec = prof_begin(name, 0.0, (4.0 * K + 20.0) * (double)n, stream);
-    }
-    switch (K) {
-#define CG_CASE(k) case k: launch<k>(w, v, g_local, pt, K, n, sgd, b, stream); break;
-        CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7) CG_CASE(8)
-        CG_CASE(9) CG_CASE(10) CG_CASE(11) CG_CASE(12) CG_CASE(13) CG_CASE(14) CG_CASE(15) CG_CASE(16)
-#undef CG_CASE
-    default: launch<-1>(w, v, g_local, pt, K, n, sgd, b, stream); break;
-    }
-    prof_end(rec, stream);
-    CG_HIP_TRY(hipGetLastError());
-    return CG_OK;
+    if (n == 0) return (K < 0 || K > CG_MAX_PEERS) ? CG_EINVAL : CG_OK;
+    return grad_reduce_sgd_multi_impl(1, &w, &v, &g_local, &g_peers, K, &n, sgd, stream);
 }
 
 }  // namespace cg
@@ -130,4 +241,12 @@ extern "C" int cg_grad_reduce_sgd(float *w, float *v, const float *g_local, cons
 {
     if (!sgd) return CG_EINVAL;
     return cg::grad_reduce_sgd_impl(w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int cg_grad_reduce_sgd_multi(int nb, float *const *w, float *const *v, const float *const *g_local,
+                                        const float *const *const *g_peers, int K, const size_t *n, const cg_sgd *sgd,
+                                        void *stream)
+{
+    if (!sgd) return CG_EINVAL;
+    return cg::grad_reduce_sgd_multi_impl(nb, w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream));
 }

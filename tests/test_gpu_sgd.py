@@ -92,3 +92,31 @@ def test_two_consecutive_steps_and_stream_argument(orc32):
         orc32.grad_reduce_sgd(w, v, g, peers, 0.01, 0.9, 5e-4)
     s.synchronize()
     assert host(dw).tobytes() == w.tobytes() and host(dv).tobytes() == v.tobytes()
+
+
+@pytest.mark.parametrize("K", [0, 4, 16, 20])
+def test_multi_bucket_launch_is_bit_exact_per_bucket(orc32, K):
+    """One launch over many layer buckets (ragged sizes, a 1..3-element bucket, an empty one, more
+    than eight buckets) gives every bucket exactly what its own cg_grad_reduce_sgd call gives."""
+    sgd = (0.01, 0.9, 5e-4, 1.0)
+    sizes = [34944, 3, 307456, 0, 1027, 885120, 5, 663936, 442624, 4096 * 25 + 2, 1]
+    rng = np.random.default_rng(100 + K)
+    host_sets, dev_sets = [], []
+    for n in sizes:
+        w = (rng.standard_normal(n) * 1e-2).astype(F32)
+        v = (rng.standard_normal(n) * 1e-4).astype(F32)
+        g = (rng.standard_normal(n) * 1e-3).astype(F32)
+        peers = [(rng.standard_normal(n) * 1e-3).astype(F32) for _ in range(K)]
+        host_sets.append((w, v, g, peers))
+        # empty tensors have no device address worth passing: a 4-float dummy stands in
+        mk = (lambda a: dev(a) if a.size else torch.zeros(4, device="cuda"))
+        dev_sets.append((mk(w), mk(v), mk(g), [mk(p) for p in peers]))
+    cg.cg_grad_reduce_sgd_multi([d[0] for d in dev_sets], [d[1] for d in dev_sets], [d[2] for d in dev_sets],
+                                [d[3] for d in dev_sets], sizes, cg.cg_sgd(*sgd))
+    for (w, v, g, peers), d, n in zip(host_sets, dev_sets, sizes):
+        if n == 0:
+            continue
+        orc32.grad_reduce_sgd(w, v, g, peers, *sgd)
+        assert host(d[0])[:n].tobytes() == w.tobytes()
+        assert host(d[1])[:n].tobytes() == v.tobytes()
+        assert host(d[2])[:n].tobytes() == g.tobytes()
