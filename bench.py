@@ -151,6 +151,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--serial", action="store_true", help="one-stream schedule (no overlap)")
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
+    ap.add_argument("--skip-update-bench", action="store_true", help="leave out the stand-alone update benchmark")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures ONE worker on ONE GPU; the peers' gradients are resident buffers. "
@@ -165,7 +166,12 @@ def main():
     sgd = cg.cg_sgd(0.01, 0.9, 5e-4, 1.0)
     flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
     st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps)))
+    # one plain copy of 256 MiB before anything is timed: under a counter-collecting profiler its
+    # dispatch is the known traffic the other kernels' FETCH_SIZE / WRITE_SIZE readings are scaled by
+    cal = torch.zeros(2, 64 << 20, device="cuda")
+    cg.cg_debug_copy(cal[0], cal[1], cal[0].numel() * 4)
     torch.cuda.synchronize()
+    del cal
     run_steps(cg, torch, st, sgd, args.warmup, flags)
     sync(torch, st)
 
@@ -207,7 +213,7 @@ def main():
     # free the net before the stand-alone update benchmark
     del st
     torch.cuda.empty_cache()
-    grad_update = grad_update_standalone(cg, torch, max(args.steps, 5), args.warmup)
+    grad_update = None if args.skip_update_bench else grad_update_standalone(cg, torch, max(args.steps, 5), args.warmup)
     cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
 
     out = {

@@ -204,6 +204,11 @@ int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
  * tests.  count receives the number of 4-byte elements. */
 int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count);
 
+/* Measurement aid: dst[0..bytes) = src[0..bytes) by a plain kernel (16-byte
+ * aligned device pointers, bytes % 16 == 0): a dispatch of known HBM traffic to
+ * scale hardware-counter readings of the other kernels by. */
+int cg_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Test hook (host only, launches nothing): which element of which tensor the
  * implicit-GEMM view of a convolution pass reads for operand A (0) or B (1) at
  * (row, k) of the given group.  elem_offset is in floats from the tensor's base

@@ -96,6 +96,28 @@ extern "C" int cg_profile_get(int i, cg_profile_record *out)
     return CG_OK;
 }
 
+// A plain copy of known size: the yardstick that hardware-counter readings (bytes fetched from and
+// written to HBM per dispatch) of the other kernels are scaled by.
+namespace cg {
+__global__ __launch_bounds__(256) void debug_copy_kernel(float4 *__restrict__ dst, const float4 *__restrict__ src, size_t n4)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) dst[i] = src[i];
+}
+}  // namespace cg
+
+extern "C" int cg_debug_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || !cg::aligned16(dst) || !cg::aligned16(src) || bytes % 16) return CG_EINVAL;
+    if (bytes == 0) return CG_OK;
+    const size_t n4 = bytes / 16;
+    if ((n4 + 255) / 256 >= (1ull << 31)) return CG_EUNSUPPORTED;
+    hipLaunchKernelGGL(cg::debug_copy_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<float4 *>(dst), static_cast<const float4 *>(src), n4);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
 extern "C" const char *cg_strerror(int code)
 {
     switch (code) {
