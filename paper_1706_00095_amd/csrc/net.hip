@@ -8,8 +8,9 @@
 // next iteration's forward of layer l waits only on layer l's own update event, so there is no
 // device-wide synchronisation anywhere (design principle 2, section 2.2).
 //
-// Within a layer's turn backward-data runs before backward-weight: backward-data still reads
-// the layer's model, which the update overwrites.
+// Within a layer's turn backward-data and backward-weight are independent and run side by side
+// (backward-weight on a third stream owned by the net); the update waits for both, because it
+// overwrites the model that backward-data still reads.
 #include <new>
 #include <vector>
 #include "cg_internal.h"
@@ -27,6 +28,7 @@ struct cg_net {
         std::vector<const float *> peers;
         bool bound = false;
         hipEvent_t ev_grad = nullptr, ev_upd = nullptr;
+        hipEvent_t ev_dy = nullptr, ev_bd = nullptr;   // gradient of the output complete / backward-data done
         bool upd_pending = false;             // an update of this layer was enqueued by a previous step
         bool grad_written = false;            // per step: has anything been written to this layer's gradient?
         bool needs_grad = false;              // false when no parameter lies upstream of this output
@@ -46,7 +48,9 @@ struct cg_net {
     };
     int B = 0, C = 0, H = 0, W = 0;
     std::vector<Layer> layers;
-    size_t scratch_off = 0, scratch_bytes = 0;   // kernel scratch (filter transpose, split-K partials)
+    size_t scratch_off = 0, scratch_bytes = 0;   // kernel scratch (filter copies, split-K partials): two regions of
+                                                 // scratch_bytes, one per stream that launches matrix kernels
+    hipStream_t wgrad_stream = nullptr;          // backward-weight passes run here, beside backward-data
     size_t loss_off = 0;                         // B floats of per-sample loss
     size_t ws_floats = 0;
 };
@@ -200,13 +204,16 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
     if (rc == CG_OK) {
         net->loss_off = off; off += round_up((size_t)B, 64);
         net->scratch_off = off; net->scratch_bytes = round_up(scratch, 256);
-        off += net->scratch_bytes / sizeof(float);
+        off += 2 * (net->scratch_bytes / sizeof(float));
         net->ws_floats = off;
         for (Layer &ly : net->layers)
             if (ly.n_params) {
                 if (hipEventCreateWithFlags(&ly.ev_grad, hipEventDisableTiming) != hipSuccess ||
-                    hipEventCreateWithFlags(&ly.ev_upd, hipEventDisableTiming) != hipSuccess) { rc = CG_EHIP; break; }
+                    hipEventCreateWithFlags(&ly.ev_upd, hipEventDisableTiming) != hipSuccess ||
+                    hipEventCreateWithFlags(&ly.ev_dy, hipEventDisableTiming) != hipSuccess ||
+                    hipEventCreateWithFlags(&ly.ev_bd, hipEventDisableTiming) != hipSuccess) { rc = CG_EHIP; break; }
             }
+        if (rc == CG_OK && hipStreamCreateWithFlags(&net->wgrad_stream, hipStreamNonBlocking) != hipSuccess) rc = CG_EHIP;
     }
     if (rc != CG_OK) { cg_net_destroy(net); return rc; }
     *out = net;
@@ -219,7 +226,10 @@ extern "C" int cg_net_destroy(cg_net *net)
     for (Layer &ly : net->layers) {
         if (ly.ev_grad) (void)hipEventDestroy(ly.ev_grad);
         if (ly.ev_upd) (void)hipEventDestroy(ly.ev_upd);
+        if (ly.ev_dy) (void)hipEventDestroy(ly.ev_dy);
+        if (ly.ev_bd) (void)hipEventDestroy(ly.ev_bd);
     }
+    if (net->wgrad_stream) (void)hipStreamDestroy(net->wgrad_stream);
     delete net;
     return CG_OK;
 }
@@ -290,6 +300,12 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
     float *base = static_cast<float *>(ws);
     void *scratch = base + net->scratch_off;
     const size_t scratch_bytes = net->scratch_bytes;
+    void *scratch2 = serial ? scratch : static_cast<char *>(scratch) + scratch_bytes;
+    // Backward-weight of a layer needs only that layer's dy and input, backward-data only dy and the
+    // model: the two run side by side, backward-weight on a stream of the net's own, so that the blocks
+    // of one fill the compute units the other's last wave of blocks leaves idle.
+    hipStream_t S2 = serial ? S0 : net->wgrad_stream;
+    hipEvent_t last_wgrad = nullptr;
     const int B = net->B;
     auto act = [&](int i) -> const float * { return i < 0 ? x : base + net->layers[i].act_off; };
     int rc = CG_OK;
@@ -370,15 +386,22 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
         switch (d.kind) {
         case CG_LAYER_CONV:
-            if (want_dx) rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0);
-            if (rc == CG_OK)
-                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch, scratch_bytes, S0);
-            break;
         case CG_LAYER_FC: {
+            if (!serial) {
+                CG_HIP_TRY(hipEventRecord(ly.ev_dy, S0));
+                CG_HIP_TRY(hipStreamWaitEvent(S2, ly.ev_dy, 0));
+            }
             const int IN = ly.inC * ly.inH * ly.inW;
-            if (want_dx) rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0);
-            if (rc == CG_OK)
-                rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch, scratch_bytes, S0);
+            if (d.kind == CG_LAYER_CONV)
+                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2);
+            else
+                rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2);
+            if (rc == CG_OK && want_dx) {
+                if (d.kind == CG_LAYER_CONV)
+                    rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0);
+                else
+                    rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0);
+            }
             break;
         }
         case CG_LAYER_RELU:
@@ -424,8 +447,13 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         if (ly.n_params) {
             // the turn's second half: aggregate this layer's gradient over the ranks and update its model
             if (!serial) {
-                CG_HIP_TRY(hipEventRecord(ly.ev_grad, S0));
+                // the update overwrites the model backward-data reads and consumes the gradient
+                // backward-weight writes: it waits for both
+                CG_HIP_TRY(hipEventRecord(ly.ev_grad, S2));
+                CG_HIP_TRY(hipEventRecord(ly.ev_bd, S0));
                 CG_HIP_TRY(hipStreamWaitEvent(S1, ly.ev_grad, 0));
+                CG_HIP_TRY(hipStreamWaitEvent(S1, ly.ev_bd, 0));
+                last_wgrad = ly.ev_grad;
             }
             rc = grad_reduce_sgd_impl(ly.w, ly.v, ly.g, ly.peers.data(), (int)ly.peers.size(), (size_t)ly.n_params,
                                       *sgd, S1);
@@ -436,5 +464,8 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             }
         }
     }
+    // the local gradients are promised in compute-stream order, and the next call's forward may
+    // overwrite what the last backward-weight still reads
+    if (!serial && last_wgrad) CG_HIP_TRY(hipStreamWaitEvent(S0, last_wgrad, 0));
     return rc;
 }
