@@ -55,9 +55,12 @@ struct IndexMap {
     FastDiv d1, d2;
     int32_t s1, s2, s3, o0;
     int32_t sa, a0, sb, b0;
+    uint32_t r1_lim;   // if non-zero: indices with r1 >= r1_lim are padding (read as 0): runs of r1_lim real
+                       // indices, each padded to d1 (a reduction over images whose pixel count is rounded
+                       // up to a multiple of 4 so that aligned groups of four never straddle two images)
 };
 
-struct Info { int32_t off, a, b; };
+struct Info { int32_t off, a, b; uint32_t r1; };
 
 FastDiv make_fastdiv(uint32_t d);
 IndexMap linear_map(uint32_t count, int32_t stride);
@@ -78,6 +81,7 @@ __host__ __device__ inline Info map_info(const IndexMap &m, uint32_t idx)
     r.off = (int32_t)q1 * m.s1 + (int32_t)q2 * m.s2 + (int32_t)r2 * m.s3 + m.o0;
     r.a = (int32_t)q2 * m.sa + m.a0;
     r.b = (int32_t)r2 * m.sb + m.b0;
+    r.r1 = r1;
     return r;
 }
 
@@ -132,6 +136,7 @@ struct IgemmProblem {
     int32_t bias_gstride;
     uint32_t M, N, K;
     uint32_t groups, splits, k_per_split;
+    double flops;             // algorithmic work to report (0: 2*M*N*K*groups; set when K counts padding)
     int accumulate;           // C += result instead of C = result
     int relu;                 // C = max(result, 0) after bias (forward passes followed by a rectifier)
     const float *gate;        // same layout as C, or NULL: result = 0 where gate <= 0 (backward-data into a

@@ -326,14 +326,18 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
 }
 
+// The reduction runs over pixels (n, oh, ow).  Its index space pads every image's OH*OW pixels to
+// a multiple of four (padding indices read as zero in B), so that dy, contiguous along the pixels
+// of one image, can be fetched in aligned groups of four that never straddle two images.
 static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *dy,
                                        float *dw)
 {
     const int G = d.groups, Cg = d.C / G, Mg = d.M / G, Kg = Cg * d.KH * d.KW, P = OH * OW;
+    const int Pp = (P + 3) / 4 * 4;
     IgemmProblem p{};
     p.A.ptr = dy;
     p.A.row = linear_map(Mg, P);
-    p.A.k = split_map((uint32_t)d.N * P, P, d.M * P, 1);
+    p.A.k = split_map((uint32_t)d.N * Pp, Pp, d.M * P, 1);
     p.A.limA = p.A.limB = 1;
     p.A.gstride = (int64_t)Mg * P;
     p.A.elems = (uint64_t)d.N * d.M * P;
@@ -341,6 +345,9 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
     p.B.ptr = x;
     p.B.row = tap_map(d, Cg);
     p.B.k = window_origin_map(d, OH, OW);
+    p.B.k.count = (uint32_t)d.N * Pp;
+    p.B.k.d1 = make_fastdiv((uint32_t)Pp);
+    p.B.k.r1_lim = (uint32_t)P;
     p.B.limA = d.H; p.B.limB = d.W;
     p.B.gstride = (int64_t)Cg * d.H * d.W;
     p.B.elems = (uint64_t)d.N * d.C * d.H * d.W;
@@ -350,7 +357,8 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
     p.c_row_stride = Kg;
     p.c_col = linear_map(Kg, 1);
     p.c_gstride = (int64_t)Mg * Kg;
-    p.M = Mg; p.N = Kg; p.K = (uint32_t)d.N * P;
+    p.M = Mg; p.N = Kg; p.K = (uint32_t)d.N * Pp;
+    p.flops = 2.0 * Mg * (double)Kg * ((double)d.N * P) * G;
     p.groups = G; p.splits = 1; p.k_per_split = p.K;
     return p;
 }

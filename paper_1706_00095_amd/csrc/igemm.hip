@@ -30,6 +30,7 @@ namespace {
 #ifndef CG_EXP
 #define CG_EXP 0
 #endif
+
 constexpr int KT = 16;                       // reduction indices per LDS stage (a ring of NST stages)
 constexpr int NPART = KT / 2;                // MFMA steps per tile = parts the loads of a tile are issued in
 // Offsets that no buffer descriptor of this library covers (descriptors span < 0x7fffff00 bytes).
@@ -122,7 +123,7 @@ template <int R, bool CHECK> struct RowsLoader {
             const uint32_t kl = (uint32_t)(4 * wave + t), k = k0 + kl;       // wave-uniform
             if (c == 0) {
                 kq = map_info(op.k, k);
-                ksoff = k < kend ? (uint32_t)kq.off * 4u : OOB_K;
+                ksoff = (k < kend && (op.k.r1_lim == 0 || kq.r1 < op.k.r1_lim)) ? (uint32_t)kq.off * 4u : OOB_K;
             }
             uint32_t voff = roff[c];
             if (CHECK) {
@@ -169,7 +170,7 @@ template <int R, bool CHECK> struct KLoader {
         if (P == 0) {
             const uint32_t k = k0 + (uint32_t)(lane & 15);
             kq = map_info(op.k, k);
-            koff = k < kend ? (uint32_t)kq.off * 4u : OOB_K;
+            koff = (k < kend && (op.k.r1_lim == 0 || kq.r1 < op.k.r1_lim)) ? (uint32_t)kq.off * 4u : OOB_K;
         }
 #pragma unroll
         for (int j = P * LPT / NPART; j < (P + 1) * LPT / NPART; ++j) {
@@ -188,17 +189,21 @@ template <int R, bool CHECK> struct KLoader {
     }
 };
 
-// KLoader4: for an operand whose reduction index is unit-stride in memory with 16-byte aligned
-// rows (a plain row-major matrix with K % 4 == 0).  One load moves 16 rows x 16 k: lane l fetches
-// the aligned quad (l&3) ^ ((row>>2)&3) of row l>>2, so that the four quads of a row sit in its
-// 64-byte LDS line in an order that spreads a fragment read of 16 rows over all banks.  The k part
-// of the address is wave-uniform (scalar offset); nothing is computed per load.
+// KLoader4: for an operand in which every aligned group of four reduction indices is four
+// consecutive floats in memory (a row-major matrix; or runs of pixels, one run per image, the run
+// length padded to a multiple of four in the index space).  One load moves 16 rows x 16 k: lane l
+// fetches quad (l&3) ^ ((row>>2)&3) of row l>>2, so that the four quads of a row sit in its 64-byte
+// LDS line in an order that spreads a fragment read of 16 rows over all banks.  Addresses need
+// only 4-byte alignment, and the range check is per float: a quad that reaches beyond K, a run or
+// the tensor delivers the floats that exist and zeros (or the neighbouring row's values) for the
+// rest, which meet zeros of operand B.
 template <int R> struct KLoader4 {
     static constexpr int NJ = (R + 63) / 64;     // load instructions per tile and wave
     static constexpr int SZ = 4 * NJ * 256;      // rows beyond R are loaded as zeros
     static constexpr int LPT = NJ;
     uint32_t roff[NJ];
     uint32_t kq4;                                // first k of this lane's quad inside the tile
+    uint32_t koff;                               // byte offset of that quad (set by part 0 of a tile)
 
     __device__ __forceinline__ void init(const Operand &op, uint32_t row0, uint32_t nrows, int wave, int lane)
     {
@@ -208,18 +213,22 @@ template <int R> struct KLoader4 {
         for (int j = 0; j < NJ; ++j) {
             const uint32_t rl = (uint32_t)(16 * (wave * NJ + j)) + r, row = row0 + rl;
             const Info q = map_info(op.row, row);
-            roff[j] = (rl < (uint32_t)R && row < nrows) ? ((uint32_t)q.off + kq4) * 4u : OOB_ROW;
+            roff[j] = (rl < (uint32_t)R && row < nrows) ? (uint32_t)q.off * 4u : OOB_ROW;
         }
     }
     template <int P>
     __device__ __forceinline__ void issue_part(BufferRsrc rsrc, float *stage, const Operand &op, uint32_t k0,
                                                uint32_t kend, int wave, int)
     {
-#pragma unroll
-        for (int j = P * LPT / NPART; j < (P + 1) * LPT / NPART; ++j) {
-            const uint32_t voff = k0 + kq4 < kend ? roff[j] : OOB_ROW;
-            load4_to_lds(rsrc, stage + (wave * NJ + j) * 256, voff, (k0 * (uint32_t)op.k.s1 + (uint32_t)op.k.o0) * 4u);
+        if (P == 0) {
+            const uint32_t k = k0 + kq4;
+            // a plain matrix (wave-uniform test) needs no index arithmetic: its k is its offset
+            const uint32_t off = op.k.d1.d == 1 ? k + (uint32_t)op.k.o0 : (uint32_t)map_info(op.k, k).off;
+            koff = k < kend ? off * 4u : OOB_K;
         }
+#pragma unroll
+        for (int j = P * LPT / NPART; j < (P + 1) * LPT / NPART; ++j)
+            load4_to_lds(rsrc, stage + (wave * NJ + j) * 256, roff[j] + koff, 0u);
     }
     __device__ __forceinline__ static void frag(const float *stage, int row, int ks, int h, float out[4])
     {
@@ -560,7 +569,7 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
     if (prof_on()) {
         char name[64];
         snprintf(name, sizeof name, "igemm_kernel<%dx%d,%s>", MT, NT, modes);
-        rec = prof_begin(name, 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
+        rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = (size_t)NST * (LA::SZ + LB::SZ) * sizeof(float);
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
@@ -596,11 +605,14 @@ int launch_modes(const IgemmProblem &p, int mt, hipStream_t stream)
     }
 }
 
-// rows and k both plain strides, k unit-stride, everything 16-byte aligned: aligned quads can be loaded
-bool quad_ok(const Operand &o, uint32_t K)
+// every aligned group of four reduction indices is four consecutive floats: k is unit-stride, either
+// throughout or inside runs whose padded length is a multiple of four
+bool quad_ok(const Operand &o, uint32_t)
 {
-    return o.lanes_k && !o.check && K % 4 == 0 && o.k.d1.d == 1 && o.k.d2.d == 1 && o.k.s1 == 1 && o.row.d1.d == 1 &&
-           o.row.d2.d == 1 && o.row.s1 % 4 == 0 && o.gstride % 4 == 0 && (o.row.o0 + o.k.o0 + o.shift) % 4 == 0;
+    if (!o.lanes_k || o.check) return false;
+    const bool linear = o.k.d1.d == 1 && o.k.d2.d == 1 && o.k.s1 == 1;
+    const bool runs = o.k.d1.d % 4 == 0 && o.k.d2.d == 1 && o.k.s2 == 1;
+    return linear || runs;
 }
 
 // Row-tile height for a problem.  A taller tile gathers the B operand (the costly one: one load
@@ -688,7 +700,7 @@ int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
     if (prof_on()) {
         char name[64];
         snprintf(name, sizeof name, "igemm_patch_kernel<%dx128,%d>", MT, NSL);
-        rec = prof_begin(name, 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
+        rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL>::BUF) * sizeof(float);
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
@@ -810,7 +822,8 @@ IndexMap split_map(uint32_t count, uint32_t d, int32_t sq, int32_t sr)
 void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, int64_t *off, int *valid)
 {
     const Info r = map_info(op.row, row), q = map_info(op.k, k);
-    *valid = (uint32_t)(r.a + q.a) < op.limA && (uint32_t)(r.b + q.b) < op.limB;
+    *valid = (uint32_t)(r.a + q.a) < op.limA && (uint32_t)(r.b + q.b) < op.limB &&
+             (op.k.r1_lim == 0 || q.r1 < op.k.r1_lim);
     *off = (int64_t)r.off + q.off + op.shift;
 }
 
@@ -845,7 +858,7 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     const int bm = quad_ok(p.B, p.K) ? LD_K4 : p.B.lanes_k ? LD_K : LD_ROWS;
     if (am == LD_K4 && bm == LD_ROWS) return bc ? launch_modes<LD_K4, LD_ROWS, true>(p, mt, stream) : launch_modes<LD_K4, LD_ROWS, false>(p, mt, stream);
     if (am == LD_K4 && bm == LD_K4) return launch_modes<LD_K4, LD_K4, false>(p, mt, stream);
-    if (am == LD_K4 && bm == LD_K) return bc ? launch_modes<LD_K, LD_K, true>(p, mt, stream) : launch_modes<LD_K, LD_K, false>(p, mt, stream);
+    if (am == LD_K4 && bm == LD_K) return bc ? launch_modes<LD_K4, LD_K, true>(p, mt, stream) : launch_modes<LD_K4, LD_K, false>(p, mt, stream);
     if (am == LD_K && bm == LD_ROWS) return bc ? launch_modes<LD_K, LD_ROWS, true>(p, mt, stream) : launch_modes<LD_K, LD_ROWS, false>(p, mt, stream);
     if (am == LD_K && (bm == LD_K || bm == LD_K4)) return bc ? launch_modes<LD_K, LD_K, true>(p, mt, stream) : launch_modes<LD_K, LD_K, false>(p, mt, stream);
     if (am == LD_ROWS && bm == LD_ROWS && !bc) return launch_modes<LD_ROWS, LD_ROWS, false>(p, mt, stream);

@@ -91,6 +91,7 @@ def test_forward_and_backward_weight_maps_address_the_definition(case):
     OH, OW = cg.cg_conv_out_shape(d)
     Cg, Mg = Cin // G, M // G
     K = Cg * KH * KW
+    Pp = (OH * OW + 3) // 4 * 4
     for g in range(G):
         # forward: A = filters, B = x gathered through the window
         for m, k in itertools.product(range(Mg), range(K)):
@@ -106,12 +107,16 @@ def test_forward_and_backward_weight_maps_address_the_definition(case):
                 assert ok == inside
                 if inside:
                     assert off == ((n * Cin + g * Cg + c) * H + ih) * W + iw
-                # backward-weight swaps the roles: rows are filter taps, the reduction runs over pixels
-                off2, ok2 = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 1, k, row, g)
+                # backward-weight swaps the roles: rows are filter taps, the reduction runs over pixels,
+                # every image's pixels padded to a multiple of four in the index space
+                off2, ok2 = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 1, k, n * Pp + oh * OW + ow, g)
                 assert ok2 == inside and (not inside or off2 == off)
+        for k in (0, K - 1):
+            for n, q in itertools.product(range(N), range(OH * OW, Pp)):
+                assert not cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 1, k, n * Pp + q, g)[1]   # padding index
         for m in range(Mg):
             for n, q in itertools.product(range(N), range(OH * OW)):
-                off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 0, m, n * OH * OW + q, g)
+                off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 0, m, n * Pp + q, g)
                 assert ok and off == (n * M + g * Mg + m) * OH * OW + q
 
 
@@ -150,6 +155,7 @@ def test_maps_at_alexnet_sizes_stay_in_bounds():
         G = c["groups"]
         Cg, Mg = c["C"] // G, c["M"] // G
         K, NP = Cg * c["k"] ** 2, 256 * OH * OW
+        Pp = (OH * OW + 3) // 4 * 4
         x_elems, y_elems = 256 * c["C"] * c["H"] ** 2, 256 * c["M"] * OH * OW
         rows = [0, NP - 1] + list(rng.integers(0, NP, 200))
         ks = [0, K - 1] + list(rng.integers(0, K, 20))
@@ -158,7 +164,8 @@ def test_maps_at_alexnet_sizes_stay_in_bounds():
                 for k in ks:
                     off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_FWD, 1, int(row), int(k), g)
                     assert not ok or 0 <= off < x_elems
-                    off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 1, int(k), int(row), g)
+                    rowp = int(row) // (OH * OW) * Pp + int(row) % (OH * OW)       # the padded reduction index
+                    off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 1, int(k), rowp, g)
                     assert not ok or 0 <= off < x_elems
-                off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 0, Mg - 1, int(row), g)
+                off, ok = cg.cg_debug_conv_operand(d, cg.CG_PASS_BWD_WEIGHT, 0, Mg - 1, rowp, g)
                 assert ok and 0 <= off < y_elems
