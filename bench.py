@@ -141,6 +141,52 @@ def cpu_baseline(sample_B, K):
                        f"({dt:.1f} s of CPU time; time scales linearly in B except the update)")
 
 
+def load_traffic():
+    """Per-launch HBM traffic by kernel label, from the committed counter summary (profiles/)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)["kernels"]
+    except (OSError, ValueError, KeyError):
+        return {}
+
+
+def kernel_rooflines(agg, steps, traffic):
+    """(dominant matrix-core kernel's roofline, update kernel's roofline, totals) from per-launch records."""
+    mm = {k: a for k, a in agg.items() if k.startswith("igemm")}
+    dom_name, dom = max(mm.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["flops"] / dom["ms"] / 1e9       # TFLOP/s over that kernel's own launches
+    t = traffic.get(dom_name)
+    roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_FP32_MFMA_TFLOPS,
+                    traffic=(t["fetch_bytes"] + t["write_bytes"]) if t else None, kernel=dom_name,
+                    avg_launch_ms=dom["ms"] / dom["launches"], launches_per_step=dom["launches"] / steps,
+                    flops_per_launch=dom["flops"] / dom["launches"])
+    all_flops = sum(a["flops"] for a in mm.values())
+    all_ms = sum(a["ms"] for a in mm.values())
+    upd = {k: a for k, a in agg.items() if k.startswith("reduce_sgd")}
+    upd_bytes = sum(a["bytes"] for a in upd.values())
+    upd_ms = sum(a["ms"] for a in upd.values())
+    upd_name = max(upd.items(), key=lambda kv: kv[1]["ms"])[0]
+    t = traffic.get(upd_name)
+    n_upd = sum(a["launches"] for a in upd.values())
+    update = dict(bound="hbm", achieved=upd_bytes / upd_ms / 1e6, peak=PEAK_HBM_GBS, unit="GB/s",
+                  frac=upd_bytes / upd_ms / 1e6 / PEAK_HBM_GBS,
+                  traffic=(t["fetch_bytes"] + t["write_bytes"]) if t else None, kernel=upd_name,
+                  bytes_per_launch=upd_bytes / n_upd, avg_launch_ms=upd_ms / n_upd, launches_per_step=n_upd / steps)
+    totals = dict(tflops=all_flops / all_ms / 1e9, ms_per_step=all_ms / steps,
+                  frac=all_flops / all_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, flops_per_step=all_flops / steps)
+    return roofline, update, totals
+
+
+def kernel_table(agg, steps):
+    log(f"{'kernel':34s} {'pass@layer':24s} {'launch/step':>11s} {'avg ms':>9s} {'TFLOP/s':>9s} {'GB/s':>9s}")
+    for k, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
+        for pk, p in sorted(a["passes"].items(), key=lambda kv: -kv[1]["ms"]):
+            log(f"{k:34s} {pk:24s} {p['launches'] / steps:11.1f} {p['ms'] / p['launches']:9.4f} "
+                f"{p['flops'] / p['ms'] / 1e9:9.1f} {p['bytes'] / p['ms'] / 1e6:9.1f}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,9 +195,12 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--peers", type=int, default=4)
     ap.add_argument("--cpu-sample", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--serial", action="store_true", help="one-stream schedule (no overlap)")
+    ap.add_argument("--serial", action="store_true", help="one-stream schedule (no overlap) in the timed region")
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--skip-update-bench", action="store_true", help="leave out the stand-alone update benchmark")
+    ap.add_argument("--update-only", action="store_true", help="only the stand-alone update benchmark (for counter runs)")
+    ap.add_argument("--exclusive-steps", type=int, default=5,
+                    help="steps of the extra one-stream pass that times every kernel alone on the GPU (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures ONE worker on ONE GPU; the peers' gradients are resident buffers. "
@@ -164,17 +213,25 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B, K = args.batch, args.peers
     sgd = cg.cg_sgd(0.01, 0.9, 5e-4, 1.0)
-    flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
-    st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps)))
+    traffic = load_traffic()
     # one plain copy of 256 MiB before anything is timed: under a counter-collecting profiler its
     # dispatch is the known traffic the other kernels' FETCH_SIZE / WRITE_SIZE readings are scaled by
     cal = torch.zeros(2, 64 << 20, device="cuda")
     cg.cg_debug_copy(cal[0], cal[1], cal[0].numel() * 4)
     torch.cuda.synchronize()
     del cal
+    if args.update_only:
+        print(json.dumps({"grad_update": grad_update_standalone(cg, torch, max(args.steps, 1), args.warmup)}), flush=True)
+        return
+
+    flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
+    extra = args.exclusive_steps if not args.serial else 0
+    st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps + extra)))
+    torch.cuda.synchronize()
     run_steps(cg, torch, st, sgd, args.warmup, flags)
     sync(torch, st)
 
+    # ---- the timed region: K whole iterations, every matrix-core and update launch bracketed by events
     cg.cg_profile_enable(True)
     t0 = time.perf_counter()
     run_steps(cg, torch, st, sgd, args.steps, flags)
@@ -184,36 +241,52 @@ def main():
     agg = collect_profile(cg)
     loss = float(st["loss"].cpu()[0])
     ms_per_step = wall / args.steps * 1e3
-
-    mm = {k: a for k, a in agg.items() if k.startswith("igemm")}
-    dom_name, dom = max(mm.items(), key=lambda kv: kv[1]["ms"])
-    achieved = dom["flops"] / dom["ms"] / 1e9       # TFLOP/s over that kernel's own launches
-    roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_FP32_MFMA_TFLOPS, traffic=None, kernel=dom_name,
-                    avg_launch_ms=dom["ms"] / dom["launches"], launches_per_step=dom["launches"] / args.steps,
-                    flops_per_launch=dom["flops"] / dom["launches"])
-    all_flops = sum(a["flops"] for a in mm.values())
-    all_ms = sum(a["ms"] for a in mm.values())
-    upd = {k: a for k, a in agg.items() if k.startswith("reduce_sgd")}
-    upd_bytes = sum(a["bytes"] for a in upd.values())
-    upd_ms = sum(a["ms"] for a in upd.values())
-    update_roofline = dict(bound="hbm", achieved=upd_bytes / upd_ms / 1e6, peak=PEAK_HBM_GBS, unit="GB/s",
-                           frac=upd_bytes / upd_ms / 1e6 / PEAK_HBM_GBS, traffic=None,
-                           kernel=f"reduce_sgd_kernel<{K}> inside the step (overlapped with backward)",
-                           bytes_per_step=upd_bytes / args.steps, ms_per_step=upd_ms / args.steps)
+    roofline, update_roofline, totals = kernel_rooflines(agg, args.steps, traffic)
+    roofline["measured"] = update_roofline["measured"] = (
+        "HIP events around every launch of the timed region" +
+        ("" if args.serial else ", in which backward-data, backward-weight and the update run on three streams: "
+         "a launch's duration is its share of a GPU it does not have to itself"))
     if args.kernel_table:
-        log(f"{'kernel':34s} {'pass@layer':24s} {'launch/step':>11s} {'avg ms':>9s} {'TFLOP/s':>9s} {'GB/s':>9s}")
-        for k, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
-            for pk, p in sorted(a["passes"].items(), key=lambda kv: -kv[1]["ms"]):
-                log(f"{k:34s} {pk:24s} {p['launches'] / args.steps:11.1f} {p['ms'] / p['launches']:9.4f} "
-                    f"{p['flops'] / p['ms'] / 1e9:9.1f} {p['bytes'] / p['ms'] / 1e6:9.1f}")
-        log(f"matrix-core kernels: {all_ms / args.steps:.3f} ms/step, {all_flops / all_ms / 1e9:.1f} TFLOP/s overall; "
-            f"update kernels: {upd_ms / args.steps:.3f} ms/step; wall {ms_per_step:.3f} ms/step; loss {loss:.4f}")
+        kernel_table(agg, args.steps)
+        log(f"matrix-core kernels: {totals['ms_per_step']:.3f} ms/step of launch time, {totals['tflops']:.1f} TFLOP/s over it; "
+            f"wall {ms_per_step:.3f} ms/step; loss {loss:.4f}")
+
+    # ---- the same kernels alone on the GPU: a few iterations of the one-stream schedule
+    roofline_excl = update_excl = totals_excl = None
+    serial_ms = None
+    if extra > 0:
+        cg.cg_profile_enable(True)
+        t0 = time.perf_counter()
+        run_steps(cg, torch, st, sgd, extra, cg.CG_STEP_SERIAL)
+        sync(torch, st)
+        serial_ms = (time.perf_counter() - t0) / extra * 1e3
+        cg.cg_profile_enable(False)
+        agg1 = collect_profile(cg)
+        roofline_excl, update_excl, totals_excl = kernel_rooflines(agg1, extra, traffic)
+        roofline_excl["measured"] = update_excl["measured"] = (
+            f"HIP events around every launch of {extra} further iterations run right after the timed region with "
+            "the one-stream schedule (CG_STEP_SERIAL: same kernels, same order, one at a time)")
+        # the timed region's figures for that same kernel
+        if roofline_excl["kernel"] in agg:
+            a = agg[roofline_excl["kernel"]]
+            roofline = dict(roofline, kernel=roofline_excl["kernel"], achieved=a["flops"] / a["ms"] / 1e9,
+                            frac=a["flops"] / a["ms"] / 1e9 / PEAK_FP32_MFMA_TFLOPS,
+                            avg_launch_ms=a["ms"] / a["launches"], launches_per_step=a["launches"] / args.steps,
+                            flops_per_launch=a["flops"] / a["launches"], traffic=roofline_excl["traffic"])
+        if args.kernel_table:
+            log("-- one-stream pass --")
+            kernel_table(agg1, extra)
+            log(f"matrix-core kernels alone: {totals_excl['ms_per_step']:.3f} ms/step, {totals_excl['tflops']:.1f} TFLOP/s; "
+                f"wall {serial_ms:.3f} ms/step")
 
     # free the net before the stand-alone update benchmark
     del st
     torch.cuda.empty_cache()
     grad_update = None if args.skip_update_bench else grad_update_standalone(cg, torch, max(args.steps, 5), args.warmup)
+    if grad_update:
+        for k, v in grad_update.items():
+            t = traffic.get(f"standalone_update_{k}")
+            v["traffic"] = (t["fetch_bytes"] + t["write_bytes"]) if t else None
     cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
 
     out = {
@@ -223,10 +296,18 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"alexnet_shaped_train_step_B{B}_K{K}", "global_batch": B, "peers": K,
                    "schedule": "serial" if args.serial else "overlap", "lr": 0.01, "mu": 0.9, "wd": 5e-4},
-        "roofline": roofline,
-        "update_roofline": update_roofline,
-        "matrix_core_overall": {"tflops": all_flops / all_ms / 1e9, "ms_per_step": all_ms / args.steps,
-                                "frac": all_flops / all_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS},
+        # the kernel's own speed: timed alone on the GPU (one-stream pass of the same iteration, same
+        # process, HIP events around every launch); the shared-GPU durations of the timed region follow
+        "roofline": roofline_excl if roofline_excl else roofline,
+        "roofline_in_timed_region": roofline,
+        "update_roofline": update_excl if update_excl else update_roofline,
+        "update_roofline_in_timed_region": update_roofline,
+        "whole_step_matrix_core": {"tflops": totals["flops_per_step"] / (ms_per_step * 1e-3) / 1e12,
+                                   "frac": totals["flops_per_step"] / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+                                   "what": "algorithmic FLOP of all matrix-core launches of a step / wall time of the step "
+                                           "(glue layers and updates included in the time)"},
+        "matrix_core_kernels_exclusive": totals_excl,
+        "serial_schedule_ms_per_step": serial_ms,
         "grad_update": grad_update,
         "cpu_baseline": cpu,
         "loss": loss,

@@ -1,0 +1,75 @@
+#!/usr/bin/env python3
+"""HBM traffic per kernel launch from two rocprofv3 counter runs of bench.py.
+
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d <dirF> -o f -- python3 bench.py <args>
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d <dirW> -o w -- python3 bench.py <args>
+    python3 paper_1706_00095_amd/pmc_traffic.py <dirF>/f_counter_collection.csv <dirW>/w_counter_collection.csv \
+            <out.json> <out.txt> "<args>"
+
+Each counter is scaled by what it reads for the 256 MiB plain copy bench.py runs first
+(cg::debug_copy_kernel: 256 MiB fetched, 256 MiB written).  Kernel names are mapped to the labels
+the library's per-launch profile uses, and the result is the mean over a label's launches.
+"""
+import collections
+import csv
+import json
+import re
+import sys
+
+COPY_BYTES = 256 << 20
+
+
+def label(name):
+    name = name.replace("(anonymous namespace)::", "").replace("void ", "")
+    m = re.match(r"cg::igemm_patch_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+)>", name)
+    if m:
+        wm, _, tm, _, _, nsl = map(int, m.groups())
+        return f"igemm_patch_kernel<{wm * tm * 32}x128,{nsl}>"
+    m = re.match(r"cg::igemm_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), cg::(\w+)<(\d+)(?:, (\w+))?>, cg::(\w+)<(\d+)(?:, (\w+))?> ?>", name)
+    if m:
+        wm, wn, tm, tn = (int(m.group(i)) for i in (1, 2, 3, 4))
+        code = {"KLoader4": "4", "KLoader": "k", "RowsLoader": "r"}
+        return f"igemm_kernel<{wm * tm * 32}x{wn * tn * 32},{code[m.group(6)]}{code[m.group(9)]}{'c' if m.group(11) == 'true' else '-'}>"
+    m = re.match(r"cg::(\w+)(<[^(]*>)?", name)
+    if m:
+        return m.group(1) + (m.group(2) or "").replace(" ", "")
+    return None
+
+
+def load(path):
+    d = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        if "cg::" not in r["Kernel_Name"]:
+            continue
+        lab = label(r["Kernel_Name"])
+        if lab:
+            d[lab].append(float(r["Counter_Value"]))
+    return d
+
+
+def main():
+    fpath, wpath, out_json, out_txt, args = sys.argv[1:6]
+    f, w = load(fpath), load(wpath)
+    kf = COPY_BYTES / f["debug_copy_kernel"][0]
+    kw = COPY_BYTES / w["debug_copy_kernel"][0]
+    res = {}
+    for lab in sorted(f, key=lambda k: -sum(f[k])):
+        fb = sum(f[lab]) / len(f[lab]) * kf
+        wb = sum(w.get(lab, [0.0])) / max(len(w.get(lab, [0.0])), 1) * kw
+        res[lab] = dict(fetch_bytes=fb, write_bytes=wb, launches=len(f[lab]))
+    json.dump(dict(command_args=args, scale_fetch_bytes_per_count=kf, scale_write_bytes_per_count=kw, kernels=res),
+              open(out_json, "w"), indent=1)
+    with open(out_txt, "w") as o:
+        o.write("# HBM traffic per kernel launch (bytes fetched from / written to memory behind L2), mean over the launches of a label\n")
+        o.write("# commands (from the repository root on the MI355X box), one counter per run:\n")
+        o.write(f"#   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_f -o f -- python3 bench.py {args}\n")
+        o.write(f"#   rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_w -o w -- python3 bench.py {args}\n")
+        o.write("#   python3 paper_1706_00095_amd/pmc_traffic.py gpurun_out/pmc_f/f_counter_collection.csv gpurun_out/pmc_w/w_counter_collection.csv <json> <txt> '<args>'\n")
+        o.write(f"# scale from the 256 MiB copy (cg::debug_copy_kernel): {kf:.1f} bytes per FETCH_SIZE count, {kw:.1f} bytes per WRITE_SIZE count\n")
+        o.write(f"{'kernel label':44s} {'launches':>8s} {'fetch MB':>10s} {'write MB':>10s}\n")
+        for lab, v in res.items():
+            o.write(f"{lab:44s} {v['launches']:8d} {v['fetch_bytes'] / 1e6:10.1f} {v['write_bytes'] / 1e6:10.1f}\n")
+
+
+if __name__ == "__main__":
+    main()
