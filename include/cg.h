@@ -204,6 +204,13 @@ int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
  * tests.  count receives the number of 4-byte elements. */
 int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count);
 
+/* Test hook: forward and stride-1 backward-data convolutions with enough
+ * output tiles to fill the chip without cutting the reduction (512 by default)
+ * run a kernel that stages raw image rows instead of gathered im2col tiles;
+ * tests lower the threshold so that small shapes the oracle can check element
+ * by element take that path too.  Process-wide, not thread-safe. */
+int cg_debug_patch_min_tiles(int tiles);
+
 /* Measurement aid: dst[0..bytes) = src[0..bytes) by a plain kernel (16-byte
  * aligned device pointers, bytes % 16 == 0): a dispatch of known HBM traffic to
  * scale hardware-counter readings of the other kernels by. */

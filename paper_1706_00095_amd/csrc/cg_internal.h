@@ -148,6 +148,8 @@ struct IgemmProblem {
 // Fills the derived fields of a patch description (Wp, Rfull, dividers) and decides whether the
 // patch kernel can run it for N output pixels and M rows: sets g.nsl, returns true if usable.
 bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups);
+// smallest number of C tiles for which the patch kernel is chosen (512; tests lower it)
+void patch_set_min_tiles(uint32_t t);
 
 // Validates the problem against what the kernels assume and launches it.
 int igemm_launch(const IgemmProblem &p, hipStream_t stream);

@@ -518,6 +518,13 @@ extern "C" int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operan
     return CG_OK;
 }
 
+extern "C" int cg_debug_patch_min_tiles(int tiles)
+{
+    if (tiles < 1) return CG_EINVAL;
+    patch_set_min_tiles((uint32_t)tiles);
+    return CG_OK;
+}
+
 extern "C" int cg_conv_out_shape(const cg_conv_desc *d, int *OH, int *OW)
 {
     return conv_check(d, OH, OW);

@@ -738,6 +738,9 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
 
 }  // namespace
 
+static uint32_t g_patch_min_tiles = 512;
+void patch_set_min_tiles(uint32_t t) { g_patch_min_tiles = t; }
+
 bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
 {
     g.nsl = 0;
@@ -755,7 +758,7 @@ bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
     g.divRfull = make_fastdiv((uint32_t)g.Rfull);
     // enough tiles to fill the chip without cutting K (the patch kernel has no K slices)
     const int mt = patch_mt(M, N, groups);
-    if ((uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups < 512) return false;
+    if ((uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups < g_patch_min_tiles) return false;
     // The largest patch any block needs: a fragment read reaches (KH-1)*Wp + KW-1 beyond sigma, and
     // sigma + that stays below the slot count of the block's segments, which is what is counted.
     auto slots = [&](uint32_t n0, uint32_t n1) {

@@ -106,3 +106,65 @@ def test_alexnet_layer_small_batch_full_spatial_size(orc32, layer):
     rdw, rdb = orc32.conv_bwd_weight(od, x, dy)
     gdw, gdb = conv_bwd_weight(d, dx_, dy_)
     assert max_abs_rel(host(gdw), rdw) <= TOL and max_abs_rel(host(gdb), rdb) <= TOL
+
+
+# Shapes that qualify for the patch kernel (reduction channels per group a multiple of 16, at least
+# five taps) once the tile threshold is lowered: padded borders, 5x5 windows, stride 2, groups, row
+# tiles of 64 / 128 / 192, pixel tiles that span two and more images, ragged last tiles, and images
+# large enough that blocks are confined to one image (27x27 with a 5x5 window).
+PATCH_SHAPES = {
+    "p3x3_13_c32_m128": (3, dict(C=32, H=13, M=128, k=3, stride=1, pad=1, groups=1)),
+    "p3x3_13_g2_m384": (2, dict(C=32, H=13, M=384, k=3, stride=1, pad=1, groups=2)),
+    "p5x5_27_g2": (1, dict(C=32, H=27, M=64, k=5, stride=1, pad=2, groups=2)),
+    "p3x3_7_many_images": (9, dict(C=16, H=7, M=48, k=3, stride=1, pad=1, groups=1)),
+    "p3x3_s2_p1": (2, dict(C=16, H=15, M=32, k=3, stride=2, pad=1, groups=1)),
+    "p3x3_nopad_w11": (2, dict(C=16, H=17, W=11, M=100, k=3, stride=1, pad=0, groups=1)),
+    "p2x3_like_5taps": (2, dict(C=16, H=9, M=16, k=3, stride=1, pad=2, groups=1)),
+}
+
+
+@pytest.fixture
+def patch_path():
+    cg.cg_debug_patch_min_tiles(1)
+    yield
+    cg.cg_debug_patch_min_tiles(512)
+
+
+def _setup_patch(name):
+    B, cfg = PATCH_SHAPES[name]
+    c, x, w, b, dy = cg_synth.conv_layer_tensors(name, B, seed=sum(map(ord, name)), cfg=cfg)
+    Wd = c.get("W", c["H"])
+    d = cg.conv_desc(B, c["C"], c["H"], Wd, c["M"], c["k"], stride=c["stride"], pad=c["pad"], groups=c["groups"])
+    od = odesc(B, c["C"], c["H"], Wd, c["M"], c["k"], c["stride"], c["pad"], c["groups"])
+    return d, od, x, w, b, dy
+
+
+@pytest.mark.parametrize("name", list(PATCH_SHAPES))
+def test_patch_kernel_forward(orc32, patch_path, name):
+    d, od, x, w, b, dy = _setup_patch(name)
+    assert cg.cg_conv_workspace_bytes(d, cg.CG_PASS_FWD) >= w.size * 4        # the tap-major filter copy: patch path taken
+    ref = orc32.conv_fwd(od, x, w, b)
+    got = host(conv_fwd(d, dev(x), dev(w), dev(b)))
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    assert max_abs_rel(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("name", [n for n, (_, c) in PATCH_SHAPES.items() if c["stride"] == 1])
+def test_patch_kernel_backward_data(orc32, patch_path, name):
+    d, od, x, w, b, dy = _setup_patch(name)
+    ref = orc32.conv_bwd_data(od, dy, w)
+    got = host(conv_bwd_data(d, dev(dy), dev(w)))
+    assert np.isfinite(got).all()
+    assert max_abs_rel(got, ref) <= TOL
+
+
+def test_patch_and_gather_kernels_agree(orc32):
+    """The same forward convolution through both kernels: equal up to summation order."""
+    d, od, x, w, b, dy = _setup_patch("p3x3_13_c32_m128")
+    a = host(conv_fwd(d, dev(x), dev(w), dev(b)))
+    cg.cg_debug_patch_min_tiles(1)
+    try:
+        c = host(conv_fwd(d, dev(x), dev(w), dev(b)))
+    finally:
+        cg.cg_debug_patch_min_tiles(512)
+    assert max_abs_rel(c, a) <= 1e-5

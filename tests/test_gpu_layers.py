@@ -1,0 +1,64 @@
+"""GPU parity of the glue layers inside small nets the oracle runs in full: LRN windows the
+streaming kernel specialises (3, 5, 7) and one it does not (4), max-pool windows with and
+without specialisation and with padding, and rectifiers in positions where their forward is
+folded into the producer's store and their backward into the consumer's kernel."""
+import numpy as np
+import pytest
+
+import cg_synth
+from gpu_util import host, max_abs_rel
+from net_util import GpuNet
+from oracle import net as onet
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+SGD = (0.01, 0.9, 5e-4, 1.0)
+
+
+def _net(lrn_size, pool):
+    k, s, p = pool
+    layers = [
+        dict(kind="conv", inputs=[-1], M=20, k=3, stride=1, pad=1, groups=1),
+        dict(kind="relu", inputs=[0]),
+        dict(kind="lrn", inputs=[1], size=lrn_size, alpha=1e-2, beta=0.75 if lrn_size != 7 else 0.6, kappa=1.0),
+        dict(kind="maxpool", inputs=[2], k=k, stride=s, pad=p),
+        dict(kind="conv", inputs=[3], M=16, k=3, stride=1, pad=1, groups=2),
+        dict(kind="relu", inputs=[4]),
+        dict(kind="maxpool", inputs=[5], k=2, stride=2, pad=0),
+        dict(kind="fc", inputs=[6], out=24),
+        dict(kind="relu", inputs=[7]),
+        dict(kind="dropout", inputs=[8], p=0.5),
+        dict(kind="fc", inputs=[9], out=7),
+        dict(kind="softmax_ce", inputs=[10]),
+    ]
+    return layers, (6, 14, 14)
+
+
+@pytest.mark.parametrize("lrn_size,pool", [(3, (3, 2, 0)), (5, (3, 1, 1)), (7, (2, 2, 0)), (4, (4, 3, 1))])
+def test_layer_variants_match_oracle(orc32, lrn_size, pool):
+    layers, in_shape = _net(lrn_size, pool)
+    B = 5
+    t = cg_synth.net_tensors(layers, in_shape, B, 2, seed=40 + lrn_size, num_classes=7, init="fan_in", peer_std=1e-3)
+    gn = GpuNet(layers, in_shape, B, t)
+    gn.step(SGD)
+    gn.sync()
+    buckets = {k: v.copy() for k, v in t["buckets"].items()}
+    loss, acts, aux = onet.forward(orc32, layers, t["x"], buckets, t["labels"], t["masks"])
+    grads, dact, _ = onet.backward(orc32, layers, t["x"], buckets, t["masks"], acts, aux)
+    assert abs(float(host(gn.loss)[0]) - float(loss)) <= TOL * max(1.0, abs(float(loss)))
+    folded_fwd = folded_bwd = 0
+    for li in range(len(layers) - 1):
+        if gn.fused(li):
+            folded_fwd += 1
+            continue
+        assert max_abs_rel(host(gn.act(li)), acts[li].ravel()) <= TOL, ("activation", li, layers[li]["kind"])
+    for li, dref in dact.items():
+        if li == len(layers) - 1:
+            continue
+        if gn.grad_folded(li):
+            folded_bwd += 1
+            continue
+        assert max_abs_rel(host(gn.act(li, 1)), dref.ravel()) <= TOL, ("gradient", li, layers[li]["kind"])
+    assert folded_fwd == 3 and folded_bwd == 3        # the three rectifiers, both directions
+    for li in grads:
+        assert max_abs_rel(host(gn.g[li]), grads[li]) <= TOL, ("g_local", li)
