@@ -1,12 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark: one worker's AlexNet-shaped SGD iteration (forward + backward + per-layer
-gradient aggregation over K peers + model update, overlapped on two streams) on one MI355X.
+gradient aggregation over K peers + model update, overlapped on three streams) on one MI355X.
 
 Prints ONE JSON line.  `value` is images/s of whole iterations with every input resident in
-HBM; `roofline` describes the matrix-core kernel that takes the most time inside the step,
-timed live with HIP events around each of its launches on its own stream; `update_roofline`
-and `grad_update` give the HBM figure of the fused gradient-sum + update kernel; `cpu_baseline`
-is the CPU oracle timed on a bounded sample of the same workload.
+HBM.  `roofline` describes the matrix-core kernel that takes the most time inside the step and
+`update_roofline` the fused gradient-sum + update kernel, both timed with HIP events around each
+launch on its own stream while the kernel has the GPU to itself (a few more iterations with the
+one-stream schedule, right after the timed region); the `*_in_timed_region` objects hold the same
+kernels' durations inside the timed region, where up to three kernels share the GPU.
+`grad_update` is the stand-alone update over the eight AlexNet buckets; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
