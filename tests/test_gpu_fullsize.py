@@ -84,11 +84,38 @@ def test_fully_connected_stack_at_b256(orc32):
     _check_step(orc32, layers, in_shape, B, t)
 
 
-def test_whole_alexnet_shaped_iteration_at_b16(orc32):
+@pytest.mark.parametrize("B,K", [(16, 1), (64, 4)])
+def test_whole_alexnet_shaped_iteration(orc32, B, K):
+    """Configuration 4: B = 64 with K = 4 peers is the per-worker batch the configuration names; B = 16
+    keeps the convolutions below the patch kernel's tile threshold, so both kernel families are
+    checked inside a whole iteration."""
     layers, in_shape = cg_synth.alexnet_layers()
-    B = 16
-    t = cg_synth.net_tensors(layers, in_shape, B, 1, seed=4, num_classes=1000)
+    t = cg_synth.net_tensors(layers, in_shape, B, K, seed=4, num_classes=1000)
     _check_step(orc32, layers, in_shape, B, t)
+
+
+def test_inception_stack_at_its_real_shape(orc32):
+    """Configuration 5: two inception modules on 192 x 28 x 28, B = 32, K = 8 peers."""
+    layers, in_shape = cg_synth.inception_layers()
+    B = 32
+    t = cg_synth.net_tensors(layers, in_shape, B, 8, seed=5, num_classes=1000)
+    _check_step(orc32, layers, in_shape, B, t)
+
+
+def test_update_of_the_eight_alexnet_buckets_in_one_launch(orc32):
+    """Configuration 3 at its real sizes (60 965 224 parameters), K = 4: bit-exact, bucket by bucket."""
+    sgd = (0.01, 0.9, 5e-4, 1.0)
+    K = 4
+    bk = cg_synth.sgd_buckets(K, seed=3, v_zero=False)
+    for b in bk.values():
+        b["g"], b["peers"] = b["g_local"], b["g_peers"]
+    devs = {name: (dev(b["w"]), dev(b["v"]), dev(b["g"]), [dev(p) for p in b["peers"]]) for name, b in bk.items()}
+    cg.cg_grad_reduce_sgd_multi([d[0] for d in devs.values()], [d[1] for d in devs.values()], [d[2] for d in devs.values()],
+                                [d[3] for d in devs.values()], [b["w"].size for b in bk.values()], cg.cg_sgd(*sgd))
+    for name, b in bk.items():
+        orc32.grad_reduce_sgd(b["w"], b["v"], b["g"], b["peers"], *sgd)
+        assert host(devs[name][0]).tobytes() == b["w"].tobytes(), name
+        assert host(devs[name][1]).tobytes() == b["v"].tobytes(), name
 
 
 def _sample_fwd(x, w, b, c, n, m, oh, ow):
