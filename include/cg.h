@@ -211,6 +211,12 @@ int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr
  * by element take that path too.  Process-wide, not thread-safe. */
 int cg_debug_patch_min_tiles(int tiles);
 
+/* Test hook: backward-weight of convolutions with at least nine taps runs a
+ * kernel that stages bands of raw image rows; on = 0 makes every
+ * backward-weight take the gathered kernel instead, so that tests can compare
+ * the two.  Process-wide, not thread-safe. */
+int cg_debug_band_kernel(int on);
+
 /* Measurement aid: dst[0..bytes) = src[0..bytes) by a plain kernel (16-byte
  * aligned device pointers, bytes % 16 == 0): a dispatch of known HBM traffic to
  * scale hardware-counter readings of the other kernels by. */

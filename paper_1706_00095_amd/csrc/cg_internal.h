@@ -123,6 +123,23 @@ struct PatchGeom {
     FastDiv divTpi;
 };
 
+// Backward-weight seen as  dw[m][(c,kh,kw)] = sum over pixels of dy[m][pix] * x[c][window of pix at (kh,kw)]
+// with the input staged as raw padded rows: the reduction walks "units" = (image, band of Rb output
+// rows), whose padded source rows (((rows-1)*s + KH) x Wp slots per channel) a block keeps in LDS for
+// the channels its 128 columns (c,kh,kw) belong to, while dy arrives in K-tiles of 16 pixels.
+struct WgradGeom {
+    const float *x;
+    uint64_t x_elems;
+    int32_t C, Cg, H, W, OH, OW, s, pad_h, pad_w, KH, KW;
+    int32_t M;                // all output channels (dy's channel count)
+    int32_t Wp;               // padded patch width (OW-1)*s + KW
+    int32_t nb, Rb;           // bands per image, output rows per band (the last band of an image takes the rest)
+    int32_t units;            // images * nb
+    int32_t units_per_split;
+    int32_t cpb, nsl;         // channels and 64-slot chunks per channel a block stages: (16, 4) or (8, 8); 0 = unusable
+    FastDiv divOW, divWp, divKK, divKW;
+};
+
 // C[m][n] = sum_k A(m,k) * B(n,k)   (+ bias), for `groups` independent problems, the K range
 // optionally cut into `splits` slices whose partial results go to consecutive output planes.
 struct IgemmProblem {
@@ -143,11 +160,17 @@ struct IgemmProblem {
                               // rectifier: the gradient with respect to the rectifier's input), before accumulate
     int use_patch;            // B is described by `patch` (and A is the matching tap-major matrix); B unused
     PatchGeom patch;
+    int use_wgrad;            // backward-weight from image bands (`wgrad`): A = dy rows, B unused, K counted in pixels
+    WgradGeom wgrad;
 };
 
 // Fills the derived fields of a patch description (Wp, Rfull, dividers) and decides whether the
 // patch kernel can run it for N output pixels and M rows: sets g.nsl, returns true if usable.
 bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups);
+// The same for backward-weight: fills Wp, bands, dividers, chooses the staging and the number of K
+// slices (p.splits, units_per_split); returns true if the band kernel can run the problem.
+bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t images, uint32_t *splits);
+void wgrad_set_enabled(int on);     // tests compare the band kernel with the gathered one
 // smallest number of C tiles for which the patch kernel is chosen (512; tests lower it)
 void patch_set_min_tiles(uint32_t t);
 

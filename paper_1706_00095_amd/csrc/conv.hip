@@ -360,6 +360,19 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
     p.M = Mg; p.N = Kg; p.K = (uint32_t)d.N * Pp;
     p.flops = 2.0 * Mg * (double)Kg * ((double)d.N * P) * G;
     p.groups = G; p.splits = 1; p.k_per_split = p.K;
+    // the band kernel, where it applies: x as padded rows in LDS, dy in tiles of 16 pixels
+    if (d.stride_h == d.stride_w) {
+        WgradGeom wgm{};
+        wgm.x = x; wgm.x_elems = (uint64_t)d.N * d.C * d.H * d.W;
+        wgm.C = d.C; wgm.Cg = Cg; wgm.H = d.H; wgm.W = d.W; wgm.OH = OH; wgm.OW = OW; wgm.s = d.stride_h;
+        wgm.pad_h = d.pad_h; wgm.pad_w = d.pad_w; wgm.KH = d.KH; wgm.KW = d.KW; wgm.M = d.M;
+        uint32_t splits = 1;
+        if (wgrad_plan(wgm, (uint32_t)Mg, (uint32_t)Kg, (uint32_t)G, (uint32_t)d.N, &splits)) {
+            p.use_wgrad = 1;
+            p.wgrad = wgm;
+            p.splits = splits;
+        }
+    }
     return p;
 }
 
@@ -515,6 +528,12 @@ extern "C" int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operan
     int64_t off;
     igemm_host_element(op, row, k, &off, valid);
     *elem_offset = off + (int64_t)group * op.gstride;
+    return CG_OK;
+}
+
+extern "C" int cg_debug_band_kernel(int on)
+{
+    wgrad_set_enabled(on);
     return CG_OK;
 }
 

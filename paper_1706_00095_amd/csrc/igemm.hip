@@ -557,6 +557,205 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
     store_tile<TM, TN>(p, acc, g, 0u, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), n1 + 1, h, li);
 }
 
+// ---- band kernel: backward-weight with the input staged as raw padded rows ------------------------
+//
+//   dw[m][(c,kh,kw)] = sum over pixels (n,oh,ow) of dy[n][m][oh][ow] * x[n][c][oh*s-p+kh][ow*s-p+kw]
+//
+// The gathered kernel fetches x once per filter tap and column tile.  Here the reduction walks
+// "units" = (image, band of output rows); for a unit a block keeps the zero-padded source rows of
+// the CPB input channels its 128 columns (c,kh,kw) belong to in LDS (loaded once per unit), and
+// the B fragment of column (c,kh,kw) at pixel (r,ow) of the band is
+//   patch[c - c0][ (r*s + kh)*Wp + ow*s + kw ] = patch[colbase(lane) + sigma(pixel)],
+// colbase fixed per lane for the whole kernel, sigma computed per K-tile for the eight pixels a
+// lane half multiplies.  dy arrives in K-tiles of 16 consecutive pixels of the band (aligned quads;
+// what a quad reads beyond the band's last pixel meets B values forced to zero).  Pipeline and
+// waits as in the patch kernel above: A ring of NSTA stages, the patch double buffered, the next
+// unit's patch loads issued during the current unit's first K-tile (a unit has >= 5 K-tiles).
+
+template <int WM, int WN, int TM, int TN, int NSTA, int CPB, int NSL>
+__global__ __launch_bounds__(256, 2) void igemm_wgrad_kernel(const IgemmProblem p)
+{
+    static_assert(WM * WN == 4 && WN * TN == 4, "four waves, 128 columns per block");
+    static_assert(CPB % 4 == 0, "whole channels per wave");
+    constexpr int MT = WM * TM * 32, NT = 128;
+    using LA = KLoader4<MT>;
+    constexpr int LAW = LA::LPT;
+    constexpr int CS = NSL * 64 + 1;            // odd: the channels of one tap fall on different banks
+    constexpr int BUF = CPB * CS;
+    constexpr int NB = CPB / 4 * NSL;           // patch load instructions per wave and unit
+    static_assert((NSTA - 1) * LAW + NB <= 63, "the vector-memory counter holds 63 loads");
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];     // [NSTA][LA::SZ] then [2][BUF]
+    float *const sB = smem + NSTA * LA::SZ;
+
+    const WgradGeom &wg = p.wgrad;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t m0 = blockIdx.y * MT, n0 = blockIdx.x * NT;
+    const uint32_t g = blockIdx.z / p.splits, sp = blockIdx.z % p.splits;
+    const int KK = wg.KH * wg.KW, P = wg.OH * wg.OW, HW = wg.H * wg.W;
+    const int u0 = (int)sp * wg.units_per_split, u1 = min(wg.units, u0 + wg.units_per_split);
+
+    const BufferRsrc rsrcA = operand_rsrc(p.A, g);
+    BufferRsrc rsrcX;
+    {
+        const int64_t first = (int64_t)g * wg.Cg * HW;
+        const uint64_t base = (uint64_t)reinterpret_cast<uintptr_t>(wg.x) + (uint64_t)(first * 4);
+        rsrcX.x = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        rsrcX.y = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+        rsrcX.z = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)wg.x_elems - first) * 4));
+        rsrcX.w = 0x00020000u;
+    }
+    LA la;
+    la.init(p.A, m0, p.M, wave, lane);
+
+    const int wm = wave / WN, wn = wave % WN;
+    const int h = lane >> 5, li = lane & 31;
+    const uint32_t c0 = fdiv(n0, wg.divKK);                  // first input channel of this block's columns
+    int32_t colbase[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const uint32_t n = n0 + (uint32_t)((wn * TN + j) * 32 + li);
+        int32_t cb = 0;
+        if (n < p.N) {
+            const uint32_t c = fdiv(n, wg.divKK), tap = n - c * (uint32_t)KK;
+            const uint32_t kh = fdiv(tap, wg.divKW), kw = tap - kh * (uint32_t)wg.KW;
+            cb = (int32_t)(c - c0) * CS + (int32_t)kh * wg.Wp + (int32_t)kw;
+        }
+        colbase[j] = cb;
+    }
+
+    // a unit's band: first output row, number of output rows, pixels, K-tiles
+    auto band_of = [&](int u, int &img, int &oy0, int &rows) {
+        img = u / wg.nb;
+        const int jb = u - img * wg.nb;
+        oy0 = jb * wg.Rb;
+        rows = min(wg.Rb, wg.OH - oy0);
+    };
+    int n_iter = 0;
+    for (int u = u0; u < u1; ++u) {
+        int img, oy0, rows;
+        band_of(u, img, oy0, rows);
+        n_iter += (rows * wg.OW + KT - 1) / KT;
+    }
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // ---- patch loads of unit u (a burst, issued in NPART parts) -----------------------------------
+    uint32_t pvoff[NSL];
+    auto patch_offsets = [&](int u) {          // global byte offset of every slot this lane loads, or out of range
+        int img, oy0, rows;
+        band_of(u, img, oy0, rows);
+        const int prow = (rows - 1) * wg.s + wg.KH, sy0 = oy0 * wg.s - wg.pad_h;
+#pragma unroll
+        for (int e = 0; e < NSL; ++e) {
+            const uint32_t jslot = (uint32_t)(e * 64 + lane);
+            const uint32_t r = fdiv(jslot, wg.divWp), cc = jslot - r * (uint32_t)wg.Wp;
+            const int sy = sy0 + (int)r, sx = (int)cc - wg.pad_w;
+            const bool ok = (int)r < prow && (uint32_t)sy < (uint32_t)wg.H && (uint32_t)sx < (uint32_t)wg.W;
+            pvoff[e] = ok ? (uint32_t)(sy * wg.W + sx) * 4u : OOB_ROW;
+        }
+    };
+    auto issue_patch_part = [&](auto PC, int u) {
+        constexpr int Pn = decltype(PC)::value;
+        if (Pn == 0) patch_offsets(u);
+        const int img = u / wg.nb;
+        float *buf = sB + (u & 1) * BUF;
+#pragma unroll
+        for (int q = Pn * NB / NPART; q < (Pn + 1) * NB / NPART; ++q) {
+            const int cl = wave + 4 * (q / NSL), e = q % NSL;
+            const uint32_t c = c0 + (uint32_t)cl;
+            const uint32_t soff = c < (uint32_t)wg.Cg ? (uint32_t)((img * wg.C + (int)c) * HW) * 4u : OOB_K;
+            load_to_lds(rsrcX, buf + cl * CS + e * 64, pvoff[e], soff);
+        }
+    };
+    // ---- A loads of the K-tile t of unit u: 16 consecutive pixels of dy ---------------------------
+    auto issue_a_part = [&](auto PC, int tile, int u, int t) {
+        constexpr int Pn = decltype(PC)::value;
+        if (Pn == 0) {
+            int img, oy0, rows;
+            band_of(u, img, oy0, rows);
+            const uint32_t k = (uint32_t)(oy0 * wg.OW + t * KT) + la.kq4;            // pixel of this lane's quad in its image
+            la.koff = tile < n_iter ? ((uint32_t)(img * wg.M) * (uint32_t)P + k) * 4u : OOB_K;
+        }
+#pragma unroll
+        for (int j = Pn * LAW / NPART; j < (Pn + 1) * LAW / NPART; ++j)
+            load4_to_lds(rsrcA, smem + (tile % NSTA) * LA::SZ + (wave * LA::NJ + j) * 256, la.roff[j] + la.koff, 0u);
+    };
+    auto tiles_of = [&](int u) {
+        int img, oy0, rows;
+        band_of(u, img, oy0, rows);
+        return (rows * wg.OW + KT - 1) / KT;
+    };
+
+    // prologue: the first unit's patch, then A tiles 0..NSTA-2
+    static_for<0, NPART>([&](auto PC) { issue_patch_part(PC, u0); });
+    int iu = u0, it_ = 0, itiles = tiles_of(u0);        // (unit, tile) of the next A tile to issue
+    auto advance_issue = [&]() {
+        if (++it_ == itiles) { it_ = 0; ++iu; itiles = iu < u1 ? tiles_of(iu) : 1 << 30; }
+    };
+#pragma unroll
+    for (int d = 0; d < NSTA - 1; ++d) {
+        static_for<0, NPART>([&](auto PC) { issue_a_part(PC, d, iu, it_); });
+        advance_issue();
+    }
+
+    int cu = u0, ct = 0, ctiles = tiles_of(u0);         // (unit, tile) being multiplied
+    for (int it = 0; it < n_iter; ++it) {
+        const bool burst = cu + 1 < u1;                 // this unit issues the next one's patch in its tile 0
+        if (burst && ct >= 1 && ct <= NSTA - 2)
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTA - 2) * LAW + NB) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTA - 2) * LAW) : "memory");
+        const float *a_s = smem + (it % NSTA) * LA::SZ;
+        const float *b_s = sB + (cu & 1) * BUF;
+        int img, oy0, rows;
+        band_of(cu, img, oy0, rows);
+        const int npix = rows * wg.OW;
+        float af[KT / 8][TM][4], bf[KT / 8][TN][4];
+#pragma unroll
+        for (int ks = 0; ks < KT / 8; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[ks][i]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int pix = ct * KT + 8 * ks + 4 * h + t;
+                const uint32_t r = fdiv((uint32_t)pix, wg.divOW), ox = (uint32_t)pix - r * (uint32_t)wg.OW;
+                const int sg = (int)(r * (uint32_t)wg.s) * wg.Wp + (int)(ox * (uint32_t)wg.s);
+                const bool live = pix < npix;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const float vv = b_s[live ? colbase[j] + sg : 0];
+                    bf[ks][j][t] = live ? vv : 0.f;
+                }
+            }
+        }
+        const bool do_patch = burst && ct == 0;
+        static_for<0, NPART>([&](auto PC) {
+            constexpr int Pn = decltype(PC)::value, ks = Pn / 4, s4 = Pn % 4;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
+            issue_a_part(PC, it + NSTA - 1, iu, it_);
+            if (do_patch) issue_patch_part(PC, cu + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        advance_issue();
+        if (++ct == ctiles) { ct = 0; ++cu; ctiles = cu < u1 ? tiles_of(cu) : 1 << 30; }
+    }
+    // the padding tiles still in flight write into this block's LDS: let them finish before it is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    store_tile<TM, TN>(p, acc, g, sp, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), p.N, h, li);
+}
+
 namespace {
 
 template <int WM, int WN, int TM, int TN, int NST, class LA, class LB>
@@ -738,6 +937,94 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
 
 }  // namespace
 
+namespace {
+
+template <int TM, int NSTA, int CPB, int NSL>
+int launch_wgrad_cfg(const IgemmProblem &p, hipStream_t stream)
+{
+    constexpr int MT = 2 * TM * 32;
+    using LA = KLoader4<MT>;
+    dim3 grid((p.N + 127) / 128, (p.M + MT - 1) / MT, p.groups * p.splits);
+    if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
+    int rec = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof name, "igemm_wgrad_kernel<%dx128,%d,%d>", MT, CPB, NSL);
+        rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
+    }
+    constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * CPB * (NSL * 64 + 1)) * sizeof(float);
+    static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_wgrad_kernel<2, 2, TM, 2, NSTA, CPB, NSL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((igemm_wgrad_kernel<2, 2, TM, 2, NSTA, CPB, NSL>), grid, dim3(256), lds, stream, p);
+    prof_end(rec, stream);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
+int wgrad_mt(uint32_t M) { return M > 128 && (M + 191) / 192 * 192 <= (M + 127) / 128 * 128 ? 192 : M > 64 ? 128 : 64; }
+
+int wgrad_launch(const IgemmProblem &p, hipStream_t stream)
+{
+    const int mt = wgrad_mt(p.M);
+    if (p.wgrad.cpb == 16) {
+        if (mt == 192) return launch_wgrad_cfg<3, 3, 16, 4>(p, stream);
+        if (mt == 128) return launch_wgrad_cfg<2, 4, 16, 4>(p, stream);
+        return launch_wgrad_cfg<1, 4, 16, 4>(p, stream);
+    }
+    if (mt == 192) return launch_wgrad_cfg<3, 3, 8, 8>(p, stream);
+    if (mt == 128) return launch_wgrad_cfg<2, 4, 8, 8>(p, stream);
+    return launch_wgrad_cfg<1, 4, 8, 8>(p, stream);
+}
+
+}  // namespace
+
+static uint32_t g_wgrad_enabled = 1;
+void wgrad_set_enabled(int on) { g_wgrad_enabled = on ? 1 : 0; }
+
+bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t images, uint32_t *splits)
+{
+    g.cpb = g.nsl = 0;
+    const int KK = g.KH * g.KW;
+    if (!g_wgrad_enabled || KK < 9 || g.s <= 0 || g.Cg <= 0 || images == 0) return false;
+    if (g.x_elems * 4 > kMaxBufferBytes || (uint64_t)images * g.M * g.OH * g.OW * 4 > kMaxBufferBytes) return false;
+    g.Wp = (g.OW - 1) * g.s + g.KW;
+    // channels a block of 128 columns can touch: at most 127/KK + 2
+    const int chans = 127 / KK + 2;
+    const int cpb = chans > 8 ? 16 : 8, nsl = cpb == 16 ? 4 : 8;
+    if (chans > 16) return false;
+    const int max_prow = nsl * 64 / g.Wp;                   // padded source rows that fit the staging
+    const int max_rows = (max_prow - g.KH) / g.s + 1;       // output rows per band
+    if (max_prow < g.KH || max_rows < 1) return false;
+    g.nb = (g.OH + max_rows - 1) / max_rows;
+    g.Rb = (g.OH + g.nb - 1) / g.nb;
+    // every unit needs at least five K-tiles of 16 pixels (the patch of the next unit lands during four)
+    const int last_rows = g.OH - (g.nb - 1) * g.Rb;
+    if (last_rows < 1 || last_rows * g.OW < 5 * KT) return false;
+    if ((uint64_t)images * g.nb >= (1u << 30)) return false;
+    g.units = (int32_t)(images * (uint32_t)g.nb);
+    g.divOW = make_fastdiv((uint32_t)g.OW);
+    g.divWp = make_fastdiv((uint32_t)g.Wp);
+    g.divKK = make_fastdiv((uint32_t)KK);
+    g.divKW = make_fastdiv((uint32_t)g.KW);
+    // K slices: about 1024 blocks, whole units per slice
+    const int mt = wgrad_mt(M);
+    const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
+    uint64_t want = (1024 + tiles - 1) / tiles;
+    if (want > (uint64_t)g.units) want = (uint64_t)g.units;
+    if (want < 1) want = 1;
+    if (want > 4096) want = 4096;
+    g.units_per_split = (int32_t)(((uint64_t)g.units + want - 1) / want);
+    *splits = (uint32_t)(((uint64_t)g.units + g.units_per_split - 1) / g.units_per_split);
+    if ((uint64_t)*splits * groups * M * N >= (1ull << 31)) return false;
+    g.cpb = cpb; g.nsl = nsl;
+    return true;
+}
+
 static uint32_t g_patch_min_tiles = 512;
 void patch_set_min_tiles(uint32_t t) { g_patch_min_tiles = t; }
 
@@ -836,6 +1123,14 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     if (!p.c_ptr || !aligned16(p.c_ptr)) return CG_EINVAL;
     if (p.M == 0 || p.N == 0 || p.K == 0 || p.groups == 0 || p.splits == 0) return CG_EINVAL;
     if (p.M >= (1u << 30) || p.N >= (1u << 30) || p.K >= (1u << 30)) return CG_EUNSUPPORTED;
+    if (p.bias_mode && !p.bias) return CG_EINVAL;
+    if (p.use_wgrad) {         // K slices are whole units here, not k ranges
+        if (!p.wgrad.x || !aligned16(p.wgrad.x) || p.wgrad.cpb == 0 || p.A.check) return CG_EINVAL;
+        p.A.shift = 0;
+        const int rcw = normalise_operand(p.A, p.groups);
+        if (rcw) return rcw;
+        return wgrad_launch(p, stream);
+    }
     if (p.splits > 1 && (p.k_per_split % KT != 0)) return CG_EINVAL;
     if ((uint64_t)p.k_per_split * p.splits < p.K || (uint64_t)p.k_per_split * (p.splits - 1) >= p.K) return CG_EINVAL;
     if (p.bias_mode && !p.bias) return CG_EINVAL;
@@ -964,12 +1259,16 @@ SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups)
 
 size_t igemm_ws_bytes(const IgemmProblem &p)
 {
-    return p.use_patch ? 0 : plan_split(p.M, p.N, p.K, p.groups).ws_bytes;
+    if (p.use_patch) return 0;
+    if (p.use_wgrad) return p.splits > 1 ? (size_t)p.splits * p.groups * p.M * p.N * sizeof(float) : 0;
+    return plan_split(p.M, p.N, p.K, p.groups).ws_bytes;
 }
 
 int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    const SplitPlan pl = p0.use_patch ? SplitPlan{1, p0.K, 0} : plan_split(p0.M, p0.N, p0.K, p0.groups);
+    const SplitPlan pl = p0.use_patch   ? SplitPlan{1, p0.K, 0}
+                         : p0.use_wgrad ? SplitPlan{p0.splits, p0.K, igemm_ws_bytes(p0)}
+                                        : plan_split(p0.M, p0.N, p0.K, p0.groups);
     if (pl.splits <= 1) {
         IgemmProblem p = p0;
         p.splits = 1; p.k_per_split = p.K;

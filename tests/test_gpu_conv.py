@@ -168,3 +168,41 @@ def test_patch_and_gather_kernels_agree(orc32):
     finally:
         cg.cg_debug_patch_min_tiles(512)
     assert max_abs_rel(c, a) <= 1e-5
+
+
+# Backward-weight through the band kernel (input staged as padded rows): whole-image bands (13x13),
+# several bands per image (27x27 with a 5x5 window; 30x30), stride 2, groups, ragged rows and
+# columns, a channel count that leaves the last block of columns half empty.
+BAND_SHAPES = {
+    "b3x3_13_c32_m128": (3, dict(C=32, H=13, M=128, k=3, stride=1, pad=1, groups=1)),
+    "b3x3_13_g2_m384": (2, dict(C=48, H=13, M=384, k=3, stride=1, pad=1, groups=2)),
+    "b5x5_27_g2_c48": (2, dict(C=48, H=27, M=64, k=5, stride=1, pad=2, groups=2)),
+    "b3x3_30_bands": (2, dict(C=20, H=30, M=40, k=3, stride=1, pad=1, groups=1)),
+    "b3x3_s2_p1": (2, dict(C=16, H=31, M=32, k=3, stride=2, pad=1, groups=1)),
+    "b3x3_nopad_w21": (2, dict(C=7, H=15, W=21, M=100, k=3, stride=1, pad=0, groups=1)),
+    "b4x4_p2": (2, dict(C=9, H=16, M=24, k=4, stride=1, pad=2, groups=1)),
+}
+
+
+@pytest.mark.parametrize("name", list(BAND_SHAPES))
+def test_band_kernel_backward_weight(orc32, name):
+    B, cfg = BAND_SHAPES[name]
+    c, x, w, b, dy = cg_synth.conv_layer_tensors(name, B, seed=sum(map(ord, name)), cfg=cfg)
+    Wd = c.get("W", c["H"])
+    d = cg.conv_desc(B, c["C"], c["H"], Wd, c["M"], c["k"], stride=c["stride"], pad=c["pad"], groups=c["groups"])
+    od = odesc(B, c["C"], c["H"], Wd, c["M"], c["k"], c["stride"], c["pad"], c["groups"])
+    rdw, rdb = orc32.conv_bwd_weight(od, x, dy)
+    gdw, gdb = conv_bwd_weight(d, dev(x), dev(dy))
+    gdw, gdb = host(gdw), host(gdb)
+    assert np.isfinite(gdw).all()
+    assert max_abs_rel(gdw, rdw) <= TOL
+    assert max_abs_rel(gdb, rdb) <= TOL
+    # the gathered kernel on the same problem: equal up to summation order
+    cg.cg_debug_band_kernel(False)
+    try:
+        ws_gather = cg.cg_conv_workspace_bytes(d, cg.CG_PASS_BWD_WEIGHT)
+        hdw, _ = conv_bwd_weight(d, dev(x), dev(dy))
+    finally:
+        cg.cg_debug_band_kernel(True)
+    assert max_abs_rel(host(hdw), gdw) <= 1e-5
+    assert ws_gather > 0
