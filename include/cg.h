@@ -211,10 +211,12 @@ int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr
  * by element take that path too.  Process-wide, not thread-safe. */
 int cg_debug_patch_min_tiles(int tiles);
 
-/* Test hook: backward-weight of convolutions with at least nine taps runs a
- * kernel that stages bands of raw image rows; on = 0 makes every
- * backward-weight take the gathered kernel instead, so that tests can compare
- * the two.  Process-wide, not thread-safe. */
+/* Switch for an alternative backward-weight kernel that stages bands of raw
+ * image rows in LDS (convolutions with at least nine taps).  Off by default:
+ * alone on the GPU it is a few percent faster than the gathered kernel at the
+ * 3x3 AlexNet shapes, but beside the backward-data kernels of the three-stream
+ * schedule the whole iteration is slower with it.  on = 1 selects it where it
+ * applies, so that tests can compare the two.  Process-wide, not thread-safe. */
 int cg_debug_band_kernel(int on);
 
 /* Measurement aid: dst[0..bytes) = src[0..bytes) by a plain kernel (16-byte

@@ -31,6 +31,15 @@ namespace {
 #define CG_EXP 0
 #endif
 
+// Blocks a split-K launch aims at, from below: two blocks are resident per compute unit, so up to
+// 512 blocks start together and finish together.  A few blocks more than a whole number of such
+// rounds run an extra round on a nearly empty GPU (1040 blocks took 19 % longer than 1000 on the
+// backward-weight shapes of the benchmark), and one round measured faster than two or three.
+#ifndef CG_SPLIT_BLOCKS
+#define CG_SPLIT_BLOCKS 512
+#endif
+constexpr uint64_t kSplitBlocks = CG_SPLIT_BLOCKS;
+
 constexpr int KT = 16;                       // reduction indices per LDS stage (a ring of NST stages)
 constexpr int NPART = KT / 2;                // MFMA steps per tile = parts the loads of a tile are issued in
 // Offsets that no buffer descriptor of this library covers (descriptors span < 0x7fffff00 bytes).
@@ -983,7 +992,7 @@ int wgrad_launch(const IgemmProblem &p, hipStream_t stream)
 
 }  // namespace
 
-static uint32_t g_wgrad_enabled = 1;
+static uint32_t g_wgrad_enabled = 0;
 void wgrad_set_enabled(int on) { g_wgrad_enabled = on ? 1 : 0; }
 
 bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t images, uint32_t *splits)
@@ -1011,10 +1020,10 @@ bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t 
     g.divWp = make_fastdiv((uint32_t)g.Wp);
     g.divKK = make_fastdiv((uint32_t)KK);
     g.divKW = make_fastdiv((uint32_t)g.KW);
-    // K slices: about 1024 blocks, whole units per slice
+    // K slices: at most kSplitBlocks blocks, whole units per slice
     const int mt = wgrad_mt(M);
     const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
-    uint64_t want = (1024 + tiles - 1) / tiles;
+    uint64_t want = kSplitBlocks / tiles;
     if (want > (uint64_t)g.units) want = (uint64_t)g.units;
     if (want < 1) want = 1;
     if (want > 4096) want = 4096;
@@ -1242,7 +1251,7 @@ SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups)
     const uint32_t mt = (uint32_t)pick_mt(M, N, groups);
     const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
     if (tiles >= 512) return pl;
-    uint64_t want = (1024 + tiles - 1) / tiles;      // aim at ~4 resident blocks per compute unit
+    uint64_t want = kSplitBlocks / tiles;
     const uint64_t max_by_k = K / 128;               // keep at least 8 K-tiles per slice
     if (want > max_by_k) want = max_by_k;
     if (want > 512) want = 512;

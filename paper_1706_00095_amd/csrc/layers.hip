@@ -63,28 +63,59 @@ __global__ __launch_bounds__(TB) void relu_bwd_kernel(const float *__restrict__ 
 }
 
 // Pooling kernels: a block owns `ppb` consecutive (n, c) planes and first copies what it reads
-// (forward: the input planes; backward: dy and the winners) into LDS with coalesced loads, so
-// that the window gathers, whose addresses depend on loaded data in backward, never go to global
-// memory.  All index arithmetic is 32-bit and local to a plane.  KT/ST are the window and stride
-// when known at compile time (the divisions by the stride are most of the arithmetic otherwise),
-// 0 = use the run-time values.
+// (forward: the input planes; backward: dy and the winners) into LDS, so that the window gathers,
+// whose addresses depend on loaded data in backward, never go to global memory.  The copy issues
+// all of a thread's loads (16 bytes each) before its first LDS write: with one load in flight
+// per thread the copy would run at the latency of HBM, not at its bandwidth.  All index
+// arithmetic is 32-bit and local to a plane; the divisions use multipliers computed on the host.
+// KT/ST are the window and stride when known at compile time, 0 = use the run-time values.
 constexpr int POOL_LDS = 8192;         // elements of LDS staging per block (floats, or float + int pairs)
+constexpr int STAGE_U = 8;             // 16-byte loads a thread keeps in flight while staging
+
+// Copies g[0..n) to s[0..n).  `s` is placed by the caller so that s and g have the same offset
+// within a 16-byte group (s = base + ((address of g / 4) & 3), base 16-byte aligned): the groups
+// in between are moved whole, the up to three elements before and after them one by one.
+__device__ __forceinline__ void stage_to_lds(const float *__restrict__ g, float *s, uint32_t n)
+{
+    const uint32_t head = min(n, (4u - (uint32_t)(((uintptr_t)g >> 2) & 3u)) & 3u);
+    const uint32_t n4 = (n - head) / 4, tail0 = head + n4 * 4;
+    if (threadIdx.x < head) s[threadIdx.x] = g[threadIdx.x];
+    if (tail0 + threadIdx.x < n) s[tail0 + threadIdx.x] = g[tail0 + threadIdx.x];
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 *g4 = reinterpret_cast<const f4 *>(g + head);
+    f4 *s4 = reinterpret_cast<f4 *>(s + head);
+    for (uint32_t q0 = threadIdx.x; q0 < n4; q0 += TB * STAGE_U) {
+        f4 v[STAGE_U];
+#pragma unroll
+        for (int u = 0; u < STAGE_U; ++u) {
+            const uint32_t q = q0 + u * TB;
+            if (q < n4) v[u] = __builtin_nontemporal_load(g4 + q);
+        }
+#pragma unroll
+        for (int u = 0; u < STAGE_U; ++u) {
+            const uint32_t q = q0 + u * TB;
+            if (q < n4) s4[q] = v[u];
+        }
+    }
+}
 
 template <int KT, int ST>
 __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                          int32_t *__restrict__ argmax, uint32_t planes, int ppb, int H,
-                                                         int W, int OH, int OW, int k_rt, int s_rt, int p)
+                                                         int W, int OH, int OW, int k_rt, int s_rt, int p, FastDiv divP,
+                                                         FastDiv divOW)
 {
-    __shared__ float xs[POOL_LDS];
+    extern __shared__ __align__(16) float pool_lds[];
     const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
     const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
     const uint32_t np = min((uint32_t)ppb, planes - plane0);
     const float *xg = x + (size_t)plane0 * Q;
-    for (uint32_t j = threadIdx.x; j < np * Q; j += TB) xs[j] = xg[j];
+    float *xs = pool_lds + (((uintptr_t)xg >> 2) & 3u);
+    stage_to_lds(xg, xs, np * Q);
     __syncthreads();
     for (uint32_t j = threadIdx.x; j < np * P; j += TB) {
-        const uint32_t pl = j / P, o = j - pl * P;
-        const int oh = (int)(o / (uint32_t)OW), ow = (int)(o - (uint32_t)oh * OW);
+        const uint32_t pl = fdiv(j, divP), o = j - pl * P;
+        const int oh = (int)fdiv(o, divOW), ow = (int)(o - (uint32_t)oh * OW);
         const float *xp = xs + pl * Q;
         int best = -1;
         float bv = 0.f;
@@ -106,45 +137,192 @@ __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(const float *__restrict
 // Gather form: an input element collects dy from every window that covers it and elected it.
 // `gate`, if given, is the output of the rectifier that produced this layer's input: the result
 // is then the gradient with respect to the rectifier's INPUT (zero where the gate is not positive).
+// What a thread reads from global memory in the main loop (gate, dx when accumulating) is loaded
+// four elements ahead of the arithmetic.
 template <int KT, int ST, int ACC>
 __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict__ dy,
                                                          const int32_t *__restrict__ argmax, float *__restrict__ dx,
                                                          const float *__restrict__ gate, uint32_t planes, int ppb,
-                                                         int H, int W, int OH, int OW, int k_rt, int s_rt, int p)
+                                                         int H, int W, int OH, int OW, int k_rt, int s_rt, int p,
+                                                         FastDiv divQ, FastDiv divW, FastDiv divS)
 {
-    __shared__ float gs[POOL_LDS / 2];
-    __shared__ int32_t as[POOL_LDS / 2];
+    extern __shared__ __align__(16) float pool_lds[];
     const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
     const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
     const uint32_t np = min((uint32_t)ppb, planes - plane0);
-    for (uint32_t j = threadIdx.x; j < np * P; j += TB) {
-        gs[j] = dy[(size_t)plane0 * P + j];
-        as[j] = argmax[(size_t)plane0 * P + j];
+    const float *dyg = dy + (size_t)plane0 * P;
+    const float *ag = reinterpret_cast<const float *>(argmax + (size_t)plane0 * P);      // moved as 32-bit words
+    const uint32_t half = ((uint32_t)ppb * P + 4 + 3) & ~3u;
+    float *gs = pool_lds + (((uintptr_t)dyg >> 2) & 3u);
+    float *asf = pool_lds + half + (((uintptr_t)ag >> 2) & 3u);
+    stage_to_lds(dyg, gs, np * P);
+    stage_to_lds(ag, asf, np * P);
+    __syncthreads();
+    const int32_t *as = reinterpret_cast<const int32_t *>(asf);
+    const uint32_t total = np * Q;
+    const size_t g0 = (size_t)plane0 * Q;
+    // (plane, row, column) of the thread's element: one division at the start, then carried along
+    // as the element index advances by the block size
+    const uint32_t stepW = TB % (uint32_t)W, stepH = TB / (uint32_t)W;
+    uint32_t pl = fdiv(threadIdx.x, divQ);
+    uint32_t ih = fdiv(threadIdx.x - pl * Q, divW), iw = threadIdx.x - pl * Q - ih * (uint32_t)W;
+    constexpr int NW = KT ? (KT + ST - 1) / ST : 0;      // windows that can cover an element, per dimension
+    for (uint32_t j0 = threadIdx.x; j0 < total; j0 += TB * 4) {
+        float gt[4], old[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = j0 + u * TB;
+            gt[u] = (gate && j < total) ? gate[g0 + j] : 1.f;
+            old[u] = (ACC && j < total) ? dx[g0 + j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = j0 + u * TB;
+            if (j >= total) break;
+            const int32_t me = (int32_t)(ih * (uint32_t)W + iw);
+            // windows oh with oh*s - p <= ih <= oh*s - p + k - 1  (numerators below are >= 0 where divided)
+            int oh_lo = (int)ih + p - k + 1;
+            oh_lo = oh_lo <= 0 ? 0 : (int)(ST ? (uint32_t)(oh_lo + s - 1) / (uint32_t)(ST ? ST : 1)
+                                              : fdiv((uint32_t)(oh_lo + s - 1), divS));
+            int oh_hi = (int)(ST ? (ih + (uint32_t)p) / (uint32_t)(ST ? ST : 1) : fdiv(ih + (uint32_t)p, divS));
+            if (oh_hi > OH - 1) oh_hi = OH - 1;
+            int ow_lo = (int)iw + p - k + 1;
+            ow_lo = ow_lo <= 0 ? 0 : (int)(ST ? (uint32_t)(ow_lo + s - 1) / (uint32_t)(ST ? ST : 1)
+                                              : fdiv((uint32_t)(ow_lo + s - 1), divS));
+            int ow_hi = (int)(ST ? (iw + (uint32_t)p) / (uint32_t)(ST ? ST : 1) : fdiv(iw + (uint32_t)p, divS));
+            if (ow_hi > OW - 1) ow_hi = OW - 1;
+            const int32_t *ap = as + pl * P;
+            const float *gp = gs + pl * P;
+            float acc = 0.f;
+            if (NW) {
+                // a fixed NW x NW sweep, in the same order as the loops below; windows outside
+                // [lo, hi] read a clamped position and are not counted
+#pragma unroll
+                for (int a = NW - 1; a >= 0; --a)
+#pragma unroll
+                    for (int b = NW - 1; b >= 0; --b) {
+                        const int oh = oh_hi - a, ow = ow_hi - b;
+                        const bool in = oh >= oh_lo && ow >= ow_lo;
+                        const int o = in ? oh * OW + ow : 0;
+                        if (in && ap[o] == me) acc += gp[o];
+                    }
+            } else {
+                for (int oh = oh_lo; oh <= oh_hi; ++oh)
+                    for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+                        const int o = oh * OW + ow;
+                        if (ap[o] == me) acc += gp[o];
+                    }
+            }
+            if (!(gt[u] > 0.f)) acc = 0.f;
+            dx[g0 + j] = ACC ? old[u] + acc : acc;
+            iw += stepW;
+            ih += stepH;
+            if (iw >= (uint32_t)W) { iw -= (uint32_t)W; ++ih; }
+            while (ih >= (uint32_t)H) { ih -= (uint32_t)H; ++pl; }
+        }
+    }
+}
+
+// Backward for a window and stride known at compile time.  A thread owns a cell of ST x ST input
+// elements: the (at most NWC x NWC) windows that can cover any of them are read from LDS once,
+// and every element of the cell adds the dy of the windows that elected it, in ascending window
+// order (the order of the gather form above, so the sums are the same bit for bit).  The cell's
+// results go to an LDS copy of the dx planes, which the block then writes out in 16-byte groups,
+// applying `gate` and the accumulation there.
+template <int KT, int ST, int ACC>
+__global__ __launch_bounds__(TB) void maxpool_bwd_cell_kernel(const float *__restrict__ dy,
+                                                              const int32_t *__restrict__ argmax,
+                                                              float *__restrict__ dx, const float *__restrict__ gate,
+                                                              uint32_t planes, int ppb, int H, int W, int OH, int OW,
+                                                              int p, FastDiv divCells, FastDiv divCW)
+{
+    constexpr int NWC = (KT - 1 + ST - 1) / ST + 1;
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    extern __shared__ __align__(16) float pool_lds[];
+    const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW), plane0 = blockIdx.x * (uint32_t)ppb;
+    const uint32_t np = min((uint32_t)ppb, planes - plane0);
+    const float *dyg = dy + (size_t)plane0 * P;
+    const float *ag = reinterpret_cast<const float *>(argmax + (size_t)plane0 * P);      // moved as 32-bit words
+    float *dxg = dx + (size_t)plane0 * Q;
+    const float *gg = gate ? gate + (size_t)plane0 * Q : nullptr;
+    const uint32_t half = ((uint32_t)ppb * P + 4 + 3) & ~3u;
+    float *gs = pool_lds + (((uintptr_t)dyg >> 2) & 3u);
+    float *asf = pool_lds + half + (((uintptr_t)ag >> 2) & 3u);
+    float *os = pool_lds + 2 * half + (((uintptr_t)dxg >> 2) & 3u);
+    stage_to_lds(dyg, gs, np * P);
+    stage_to_lds(ag, asf, np * P);
+    __syncthreads();
+    const int32_t *as = reinterpret_cast<const int32_t *>(asf);
+    const uint32_t CW = (uint32_t)(W + ST - 1) / ST, CH = (uint32_t)(H + ST - 1) / ST, cells = CW * CH;
+    for (uint32_t j = threadIdx.x; j < np * cells; j += TB) {
+        const uint32_t pl = fdiv(j, divCells), cell = j - pl * cells;
+        const uint32_t ca = fdiv(cell, divCW), cb = cell - ca * CW;
+        const int ih0 = (int)ca * ST, iw0 = (int)cb * ST;
+        // first window that can reach the cell's first row / column (numerators >= 0 where divided)
+        int oh0 = ih0 + p - KT + 1, ow0 = iw0 + p - KT + 1;
+        oh0 = oh0 <= 0 ? 0 : (oh0 + ST - 1) / ST;
+        ow0 = ow0 <= 0 ? 0 : (ow0 + ST - 1) / ST;
+        int32_t wa[NWC][NWC];
+        float wg[NWC][NWC];
+#pragma unroll
+        for (int a = 0; a < NWC; ++a)
+#pragma unroll
+            for (int b = 0; b < NWC; ++b) {
+                const int oh = oh0 + a, ow = ow0 + b;
+                const bool in = oh < OH && ow < OW;
+                const uint32_t o = pl * P + (uint32_t)(in ? oh * OW + ow : 0);
+                wa[a][b] = in ? as[o] : -1;
+                wg[a][b] = gs[o];
+            }
+#pragma unroll
+        for (int r = 0; r < ST; ++r)
+#pragma unroll
+            for (int c = 0; c < ST; ++c) {
+                const int ih = ih0 + r, iw = iw0 + c;
+                if (ih >= H || iw >= W) continue;
+                const int32_t me = ih * W + iw;
+                float acc = 0.f;
+#pragma unroll
+                for (int a = 0; a < NWC; ++a)
+#pragma unroll
+                    for (int b = 0; b < NWC; ++b)
+                        if (wa[a][b] == me) acc += wg[a][b];
+                os[pl * Q + (uint32_t)me] = acc;
+            }
     }
     __syncthreads();
-    for (uint32_t j = threadIdx.x; j < np * Q; j += TB) {
-        const uint32_t pl = j / Q, me = j - pl * Q;
-        const int ih = (int)(me / (uint32_t)W), iw = (int)(me - (uint32_t)ih * W);
-        // windows oh with oh*s - p <= ih <= oh*s - p + k - 1  (numerators below are >= 0 where divided)
-        int oh_lo = ih + p - k + 1;
-        oh_lo = oh_lo <= 0 ? 0 : (int)((uint32_t)(oh_lo + s - 1) / (uint32_t)s);
-        int oh_hi = (int)((uint32_t)(ih + p) / (uint32_t)s);
-        if (oh_hi > OH - 1) oh_hi = OH - 1;
-        int ow_lo = iw + p - k + 1;
-        ow_lo = ow_lo <= 0 ? 0 : (int)((uint32_t)(ow_lo + s - 1) / (uint32_t)s);
-        int ow_hi = (int)((uint32_t)(iw + p) / (uint32_t)s);
-        if (ow_hi > OW - 1) ow_hi = OW - 1;
-        const int32_t *ap = as + pl * P;
-        const float *gp = gs + pl * P;
-        float acc = 0.f;
-        for (int oh = oh_lo; oh <= oh_hi; ++oh)
-            for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-                const int o = oh * OW + ow;
-                if (ap[o] == (int32_t)me) acc += gp[o];
-            }
-        const size_t gi = (size_t)plane0 * Q + j;
-        if (gate && !(gate[gi] > 0.f)) acc = 0.f;
-        dx[gi] = ACC ? dx[gi] + acc : acc;
+    // write-out: the groups of four that are aligned in global memory, then the elements around them
+    const uint32_t n = np * Q;
+    const uint32_t head = min(n, (4u - (uint32_t)(((uintptr_t)dxg >> 2) & 3u)) & 3u);
+    const uint32_t n4 = (n - head) / 4, tail0 = head + n4 * 4;
+    for (uint32_t e = threadIdx.x; e < head + (n - tail0); e += TB) {
+        const uint32_t i = e < head ? e : tail0 + (e - head);
+        float v = os[i];
+        if (gg && !(gg[i] > 0.f)) v = 0.f;
+        dxg[i] = ACC ? dxg[i] + v : v;
+    }
+    const f4 *s4 = reinterpret_cast<const f4 *>(os + head);
+    f4 *d4 = reinterpret_cast<f4 *>(dxg + head);
+    const f4 *t4 = reinterpret_cast<const f4 *>(gg ? gg + head : nullptr);
+    for (uint32_t q0 = threadIdx.x; q0 < n4; q0 += TB * 4) {
+        f4 gt[4], old[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t q = q0 + u * TB;
+            gt[u] = (gg && q < n4) ? __builtin_nontemporal_load(t4 + q) : f4{1.f, 1.f, 1.f, 1.f};
+            old[u] = (ACC && q < n4) ? d4[q] : f4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t q = q0 + u * TB;
+            if (q >= n4) break;
+            f4 v = s4[q];
+            v.x = gt[u].x > 0.f ? v.x : 0.f;
+            v.y = gt[u].y > 0.f ? v.y : 0.f;
+            v.z = gt[u].z > 0.f ? v.z : 0.f;
+            v.w = gt[u].w > 0.f ? v.w : 0.f;
+            d4[q] = ACC ? old[u] + v : v;
+        }
     }
 }
 
@@ -180,7 +358,7 @@ __global__ __launch_bounds__(TB) void lrn_fwd_stream_kernel(const float *__restr
         const int cc = c0 - half + d;
         win[d + 1] = (cc >= 0 && cc < C) ? xp[(size_t)cc * HW] : 0.f;
     }
-#pragma unroll 4
+#pragma unroll 12
     for (int c = c0; c < c1; ++c) {
         const int e = c - half + SIZE - 1;
 #pragma unroll
@@ -222,7 +400,7 @@ __global__ __launch_bounds__(TB) void lrn_bwd_stream_kernel(const float *__restr
         const int cc = cs + d;                   // ring holds x[e-SIZE+1 .. e-1] before step cs, e = cs + SIZE - 1
         win[d + 1] = (cc >= 0 && cc < C) ? xp[(size_t)cc * HW] : 0.f;
     }
-#pragma unroll 4
+#pragma unroll 8
     for (int c = cs; c < c1; ++c) {
         const int e = c + SIZE - 1, j = c + half;
 #pragma unroll
@@ -505,9 +683,11 @@ int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, 
     if (H * W > POOL_LDS) return CG_EUNSUPPORTED;        // one input plane must fit the LDS staging
     const int ppb = pool_planes_per_block(OH * OW, H * W, POOL_LDS);
     const dim3 grid((planes + ppb - 1) / ppb);
+    const size_t lds = ((size_t)ppb * H * W + 4) * sizeof(float);
+    const FastDiv divP = make_fastdiv((uint32_t)(OH * OW)), divOW = make_fastdiv((uint32_t)OW);
 #define CG_POOL_FWD(K_, S_)                                                                                          \
-    hipLaunchKernelGGL((maxpool_fwd_kernel<K_, S_>), grid, dim3(TB), 0, st, x, y, argmax, planes, ppb, H, W, OH, OW, k, \
-                       s, p)
+    hipLaunchKernelGGL((maxpool_fwd_kernel<K_, S_>), grid, dim3(TB), lds, st, x, y, argmax, planes, ppb, H, W, OH, OW, k, \
+                       s, p, divP, divOW)
     if (k == 3 && s == 2) CG_POOL_FWD(3, 2);
     else if (k == 3 && s == 1) CG_POOL_FWD(3, 1);
     else if (k == 2 && s == 2) CG_POOL_FWD(2, 2);
@@ -524,22 +704,43 @@ int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, const 
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
     if (OH * OW > POOL_LDS / 2) return CG_EUNSUPPORTED;
-    const int ppb = pool_planes_per_block(H * W, OH * OW, POOL_LDS / 2);
-    const dim3 grid((planes + ppb - 1) / ppb);
-#define CG_POOL_BWD(K_, S_)                                                                                          \
+    const bool cell = ((k == 3 && (s == 2 || s == 1)) || (k == 2 && s == 2)) && 2 * OH * OW + H * W + 20 <= 2 * POOL_LDS;
+    if (cell) {
+        // staging of dy and the winners plus an LDS copy of the dx planes
+        // about 4096 elements a block, within 20 KB of LDS so that eight blocks share a compute unit
+        int ppb = 4096 / (H * W);
+        if (ppb < 1) ppb = 1;
+        while (ppb > 1 && ppb * (2 * OH * OW + H * W) + 20 > 5120) --ppb;
+        const dim3 grid((planes + ppb - 1) / ppb);
+        const size_t lds = (2 * (((size_t)ppb * OH * OW + 4 + 3) & ~(size_t)3) + (size_t)ppb * H * W + 4) * sizeof(float);
+        const uint32_t CW = (uint32_t)(W + s - 1) / s, CH = (uint32_t)(H + s - 1) / s;
+        const FastDiv divCells = make_fastdiv(CW * CH), divCW = make_fastdiv(CW);
+#define CG_POOL_CELL(K_, S_)                                                                                         \
     do {                                                                                                             \
         if (accumulate)                                                                                              \
-            hipLaunchKernelGGL((maxpool_bwd_kernel<K_, S_, 1>), grid, dim3(TB), 0, st, dy, argmax, dx, gate, planes,  \
-                               ppb, H, W, OH, OW, k, s, p);                                                          \
+            hipLaunchKernelGGL((maxpool_bwd_cell_kernel<K_, S_, 1>), grid, dim3(TB), lds, st, dy, argmax, dx, gate,   \
+                               planes, ppb, H, W, OH, OW, p, divCells, divCW);                                       \
         else                                                                                                         \
-            hipLaunchKernelGGL((maxpool_bwd_kernel<K_, S_, 0>), grid, dim3(TB), 0, st, dy, argmax, dx, gate, planes,  \
-                               ppb, H, W, OH, OW, k, s, p);                                                          \
+            hipLaunchKernelGGL((maxpool_bwd_cell_kernel<K_, S_, 0>), grid, dim3(TB), lds, st, dy, argmax, dx, gate,   \
+                               planes, ppb, H, W, OH, OW, p, divCells, divCW);                                       \
     } while (0)
-    if (k == 3 && s == 2) CG_POOL_BWD(3, 2);
-    else if (k == 3 && s == 1) CG_POOL_BWD(3, 1);
-    else if (k == 2 && s == 2) CG_POOL_BWD(2, 2);
-    else CG_POOL_BWD(0, 0);
-#undef CG_POOL_BWD
+        if (k == 3 && s == 2) CG_POOL_CELL(3, 2);
+        else if (k == 3 && s == 1) CG_POOL_CELL(3, 1);
+        else CG_POOL_CELL(2, 2);
+#undef CG_POOL_CELL
+        CG_LAUNCH_CHECK();
+    }
+    const int ppb = pool_planes_per_block(H * W, OH * OW, POOL_LDS / 2);
+    const dim3 grid((planes + ppb - 1) / ppb);
+    const size_t lds = 2 * (((size_t)ppb * OH * OW + 4 + 3) & ~(size_t)3) * sizeof(float);
+    const FastDiv divQ = make_fastdiv((uint32_t)(H * W)), divW = make_fastdiv((uint32_t)W),
+                  divS = make_fastdiv((uint32_t)s);
+    if (accumulate)
+        hipLaunchKernelGGL((maxpool_bwd_kernel<0, 0, 1>), grid, dim3(TB), lds, st, dy, argmax, dx, gate, planes, ppb, H,
+                           W, OH, OW, k, s, p, divQ, divW, divS);
+    else
+        hipLaunchKernelGGL((maxpool_bwd_kernel<0, 0, 0>), grid, dim3(TB), lds, st, dy, argmax, dx, gate, planes, ppb, H,
+                           W, OH, OW, k, s, p, divQ, divW, divS);
     CG_LAUNCH_CHECK();
 }
 
