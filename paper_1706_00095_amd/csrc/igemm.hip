@@ -404,8 +404,8 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 // the awaited A tile is older than all of them, t = 1..NSTA-2; from t = NSTA-1 on the wait covers
 // the patch too, long before the next channel block starts (KK >= 5 > NSTA-1).
 
-template <int NSL> struct PatchB {
-    static constexpr int CS = NSL * 64 + 8;          // LDS floats between channels (+8: lane halves on different banks)
+template <int NSL, int PAD = 8> struct PatchB {
+    static constexpr int CS = NSL * 64 + PAD;        // LDS floats between channels (+8: lane halves on different banks)
     static constexpr int BUF = 16 * CS;              // one buffer: 16 channels
     static constexpr int NB = 4 * NSL;               // load instructions per wave and channel block
 };
@@ -564,6 +564,188 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
     // the padding tiles still in flight write into this block's LDS: let them finish before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     store_tile<TM, TN>(p, acc, g, 0u, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), n1 + 1, h, li);
+}
+
+// ---- patch kernel for at most 48 rows ------------------------------------------------------------
+//
+// The same data movement as igemm_patch_kernel, multiplied with v_mfma_f32_16x16x4_f32: a block
+// owns 16*TM rows (TM <= 3) x 128 pixels, each of its four waves all the rows and 32 pixels.  A
+// group of 48 channels (backward-data of a 5x5 layer whose groups have 48 input channels) then
+// fills its tile, where the 32x32 tiles above would multiply 64 rows for 48.
+// Lane (q = lane / 16, l = lane % 16) supplies A[row l][k = 4q + t] and B[k = 4q + t][pixel l] in
+// step t = 0..3 of a K-tile and holds C[row 4q + r][pixel l], r = 0..3, of each 16x16 sub-tile.
+// The patch buffers put channels NSL*64 + 4 floats apart, so that the four k of a step fall on
+// different quarters of the banks.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int TM, int NSTA, int NSL>
+__global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProblem p)
+{
+    constexpr int MT = TM * 16, NT = 128, TN = 2;
+    using LA = KLoader4<MT>;
+    using PB = PatchB<NSL, 4>;
+    constexpr int LAW = LA::LPT, NB = PB::NB;
+    static_assert(TM >= 1 && TM <= 3 && LA::NJ == 1, "at most 48 rows: one A load per wave and K-tile");
+    static_assert((NSTA - 1) * LAW + NB <= 63, "the vector-memory counter holds 63 loads");
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];     // [NSTA][LA::SZ] then [2][PB::BUF]
+    float *const sB = smem + NSTA * LA::SZ;
+
+    const PatchGeom &pg = p.patch;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t m0 = blockIdx.y * MT, g = blockIdx.z;
+    const int KK = pg.KH * pg.KW, ncb = (int)(pg.Cred / 16), n_iter = ncb * KK;
+    const uint32_t P = pg.divP.d;
+    uint32_t n0, n1;
+    if (pg.tiles_per_img) {
+        const uint32_t b = fdiv(blockIdx.x, pg.divTpi), ti = blockIdx.x - b * pg.divTpi.d;
+        n0 = b * P + ti * NT;
+        n1 = min(n0 + NT - 1, (b + 1) * P - 1);
+    } else {
+        n0 = blockIdx.x * NT;
+        n1 = min(n0 + NT - 1, p.N - 1);
+    }
+
+    const BufferRsrc rsrcA = operand_rsrc(p.A, g);
+    BufferRsrc rsrcB;
+    {
+        const uint64_t base = (uint64_t)reinterpret_cast<uintptr_t>(pg.src) + (uint64_t)((int64_t)g * pg.gstride * 4);
+        rsrcB.x = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        rsrcB.y = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+        rsrcB.z = __builtin_amdgcn_readfirstlane((uint32_t)(((int64_t)pg.src_elems - (int64_t)g * pg.gstride) * 4));
+        rsrcB.w = 0x00020000u;
+    }
+    LA la;
+    la.init(p.A, m0, p.M, wave, lane);
+
+    // where this block's pixels sit (as in igemm_patch_kernel)
+    const uint32_t bA = fdiv(n0, pg.divP), oyA = fdiv(n0 - bA * P, pg.divOW);
+    const uint32_t bB = fdiv(n1, pg.divP), oyB = fdiv(n1 - bB * P, pg.divOW);
+    const int32_t R0 = (int32_t)((((bA == bB) ? oyB : (uint32_t)pg.OHo - 1) - oyA) * pg.s + pg.KH) * pg.Wp;
+    uint32_t voff[NSL];
+#pragma unroll
+    for (int e = 0; e < NSL; ++e) {
+        const int32_t j = e * 64 + lane;
+        const uint32_t d = j < R0 ? 0u : 1u + fdiv((uint32_t)(j - R0), pg.divRfull);
+        const int32_t local = j - (d == 0 ? 0 : R0 + (int32_t)(d - 1) * pg.Rfull);
+        const uint32_t r = fdiv((uint32_t)local, pg.divWp), c = (uint32_t)local - r * (uint32_t)pg.Wp;
+        const uint32_t b = bA + d, oylo = d == 0 ? oyA : 0u;
+        const uint32_t oyhi = b == bB ? oyB : (uint32_t)pg.OHo - 1;
+        const int32_t sy = (int32_t)(oylo * pg.s) + pg.oy0 + (int32_t)r, sx = pg.ox0 + (int32_t)c;
+        const bool ok = b <= bB && r < (oyhi - oylo) * pg.s + pg.KH && (uint32_t)sy < (uint32_t)pg.Hs &&
+                        (uint32_t)sx < (uint32_t)pg.Ws;
+        voff[e] = ok ? (uint32_t)((int32_t)b * pg.img_stride + sy * pg.Ws + sx) * 4u : OOB_ROW;
+    }
+
+    const int q = lane >> 4, l16 = lane & 15;
+    int32_t sig[TN];                 // this lane's pixels in a patch buffer, with its k group's channel offset folded in
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const uint32_t n = n0 + (uint32_t)((wave * TN + j) * 16 + l16);
+        int32_t sg = 0;
+        if (n <= n1) {
+            const uint32_t b = fdiv(n, pg.divP), rem = n - b * P, oy = fdiv(rem, pg.divOW), ox = rem - oy * pg.divOW.d;
+            const uint32_t d = b - bA, oylo = d == 0 ? oyA : 0u;
+            sg = (d == 0 ? 0 : R0 + (int32_t)(d - 1) * pg.Rfull) + (int32_t)((oy - oylo) * pg.s) * pg.Wp + (int32_t)(ox * pg.s);
+        }
+        sig[j] = sg + 4 * q * PB::CS;
+    }
+
+    v4f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+
+    auto issue_patch_part = [&](auto PC, int cb) {
+        constexpr int Pn = decltype(PC)::value;
+        float *buf = sB + (cb & 1) * PB::BUF;
+#pragma unroll
+        for (int qq = Pn * NB / NPART; qq < (Pn + 1) * NB / NPART; ++qq) {
+            const int cl = wave + 4 * (qq / NSL), e = qq % NSL;
+            load_to_lds(rsrcB, buf + cl * PB::CS + e * 64, voff[e], (uint32_t)((cb * 16 + cl) * pg.chan_stride) * 4u);
+        }
+    };
+    auto issue_a_part = [&](auto PC, int tile, int cb, int t) {
+        constexpr int Pn = decltype(PC)::value;
+        const uint32_t k0 = (uint32_t)t * pg.Cred + (uint32_t)cb * 16u;
+        la.template issue_part<Pn>(rsrcA, smem + (tile % NSTA) * LA::SZ, p.A, k0, tile < n_iter ? p.K : 0u, wave, lane);
+    };
+
+    static_for<0, NPART>([&](auto PC) { issue_patch_part(PC, 0); });
+    int icb = 0, it_ = 0;
+    auto advance_issue = [&]() { if (++it_ == KK) { it_ = 0; ++icb; } };
+#pragma unroll
+    for (int d = 0; d < NSTA - 1; ++d) {
+        static_for<0, NPART>([&](auto PC) { issue_a_part(PC, d, icb, it_); });
+        advance_issue();
+    }
+
+    int ccb = 0, ct = 0, cky = 0, ckx = 0;
+    for (int it = 0; it < n_iter; ++it) {
+        const bool burst = ccb + 1 < ncb;
+        if (burst && ct >= 1 && ct <= NSTA - 2)
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTA - 2) * LAW + NB) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTA - 2) * LAW) : "memory");
+        const float *a_s = smem + (it % NSTA) * LA::SZ;
+        const int py = pg.flip ? pg.KH - 1 - cky : cky, px = pg.flip ? pg.KW - 1 - ckx : ckx;
+        const float *b_s = sB + (ccb & 1) * PB::BUF + (py * pg.Wp + px);
+        float af[TM][4], bf[TN][4];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) LA::frag(a_s, i * 16 + l16, q >> 1, q & 1, af[i]);      // the quad k = 4q .. 4q+3
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) bf[j][t] = b_s[sig[j] + t * PB::CS];
+        const bool do_patch = burst && ct == 0;
+        static_for<0, NPART>([&](auto PC) {
+            constexpr int Pn = decltype(PC)::value, t = Pn / 2, j = Pn % 2;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+            issue_a_part(PC, it + NSTA - 1, icb, it_);
+            if (do_patch) issue_patch_part(PC, ccb + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        advance_issue();
+        if (++ckx == pg.KW) { ckx = 0; ++cky; }
+        if (++ct == KK) { ct = 0; cky = 0; ++ccb; }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // epilogue: rectifier, gate and accumulation as in store_tile (this kernel is launched without
+    // split-K; bias modes as there)
+    float *c_base = p.c_ptr + (int64_t)g * p.c_gstride;
+    const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
+    const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const uint32_t n = n0 + (uint32_t)((wave * TN + j) * 16 + l16);
+        if (n > n1) continue;
+        const int32_t coff = map_info(p.c_col, n).off;
+        const float bcol = p.bias_mode == 2 ? bias[n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t m = m0 + (uint32_t)(i * 16 + q * 4 + r);
+                if (m < p.M) {
+                    float val = acc[i][j][r] + bcol;
+                    if (p.bias_mode == 1) val += bias[m];
+                    if (p.relu) val = fmaxf(val, 0.f);
+                    const int32_t idx = (int32_t)m * p.c_row_stride + coff;
+                    if (gate && !(gate[idx] > 0.f)) val = 0.f;
+                    float *dst = c_base + idx;
+                    if (p.accumulate) val += *dst;
+                    *dst = val;
+                }
+            }
+        }
+    }
 }
 
 // ---- band kernel: backward-weight with the input staged as raw padded rows ------------------------
@@ -924,6 +1106,35 @@ int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
     return CG_OK;
 }
 
+template <int TM, int NSTA, int NSL>
+int launch_patch16_cfg(const IgemmProblem &p, hipStream_t stream)
+{
+    constexpr int MT = TM * 16;
+    using LA = KLoader4<MT>;
+    const uint32_t P = p.patch.divP.d;
+    dim3 grid(p.patch.tiles_per_img ? (p.N / P) * (uint32_t)p.patch.tiles_per_img : (p.N + 127) / 128, (p.M + MT - 1) / MT,
+              p.groups);
+    if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
+    int rec = -1;
+    if (prof_on()) {
+        char name[64];
+        snprintf(name, sizeof name, "igemm_patch16_kernel<%dx128,%d>", MT, NSL);
+        rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
+    }
+    constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL, 4>::BUF) * sizeof(float);
+    static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_patch16_kernel<TM, NSTA, NSL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((igemm_patch16_kernel<TM, NSTA, NSL>), grid, dim3(256), lds, stream, p);
+    prof_end(rec, stream);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
 // row-tile height of the patch kernel: 64, 128 or 192 rows
 int patch_mt(uint32_t M, uint32_t N, uint32_t groups)
 {
@@ -933,6 +1144,14 @@ int patch_mt(uint32_t M, uint32_t N, uint32_t groups)
 
 int patch_launch(const IgemmProblem &p, hipStream_t stream)
 {
+    if (p.M <= 48) {             // the 16-row tiles waste less of a small row count than a 64-row tile
+        const int tm = (int)(p.M + 15) / 16;
+        if (p.patch.nsl == 4)
+            return tm == 3 ? launch_patch16_cfg<3, 4, 4>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 4>(p, stream)
+                                                                              : launch_patch16_cfg<1, 4, 4>(p, stream);
+        return tm == 3 ? launch_patch16_cfg<3, 4, 5>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 5>(p, stream)
+                                                                          : launch_patch16_cfg<1, 4, 5>(p, stream);
+    }
     const int mt = patch_mt(p.M, p.N, p.groups);
     if (p.patch.nsl == 4) {
         if (mt == 192) return launch_patch_cfg<3, 3, 4>(p, stream);
