@@ -1541,16 +1541,38 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
 
 namespace {
 
-// block (m, s) sums the samples of slice s; the slices are added afterwards in slice order
+// block (m, s) sums the samples of slice s; the slices are added afterwards in slice order.
+// The (image, group of four pixels) pairs of the slice are spread over the threads, each moving
+// 16 bytes (4-byte aligned: planes of an odd pixel count start anywhere) with four loads in flight.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
 __global__ __launch_bounds__(256) void bias_grad_partial_kernel(const float *__restrict__ dy, int N, int M, int P,
-                                                                int n_per, float *__restrict__ part)
+                                                                int n_per, FastDiv divQP, float *__restrict__ part)
 {
     const int m = blockIdx.x, sl = blockIdx.y;
     const int n_beg = sl * n_per, n_end = min(N, n_beg + n_per);
+    const uint32_t QP = divQP.d, total = (uint32_t)(n_end - n_beg) * QP;
     float s = 0.f;
-    for (int n = n_beg; n < n_end; ++n) {
-        const float *src = dy + ((size_t)n * M + m) * P;
-        for (int q = threadIdx.x; q < P; q += 256) s += src[q];
+    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += 256 * 4) {
+        f4u v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = i0 + u * 256;
+            v[u] = f4u{0.f, 0.f, 0.f, 0.f};
+            if (i < total) {
+                const uint32_t n = fdiv(i, divQP), qd = i - n * QP;
+                const float *src = dy + ((size_t)(n_beg + (int)n) * M + m) * P + 4 * qd;
+                const int rem = P - 4 * (int)qd;
+                if (rem >= 4) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(src));
+                else {
+                    v[u].x = src[0];
+                    if (rem > 1) v[u].y = src[1];
+                    if (rem > 2) v[u].z = src[2];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
     }
     __shared__ float red[256];
     red[threadIdx.x] = s;
@@ -1595,7 +1617,9 @@ int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, 
     const int n_per = (N + S - 1) / S;
     const int S2 = (N + n_per - 1) / n_per;
     float *part = static_cast<float *>(ws);
-    hipLaunchKernelGGL(bias_grad_partial_kernel, dim3(M, S2), dim3(256), 0, stream, dy, N, M, P, n_per, part);
+    if ((uint64_t)n_per * (uint64_t)((P + 3) / 4) >= (1ull << 31)) return CG_EUNSUPPORTED;     // 32-bit pair index
+    hipLaunchKernelGGL(bias_grad_partial_kernel, dim3(M, S2), dim3(256), 0, stream, dy, N, M, P, n_per,
+                       make_fastdiv((uint32_t)(P + 3) / 4), part);
     CG_HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, part, M, S2, db);
     CG_HIP_TRY(hipGetLastError());

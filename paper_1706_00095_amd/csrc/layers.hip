@@ -329,7 +329,7 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_cell_kernel(const float *__res
 // ---- local response normalisation across channels ---------------------------------------------
 //   scale_c = kappa + (alpha/size) * sum_{j in win(c)} x_j^2,  y_c = x_c * scale_c^-beta,
 //   win(c) = [c - half, c - half + size - 1], half = (size-1)/2.
-// A thread owns one pixel and walks along the channels of a chunk with the window in registers:
+// A thread owns four consecutive pixels and walks along the channels of a chunk with the window in registers:
 // every x is read once (plus a halo of size-1 per chunk), nothing but y is written, and backward
 // recomputes the scales from x instead of reading them back.
 
@@ -340,34 +340,82 @@ __device__ __forceinline__ float pow_neg(float sc, float beta)      // sc^-beta,
 }
 
 constexpr int LRN_CH = 48;        // channels per chunk
+constexpr int LRN_V = 4;          // consecutive pixels per thread
+
+// Four consecutive pixels of one channel plane move as one 16-byte access.  The planes of a tensor
+// with an odd pixel count start at any multiple of 4 bytes, which these accesses allow; the last
+// thread of a plane, whose group reaches beyond it, moves its `rem` < 4 pixels one by one.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
+struct Px4 { float v[LRN_V]; };
+
+__device__ __forceinline__ Px4 px_load(const float *__restrict__ p, int rem)
+{
+    Px4 r;
+    if (rem >= LRN_V) {
+        const f4u q = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(p));
+        r.v[0] = q.x; r.v[1] = q.y; r.v[2] = q.z; r.v[3] = q.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < LRN_V; ++e) r.v[e] = e < rem ? p[e] : 0.f;
+    }
+    return r;
+}
+
+__device__ __forceinline__ Px4 px_zero()
+{
+    Px4 r;
+#pragma unroll
+    for (int e = 0; e < LRN_V; ++e) r.v[e] = 0.f;
+    return r;
+}
+
+template <int ACC> __device__ __forceinline__ void px_store(float *__restrict__ p, int rem, const Px4 &r)
+{
+    if (rem >= LRN_V) {
+        f4u q = {r.v[0], r.v[1], r.v[2], r.v[3]};
+        if (ACC) q += *reinterpret_cast<const f4u *>(p);
+        *reinterpret_cast<f4u *>(p) = q;
+    } else {
+#pragma unroll
+        for (int e = 0; e < LRN_V; ++e)
+            if (e < rem) p[e] = ACC ? p[e] + r.v[e] : r.v[e];
+    }
+}
 
 template <int SIZE>
 __global__ __launch_bounds__(TB) void lrn_fwd_stream_kernel(const float *__restrict__ x, float *__restrict__ y, int C,
                                                             int HW, int nchunk, float aos, float beta, float kappa)
 {
     constexpr int half = (SIZE - 1) / 2;
-    const int pix = blockIdx.x * TB + threadIdx.x;
+    const int pix = (blockIdx.x * TB + threadIdx.x) * LRN_V;
     if (pix >= HW) return;
+    const int rem = HW - pix;
     const int n = blockIdx.y / nchunk, c0 = (blockIdx.y % nchunk) * LRN_CH;
     const int c1 = min(C, c0 + LRN_CH);
     const float *xp = x + (size_t)n * C * HW + pix;
     float *yp = y + (size_t)n * C * HW + pix;
-    float win[SIZE];               // x[c - half .. c - half + SIZE - 1] once the step's element has entered
+    Px4 win[SIZE];                 // x[c - half .. c - half + SIZE - 1] once the step's element has entered
 #pragma unroll
     for (int d = 0; d < SIZE - 1; ++d) {
         const int cc = c0 - half + d;
-        win[d + 1] = (cc >= 0 && cc < C) ? xp[(size_t)cc * HW] : 0.f;
+        win[d + 1] = (cc >= 0 && cc < C) ? px_load(xp + (size_t)cc * HW, rem) : px_zero();
     }
-#pragma unroll 12
+#pragma unroll 4
     for (int c = c0; c < c1; ++c) {
         const int e = c - half + SIZE - 1;
 #pragma unroll
         for (int d = 0; d < SIZE - 1; ++d) win[d] = win[d + 1];
-        win[SIZE - 1] = e < C ? xp[(size_t)e * HW] : 0.f;
-        float ss = 0.f;
+        win[SIZE - 1] = e < C ? px_load(xp + (size_t)e * HW, rem) : px_zero();
+        Px4 out;
 #pragma unroll
-        for (int d = 0; d < SIZE; ++d) ss += win[d] * win[d];
-        yp[(size_t)c * HW] = win[half] * pow_neg(kappa + aos * ss, beta);
+        for (int v = 0; v < LRN_V; ++v) {
+            float ss = 0.f;
+#pragma unroll
+            for (int d = 0; d < SIZE; ++d) ss += win[d].v[v] * win[d].v[v];
+            out.v[v] = win[half].v[v] * pow_neg(kappa + aos * ss, beta);
+        }
+        px_store<0>(yp + (size_t)c * HW, rem, out);
     }
 }
 
@@ -382,51 +430,60 @@ __global__ __launch_bounds__(TB) void lrn_bwd_stream_kernel(const float *__restr
                                                             float aos, float coef, float beta, float kappa)
 {
     constexpr int half = (SIZE - 1) / 2;
-    const int pix = blockIdx.x * TB + threadIdx.x;
+    const int pix = (blockIdx.x * TB + threadIdx.x) * LRN_V;
     if (pix >= HW) return;
+    const int rem = HW - pix;
     const int n = blockIdx.y / nchunk, c0 = (blockIdx.y % nchunk) * LRN_CH;
     const int c1 = min(C, c0 + LRN_CH);
     const size_t img = (size_t)n * C * HW + pix;
     const float *xp = x + img, *gp = dy + img;
     float *dp = dx + img;
-    float win[SIZE], tr[SIZE], q[half + 1];      // x window, t ring, dy*scale^-beta of the last half+1 channels
+    Px4 win[SIZE], tr[SIZE], q[half + 1];        // x window, t ring, dy*scale^-beta of the last half+1 channels
 #pragma unroll
-    for (int d = 0; d < SIZE; ++d) tr[d] = 0.f;
+    for (int d = 0; d < SIZE; ++d) tr[d] = px_zero();
 #pragma unroll
-    for (int d = 0; d <= half; ++d) q[d] = 0.f;
+    for (int d = 0; d <= half; ++d) q[d] = px_zero();
     const int cs = c0 - (SIZE - 1);
 #pragma unroll
     for (int d = 0; d < SIZE - 1; ++d) {
         const int cc = cs + d;                   // ring holds x[e-SIZE+1 .. e-1] before step cs, e = cs + SIZE - 1
-        win[d + 1] = (cc >= 0 && cc < C) ? xp[(size_t)cc * HW] : 0.f;
+        win[d + 1] = (cc >= 0 && cc < C) ? px_load(xp + (size_t)cc * HW, rem) : px_zero();
     }
-#pragma unroll 8
+#pragma unroll 2
     for (int c = cs; c < c1; ++c) {
         const int e = c + SIZE - 1, j = c + half;
 #pragma unroll
         for (int d = 0; d < SIZE - 1; ++d) { win[d] = win[d + 1]; tr[d] = tr[d + 1]; }
 #pragma unroll
         for (int d = 0; d < half; ++d) q[d] = q[d + 1];
-        win[SIZE - 1] = (e >= 0 && e < C) ? xp[(size_t)e * HW] : 0.f;
-        float t = 0.f, qq = 0.f;
+        win[SIZE - 1] = (e >= 0 && e < C) ? px_load(xp + (size_t)e * HW, rem) : px_zero();
+        Px4 t = px_zero(), qq = px_zero();
         if (j >= 0 && j < C) {
-            float ss = 0.f;
+            const Px4 g = px_load(gp + (size_t)j * HW, rem);
 #pragma unroll
-            for (int d = 0; d < SIZE; ++d) ss += win[d] * win[d];
-            const float sc = kappa + aos * ss, pw = pow_neg(sc, beta), g = gp[(size_t)j * HW];
-            qq = g * pw;
-            t = qq * win[half] / sc;             // x_j sits at position half of its own window
+            for (int v = 0; v < LRN_V; ++v) {
+                float ss = 0.f;
+#pragma unroll
+                for (int d = 0; d < SIZE; ++d) ss += win[d].v[v] * win[d].v[v];
+                const float sc = kappa + aos * ss, pw = pow_neg(sc, beta);
+                qq.v[v] = g.v[v] * pw;
+                t.v[v] = qq.v[v] * win[half].v[v] / sc;      // x_j sits at position half of its own window
+            }
         }
         tr[SIZE - 1] = t;
         q[half] = qq;
         if (c >= c0) {
-            float cross = 0.f;
+            Px4 out;
 #pragma unroll
-            for (int d = 0; d < SIZE; ++d) cross += tr[d];
-            float gval = q[0] - coef * win[0] * cross;           // x_c = x_{e-SIZE+1}: the oldest ring entry
-            if (GATE && !(win[0] > 0.f)) gval = 0.f;
-            float *dst = dp + (size_t)c * HW;
-            *dst = ACC ? *dst + gval : gval;
+            for (int v = 0; v < LRN_V; ++v) {
+                float cross = 0.f;
+#pragma unroll
+                for (int d = 0; d < SIZE; ++d) cross += tr[d].v[v];
+                float gval = q[0].v[v] - coef * win[0].v[v] * cross;     // x_c = x_{e-SIZE+1}: the oldest ring entry
+                if (GATE && !(win[0].v[v] > 0.f)) gval = 0.f;
+                out.v[v] = gval;
+            }
+            px_store<ACC>(dp + (size_t)c * HW, rem, out);
         }
     }
 }
@@ -750,7 +807,7 @@ int lrn_fwd_launch(const float *x, float *y, int N, int C, int HW, int size, flo
     if (size <= 0 || N <= 0 || C <= 0 || HW <= 0) return CG_EINVAL;
     const float aos = alpha / (float)size;
     const int nchunk = (C + LRN_CH - 1) / LRN_CH;
-    const dim3 grid((HW + TB - 1) / TB, (unsigned)(N * nchunk));
+    const dim3 grid(((HW + LRN_V - 1) / LRN_V + TB - 1) / TB, (unsigned)(N * nchunk));
     if (grid.y > 65535u && (size == 3 || size == 5 || size == 7)) return CG_EUNSUPPORTED;
     switch (size) {
     case 3: hipLaunchKernelGGL(lrn_fwd_stream_kernel<3>, grid, dim3(TB), 0, st, x, y, C, HW, nchunk, aos, beta, kappa); break;
@@ -771,7 +828,7 @@ int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int
     if (size <= 0 || N <= 0 || C <= 0 || HW <= 0) return CG_EINVAL;
     const float aos = alpha / (float)size, coef = 2.f * alpha * beta / (float)size;
     const int nchunk = (C + LRN_CH - 1) / LRN_CH;
-    const dim3 grid((HW + TB - 1) / TB, (unsigned)(N * nchunk));
+    const dim3 grid(((HW + LRN_V - 1) / LRN_V + TB - 1) / TB, (unsigned)(N * nchunk));
     if (grid.y > 65535u && (size == 3 || size == 5 || size == 7)) return CG_EUNSUPPORTED;
 #define CG_LRN_BWD(SZ)                                                                                                \
     do {                                                                                                              \
