@@ -9,10 +9,16 @@
 Each counter is scaled by what it reads for the 256 MiB plain copy bench.py runs first
 (cg::debug_copy_kernel: 256 MiB fetched, 256 MiB written).  Kernel names are mapped to the labels
 the library's per-launch profile uses, and the result is the mean over a label's launches.
+
+    python3 paper_1706_00095_amd/pmc_traffic.py --merge <step.json> <update_only.json> <out.json>
+
+joins the summary of a whole-step run with that of a `bench.py --update-only` run, whose
+reduce_sgd_kernel<K> entries become standalone_update_K<K> (the stand-alone eight-bucket launches).
 """
 import collections
 import csv
 import json
+import os
 import re
 import sys
 
@@ -25,6 +31,14 @@ def label(name):
     if m:
         wm, _, tm, _, _, nsl = map(int, m.groups())
         return f"igemm_patch_kernel<{wm * tm * 32}x128,{nsl}>"
+    m = re.match(r"cg::igemm_patch16_kernel<(\d+), (\d+), (\d+)>", name)
+    if m:
+        tm, _, nsl = map(int, m.groups())
+        return f"igemm_patch16_kernel<{tm * 16}x128,{nsl}>"
+    m = re.match(r"cg::igemm_wgrad_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+)>", name)
+    if m:
+        wm, _, tm, _, _, cpb, nsl = map(int, m.groups())
+        return f"igemm_wgrad_kernel<{wm * tm * 32}x128,{cpb},{nsl}>"
     m = re.match(r"cg::igemm_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), cg::(\w+)<(\d+)(?:, (\w+))?>, cg::(\w+)<(\d+)(?:, (\w+))?> ?>", name)
     if m:
         wm, wn, tm, tn = (int(m.group(i)) for i in (1, 2, 3, 4))
@@ -47,7 +61,22 @@ def load(path):
     return d
 
 
+def merge(step_json, update_json, out_json):
+    a, b = json.load(open(step_json)), json.load(open(update_json))
+    for lab, v in b["kernels"].items():
+        m = re.match(r"reduce_sgd_kernel<(\d+)>", lab)
+        if m:
+            a["kernels"][f"standalone_update_K{m.group(1)}"] = v
+    a["note"] = ("bytes per launch behind L2 (FETCH_SIZE / WRITE_SIZE scaled by a 256 MiB copy); in-step kernels from the "
+                 "one-stream run, standalone_update_K* from bench.py --update-only; the .txt summaries beside this file "
+                 "give the commands")
+    a["update_only_command_args"] = b["command_args"]
+    json.dump(a, open(out_json, "w"), indent=1)
+
+
 def main():
+    if sys.argv[1] == "--merge":
+        return merge(*sys.argv[2:5])
     fpath, wpath, out_json, out_txt, args = sys.argv[1:6]
     f, w = load(fpath), load(wpath)
     kf = COPY_BYTES / f["debug_copy_kernel"][0]
@@ -62,9 +91,9 @@ def main():
     with open(out_txt, "w") as o:
         o.write("# HBM traffic per kernel launch (bytes fetched from / written to memory behind L2), mean over the launches of a label\n")
         o.write("# commands (from the repository root on the MI355X box), one counter per run:\n")
-        o.write(f"#   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_f -o f -- python3 bench.py {args}\n")
-        o.write(f"#   rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_w -o w -- python3 bench.py {args}\n")
-        o.write("#   python3 paper_1706_00095_amd/pmc_traffic.py gpurun_out/pmc_f/f_counter_collection.csv gpurun_out/pmc_w/w_counter_collection.csv <json> <txt> '<args>'\n")
+        o.write(f"#   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d {os.path.dirname(fpath)} -o f -- python3 bench.py {args}\n")
+        o.write(f"#   rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d {os.path.dirname(wpath)} -o w -- python3 bench.py {args}\n")
+        o.write(f"#   python3 paper_1706_00095_amd/pmc_traffic.py {fpath} {wpath} <json> <txt> '<args>'\n")
         o.write(f"# scale from the 256 MiB copy (cg::debug_copy_kernel): {kf:.1f} bytes per FETCH_SIZE count, {kw:.1f} bytes per WRITE_SIZE count\n")
         o.write(f"{'kernel label':44s} {'launches':>8s} {'fetch MB':>10s} {'write MB':>10s}\n")
         for lab, v in res.items():
