@@ -553,8 +553,10 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
+#if CG_EXP != 1
             issue_a_part(PC, it + NSTA - 1, icb, it_);
             if (do_patch) issue_patch_part(PC, ccb + 1);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         });
         advance_issue();
@@ -707,8 +709,10 @@ __global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProble
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+#if CG_EXP != 1
             issue_a_part(PC, it + NSTA - 1, icb, it_);
             if (do_patch) issue_patch_part(PC, ccb + 1);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         });
         advance_issue();

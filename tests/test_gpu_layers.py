@@ -15,7 +15,7 @@ TOL = 1e-3
 SGD = (0.01, 0.9, 5e-4, 1.0)
 
 
-def _net(lrn_size, pool):
+def _net(lrn_size, pool, in_shape=(6, 14, 14)):
     k, s, p = pool
     layers = [
         dict(kind="conv", inputs=[-1], M=20, k=3, stride=1, pad=1, groups=1),
@@ -31,12 +31,17 @@ def _net(lrn_size, pool):
         dict(kind="fc", inputs=[9], out=7),
         dict(kind="softmax_ce", inputs=[10]),
     ]
-    return layers, (6, 14, 14)
+    return layers, in_shape
 
 
-@pytest.mark.parametrize("lrn_size,pool", [(3, (3, 2, 0)), (5, (3, 1, 1)), (7, (2, 2, 0)), (4, (4, 3, 1))])
-def test_layer_variants_match_oracle(orc32, lrn_size, pool):
-    layers, in_shape = _net(lrn_size, pool)
+# the last three: planes of 99, 110 and 225 pixels, whose last group of four pixels (LRN, bias
+# gradient) and whose 16-byte staging groups (pooling) are ragged in every possible way
+@pytest.mark.parametrize("lrn_size,pool,in_shape", [(3, (3, 2, 0), (6, 14, 14)), (5, (3, 1, 1), (6, 14, 14)),
+                                                    (7, (2, 2, 0), (6, 14, 14)), (4, (4, 3, 1), (6, 14, 14)),
+                                                    (5, (3, 2, 0), (5, 9, 11)), (3, (3, 2, 1), (7, 10, 11)),
+                                                    (5, (3, 1, 1), (3, 15, 15))])
+def test_layer_variants_match_oracle(orc32, lrn_size, pool, in_shape):
+    layers, in_shape = _net(lrn_size, pool, in_shape)
     B = 5
     t = cg_synth.net_tensors(layers, in_shape, B, 2, seed=40 + lrn_size, num_classes=7, init="fan_in", peer_std=1e-3)
     gn = GpuNet(layers, in_shape, B, t)
