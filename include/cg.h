@@ -211,6 +211,13 @@ int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr
  * by element take that path too.  Process-wide, not thread-safe. */
 int cg_debug_patch_min_tiles(int tiles);
 
+/* Test hook: the number of blocks the GPU keeps resident at once (512 = 256
+ * compute units x 2), which decides where a patch-kernel launch is cut into a
+ * launch of whole rounds and a launch of smaller tiles for the rest.  Tests
+ * lower it so that small shapes take the two-launch path.  Process-wide, not
+ * thread-safe. */
+int cg_debug_resident_blocks(int blocks);
+
 /* Switch for an alternative backward-weight kernel that stages bands of raw
  * image rows in LDS (convolutions with at least nine taps).  Off by default:
  * alone on the GPU it is a few percent faster than the gathered kernel at the

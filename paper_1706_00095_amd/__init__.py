@@ -23,7 +23,7 @@ LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc":
 EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight",
     "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
-    "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_patch_min_tiles", "cg_debug_band_kernel",
+    "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
 
@@ -192,6 +192,10 @@ def cg_grad_reduce_sgd_multi(ws, vs, gs, peers, ns, sgd, stream=None):
 
 def cg_debug_patch_min_tiles(tiles):
     _check(lib().cg_debug_patch_min_tiles(int(tiles)), "cg_debug_patch_min_tiles")
+
+
+def cg_debug_resident_blocks(blocks):
+    _check(lib().cg_debug_resident_blocks(int(blocks)), "cg_debug_resident_blocks")
 
 
 def cg_debug_band_kernel(on):

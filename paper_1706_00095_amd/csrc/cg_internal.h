@@ -121,6 +121,8 @@ struct PatchGeom {
     int32_t tiles_per_img;    // 0: blocks own 128 consecutive pixels across image boundaries; > 0: every image is
                               // cut into this many blocks of its own (smaller patches for large images)
     FastDiv divTpi;
+    uint32_t tile0;           // first pixel tile of this launch (blockIdx.x counts from it)
+    uint32_t tile_count;      // pixel tiles of this launch; 0 = all
 };
 
 // Backward-weight seen as  dw[m][(c,kh,kw)] = sum over pixels of dy[m][pix] * x[c][window of pix at (kh,kw)]
@@ -172,6 +174,7 @@ bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups);
 bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t images, uint32_t *splits);
 void wgrad_set_enabled(int on);     // tests compare the band kernel with the gathered one
 // smallest number of C tiles for which the patch kernel is chosen (512; tests lower it)
+void patch_set_resident_blocks(uint32_t blocks);
 void patch_set_min_tiles(uint32_t t);
 
 // Validates the problem against what the kernels assume and launches it.

@@ -544,6 +544,13 @@ extern "C" int cg_debug_patch_min_tiles(int tiles)
     return CG_OK;
 }
 
+extern "C" int cg_debug_resident_blocks(int blocks)
+{
+    if (blocks < 1) return CG_EINVAL;
+    patch_set_resident_blocks((uint32_t)blocks);
+    return CG_OK;
+}
+
 extern "C" int cg_conv_out_shape(const cg_conv_desc *d, int *OH, int *OW)
 {
     return conv_check(d, OH, OW);

@@ -39,6 +39,7 @@ namespace {
 #define CG_SPLIT_BLOCKS 512
 #endif
 constexpr uint64_t kSplitBlocks = CG_SPLIT_BLOCKS;
+static uint32_t g_resident_blocks = 512;      // 256 compute units x 2 blocks of the matrix kernels (tests lower it)
 
 constexpr int KT = 16;                       // reduction indices per LDS stage (a ring of NST stages)
 constexpr int NPART = KT / 2;                // MFMA steps per tile = parts the loads of a tile are issued in
@@ -431,12 +432,13 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
     // this block's pixels n0..n1
     const uint32_t P = pg.divP.d;
     uint32_t n0, n1;
+    const uint32_t tile = blockIdx.x + pg.tile0;
     if (pg.tiles_per_img) {
-        const uint32_t b = fdiv(blockIdx.x, pg.divTpi), ti = blockIdx.x - b * pg.divTpi.d;
+        const uint32_t b = fdiv(tile, pg.divTpi), ti = tile - b * pg.divTpi.d;
         n0 = b * P + ti * NT;
         n1 = min(n0 + NT - 1, (b + 1) * P - 1);
     } else {
-        n0 = blockIdx.x * NT;
+        n0 = tile * NT;
         n1 = min(n0 + NT - 1, p.N - 1);
     }
 
@@ -600,12 +602,13 @@ __global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProble
     const int KK = pg.KH * pg.KW, ncb = (int)(pg.Cred / 16), n_iter = ncb * KK;
     const uint32_t P = pg.divP.d;
     uint32_t n0, n1;
+    const uint32_t tile = blockIdx.x + pg.tile0;
     if (pg.tiles_per_img) {
-        const uint32_t b = fdiv(blockIdx.x, pg.divTpi), ti = blockIdx.x - b * pg.divTpi.d;
+        const uint32_t b = fdiv(tile, pg.divTpi), ti = tile - b * pg.divTpi.d;
         n0 = b * P + ti * NT;
         n1 = min(n0 + NT - 1, (b + 1) * P - 1);
     } else {
-        n0 = blockIdx.x * NT;
+        n0 = tile * NT;
         n1 = min(n0 + NT - 1, p.N - 1);
     }
 
@@ -1081,14 +1084,18 @@ int normalise_operand(Operand &o, uint32_t groups)
 
 namespace {
 
+// pixel tiles (blocks along x) of a patch-kernel problem
+uint32_t patch_pixel_tiles(const IgemmProblem &p)
+{
+    return p.patch.tiles_per_img ? (p.N / p.patch.divP.d) * (uint32_t)p.patch.tiles_per_img : (p.N + 127) / 128;
+}
+
 template <int TM, int NSTA, int NSL>
 int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
 {
     constexpr int MT = 2 * TM * 32;
     using LA = KLoader4<MT>;
-    const uint32_t P = p.patch.divP.d;
-    dim3 grid(p.patch.tiles_per_img ? (p.N / P) * (uint32_t)p.patch.tiles_per_img : (p.N + 127) / 128, (p.M + MT - 1) / MT,
-              p.groups);
+    dim3 grid(p.patch.tile_count ? p.patch.tile_count : patch_pixel_tiles(p), (p.M + MT - 1) / MT, p.groups);
     if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
     int rec = -1;
     if (prof_on()) {
@@ -1115,9 +1122,7 @@ int launch_patch16_cfg(const IgemmProblem &p, hipStream_t stream)
 {
     constexpr int MT = TM * 16;
     using LA = KLoader4<MT>;
-    const uint32_t P = p.patch.divP.d;
-    dim3 grid(p.patch.tiles_per_img ? (p.N / P) * (uint32_t)p.patch.tiles_per_img : (p.N + 127) / 128, (p.M + MT - 1) / MT,
-              p.groups);
+    dim3 grid(p.patch.tile_count ? p.patch.tile_count : patch_pixel_tiles(p), (p.M + MT - 1) / MT, p.groups);
     if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
     int rec = -1;
     if (prof_on()) {
@@ -1146,6 +1151,18 @@ int patch_mt(uint32_t M, uint32_t N, uint32_t groups)
     return mt >= 192 && mt != 256 ? 192 : mt >= 96 ? 128 : 64;
 }
 
+int patch_launch_tiles(const IgemmProblem &p, int mt, hipStream_t stream)
+{
+    if (p.patch.nsl == 4) {
+        if (mt == 192) return launch_patch_cfg<3, 3, 4>(p, stream);
+        if (mt == 128) return launch_patch_cfg<2, 4, 4>(p, stream);
+        return launch_patch_cfg<1, 4, 4>(p, stream);
+    }
+    if (mt == 192) return launch_patch_cfg<3, 3, 5>(p, stream);
+    if (mt == 128) return launch_patch_cfg<2, 4, 5>(p, stream);
+    return launch_patch_cfg<1, 4, 5>(p, stream);
+}
+
 int patch_launch(const IgemmProblem &p, hipStream_t stream)
 {
     if (p.M <= 48) {             // the 16-row tiles waste less of a small row count than a 64-row tile
@@ -1157,14 +1174,35 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
                                                                           : launch_patch16_cfg<1, 4, 5>(p, stream);
     }
     const int mt = patch_mt(p.M, p.N, p.groups);
-    if (p.patch.nsl == 4) {
-        if (mt == 192) return launch_patch_cfg<3, 3, 4>(p, stream);
-        if (mt == 128) return launch_patch_cfg<2, 4, 4>(p, stream);
-        return launch_patch_cfg<1, 4, 4>(p, stream);
+    // Two blocks are resident per compute unit, so blocks run in rounds of g_resident_blocks that
+    // start and end together.  When the last round would be less than three quarters full, the
+    // pixel tiles of the whole rounds go out as one launch and the rest as a second launch of
+    // 64-row tiles: three or two small blocks in place of a large one fill the compute units that
+    // the short round would leave idle (676 blocks of 192 rows: 512 + 492 of 64 rows).  Forward only:
+    // backward-data shares the GPU with backward-weight on another stream, whose blocks already
+    // fill those compute units, and a second dependent launch then only delays it (measured).
+    if (mt > 64 && p.patch.tile_count == 0 && !p.patch.flip) {
+        const uint32_t px = patch_pixel_tiles(p), per_px = ((p.M + mt - 1) / mt) * p.groups;
+        const uint64_t blocks = (uint64_t)px * per_px;
+        const uint32_t rounds = (uint32_t)(blocks / g_resident_blocks);
+        const uint32_t rest = (uint32_t)(blocks - (uint64_t)rounds * g_resident_blocks);
+        const uint32_t px_main = rounds * g_resident_blocks / per_px;
+        const uint32_t tail_blocks = (px - px_main) * ((p.M + 63) / 64) * p.groups;
+        if (rounds >= 1 && rest > 0 && rest < g_resident_blocks * 3 / 4 && px_main > 0 && px_main < px &&
+            tail_blocks <= g_resident_blocks) {
+            IgemmProblem a = p, b = p;
+            a.patch.tile0 = 0;
+            a.patch.tile_count = px_main;
+            b.patch.tile0 = px_main;
+            b.patch.tile_count = px - px_main;
+            const double fl = p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups;
+            a.flops = fl * px_main / px;
+            b.flops = fl - a.flops;
+            const int rc = patch_launch_tiles(a, mt, stream);
+            return rc != CG_OK ? rc : patch_launch_tiles(b, 64, stream);
+        }
     }
-    if (mt == 192) return launch_patch_cfg<3, 3, 5>(p, stream);
-    if (mt == 128) return launch_patch_cfg<2, 4, 5>(p, stream);
-    return launch_patch_cfg<1, 4, 5>(p, stream);
+    return patch_launch_tiles(p, mt, stream);
 }
 
 }  // namespace
@@ -1259,6 +1297,7 @@ bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t 
 
 static uint32_t g_patch_min_tiles = 512;
 void patch_set_min_tiles(uint32_t t) { g_patch_min_tiles = t; }
+void patch_set_resident_blocks(uint32_t b) { g_resident_blocks = b; }
 
 bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
 {

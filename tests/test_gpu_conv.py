@@ -158,6 +158,28 @@ def test_patch_kernel_backward_data(orc32, patch_path, name):
     assert max_abs_rel(got, ref) <= TOL
 
 
+# A launch whose last round of resident blocks would be mostly empty goes out as two launches:
+# the pixel tiles of the whole rounds with the large row tile, the rest with 64-row tiles.  With
+# the resident-block count lowered, these shapes take that path (B images of 13x13 pixels).
+@pytest.mark.parametrize("B,M,groups,resident", [(3, 128, 1, 3), (5, 384, 2, 12), (7, 256, 1, 6)])
+def test_patch_kernel_two_launches(orc32, patch_path, B, M, groups, resident):
+    cfg = dict(C=32, H=13, M=M, k=3, stride=1, pad=1, groups=groups)
+    c, x, w, b, dy = cg_synth.conv_layer_tensors("two_launch", B, seed=B * 1000 + M, cfg=cfg)
+    d = cg.conv_desc(B, c["C"], 13, 13, M, 3, stride=1, pad=1, groups=groups)
+    od = odesc(B, c["C"], 13, 13, M, 3, 1, 1, groups)
+    ref = orc32.conv_fwd(od, x, w, b)
+    cg.cg_debug_resident_blocks(resident)
+    cg.cg_profile_enable(True)
+    try:
+        got = host(conv_fwd(d, dev(x), dev(w), dev(b)))
+        names = [cg.cg_profile_get(i)["kernel"] for i in range(cg.cg_profile_count())]
+    finally:
+        cg.cg_profile_enable(False)
+        cg.cg_debug_resident_blocks(512)
+    assert len([n for n in names if n.startswith("igemm_patch_kernel")]) == 2, names
+    assert max_abs_rel(got, ref) <= TOL
+
+
 def test_patch_and_gather_kernels_agree(orc32):
     """The same forward convolution through both kernels: equal up to summation order."""
     d, od, x, w, b, dy = _setup_patch("p3x3_13_c32_m128")
