@@ -27,10 +27,6 @@ typedef uint32_t BufferRsrc __attribute__((ext_vector_type(4)));   // the four d
 
 namespace {
 
-#ifndef CG_EXP
-#define CG_EXP 0
-#endif
-
 // Blocks a split-K launch aims at, from below: two blocks are resident per compute unit, so up to
 // 512 blocks start together and finish together.  A few blocks more than a whole number of such
 // rounds run an extra round on a nearly empty GPU (1040 blocks took 19 % longer than 1000 on the
@@ -264,39 +260,88 @@ __device__ __forceinline__ BufferRsrc operand_rsrc(const Operand &op, uint32_t g
     return r;
 }
 
-// Epilogue of both kernels: a wave's TM x TN accumulator tiles, whose first row / column are
-// (mw, nw), go to C (columns below n_end) with bias, rectifier, gate and accumulation applied.  Accumulator register r of
-// lane (h, li) holds C row 8*(r/4) + 4*h + r%4, column li of its 32x32 sub-tile.
+// Epilogue of the matrix kernels: a wave's TM x TN accumulator tiles, whose first row / column
+// are (mw, nw), go to C (columns below n_end) with bias, rectifier, gate and accumulation applied.
+// Accumulator register r of lane (h, li) holds C row 8*(r/4) + 4*h + r%4, column li of its 32x32
+// sub-tile: stored from there, every store instruction would write 4 bytes per lane in runs of
+// 128 bytes.  Instead each 32-row slab of the wave's tile is turned around in LDS (`wlds`, private
+// to the wave, EpiLds<TN>::FLOATS floats, free once the block has left the K loop) so that a lane
+// owns four consecutive columns of a row and a store instruction writes whole runs of 32*TN
+// columns, 16 bytes per lane (4-byte aligned).  Columns whose C offsets are not consecutive
+// (a pixel tile that crosses into the next image) or that reach beyond n_end go one by one.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
+template <int TN> struct EpiLds {
+    static constexpr int W = TN * 32, LS = W + 8, FLOATS = 32 * LS;
+};
+
 template <int TM, int TN>
 __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&acc)[TM][TN], uint32_t g, uint32_t sp,
-                                           uint32_t mw, uint32_t nw, uint32_t n_end, int h, int li)
+                                           uint32_t mw, uint32_t nw, uint32_t n_end, int lane, float *wlds)
 {
+    constexpr int LS = EpiLds<TN>::LS, QR = TN * 8, RPI = 64 / QR;      // quads per row, rows per instruction
+    const int h = lane >> 5, li = lane & 31, qd = lane % QR, rr = lane / QR;
     float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
     const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
     const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
+    const uint32_t n = nw + 4u * (uint32_t)qd;
+    int32_t off[4];
+    bool ok[4];
+    float bcol[4];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const uint32_t n = nw + (uint32_t)(j * 32 + li);
-        if (n >= n_end) continue;
-        const int32_t coff = map_info(p.c_col, n).off;
-        const float bcol = p.bias_mode == 2 ? bias[n] : 0.f;
+    for (int e = 0; e < 4; ++e) {
+        ok[e] = n + (uint32_t)e < n_end;
+        off[e] = ok[e] ? map_info(p.c_col, n + (uint32_t)e).off : 0;
+        bcol[e] = (p.bias_mode == 2 && ok[e]) ? bias[n + (uint32_t)e] : 0.f;
+    }
+    const bool quad = ok[3] && off[1] == off[0] + 1 && off[2] == off[0] + 2 && off[3] == off[0] + 3;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const uint32_t m = mw + (uint32_t)(i * 32 + (r >> 2) * 8 + h * 4 + (r & 3));
-                if (m < p.M) {
-                    float val = acc[i][j][r] + bcol;
-                    if (p.bias_mode == 1) val += bias[m];
-                    if (p.relu) val = fmaxf(val, 0.f);
-                    const int32_t idx = (int32_t)m * p.c_row_stride + coff;
-                    if (gate && !(gate[idx] > 0.f)) val = 0.f;
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) wlds[((r >> 2) * 8 + h * 4 + (r & 3)) * LS + j * 32 + li] = acc[i][j][r];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // the slab is in LDS (one wave: no barrier)
+#pragma unroll
+        for (int ps = 0; ps < 32 / RPI; ++ps) {
+            const int row = ps * RPI + rr;
+            const uint32_t m = mw + (uint32_t)(i * 32 + row);
+            const float4 q = *reinterpret_cast<const float4 *>(wlds + row * LS + 4 * qd);
+            if (m >= p.M || !ok[0]) continue;
+            float val[4] = {q.x + bcol[0], q.y + bcol[1], q.z + bcol[2], q.w + bcol[3]};
+            const float brow = p.bias_mode == 1 ? bias[m] : 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                val[e] += brow;
+                if (p.relu) val[e] = fmaxf(val[e], 0.f);
+            }
+            const int32_t row_off = (int32_t)m * p.c_row_stride;
+            if (quad) {
+                const int32_t idx = row_off + off[0];
+                if (gate) {
+                    const f4u gt = *reinterpret_cast<const f4u *>(gate + idx);
+                    if (!(gt.x > 0.f)) val[0] = 0.f;
+                    if (!(gt.y > 0.f)) val[1] = 0.f;
+                    if (!(gt.z > 0.f)) val[2] = 0.f;
+                    if (!(gt.w > 0.f)) val[3] = 0.f;
+                }
+                f4u out = {val[0], val[1], val[2], val[3]};
+                if (p.accumulate) out += *reinterpret_cast<const f4u *>(c_base + idx);
+                *reinterpret_cast<f4u *>(c_base + idx) = out;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (!ok[e]) continue;
+                    const int32_t idx = row_off + off[e];
+                    float v = val[e];
+                    if (gate && !(gate[idx] > 0.f)) v = 0.f;
                     float *dst = c_base + idx;
-                    if (p.accumulate) val += *dst;
-                    *dst = val;
+                    if (p.accumulate) v += *dst;
+                    *dst = v;
                 }
             }
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // slab read before the next one overwrites it
     }
 }
 
@@ -374,16 +419,15 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
-#if CG_EXP != 1
             issue_part(PC, it + NST - 1);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
     }
     // the padding tiles still in flight write into this block's LDS: let them finish before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-
-    store_tile<TM, TN>(p, acc, g, sp, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), p.N, h, li);
+    __syncthreads();            // every wave has read its last fragments: the stages are free for the epilogue
+    store_tile<TM, TN>(p, acc, g, sp, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), p.N, lane,
+                       smem + wave * EpiLds<TN>::FLOATS);
 }
 
 // ---- patch kernel: convolutions whose B operand is staged as raw padded image rows ---------------
@@ -555,10 +599,8 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
-#if CG_EXP != 1
             issue_a_part(PC, it + NSTA - 1, icb, it_);
             if (do_patch) issue_patch_part(PC, ccb + 1);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
         advance_issue();
@@ -567,7 +609,9 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
     }
     // the padding tiles still in flight write into this block's LDS: let them finish before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    store_tile<TM, TN>(p, acc, g, 0u, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), n1 + 1, h, li);
+    __syncthreads();            // every wave has read its last fragments: the stages are free for the epilogue
+    store_tile<TM, TN>(p, acc, g, 0u, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), n1 + 1, lane,
+                       smem + wave * EpiLds<TN>::FLOATS);
 }
 
 // ---- patch kernel for at most 48 rows ------------------------------------------------------------
@@ -712,10 +756,8 @@ __global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProble
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
-#if CG_EXP != 1
             issue_a_part(PC, it + NSTA - 1, icb, it_);
             if (do_patch) issue_patch_part(PC, ccb + 1);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
         advance_issue();
@@ -951,7 +993,9 @@ __global__ __launch_bounds__(256, 2) void igemm_wgrad_kernel(const IgemmProblem 
     }
     // the padding tiles still in flight write into this block's LDS: let them finish before it is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    store_tile<TM, TN>(p, acc, g, sp, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), p.N, h, li);
+    __syncthreads();            // every wave has read its last fragments: the stages are free for the epilogue
+    store_tile<TM, TN>(p, acc, g, sp, m0 + (uint32_t)(wm * TM * 32), n0 + (uint32_t)(wn * TN * 32), p.N, lane,
+                       smem + wave * EpiLds<TN>::FLOATS);
 }
 
 namespace {
@@ -969,6 +1013,7 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
         rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = (size_t)NST * (LA::SZ + LB::SZ) * sizeof(float);
+    static_assert(lds >= 4 * EpiLds<TN>::FLOATS * sizeof(float), "the epilogue turns the tile around in the stages' LDS");
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
     static bool attr_set = false;      // raising the dynamic-LDS limit is a per-kernel, one-time host call
     if (!attr_set) {
@@ -1104,6 +1149,7 @@ int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
         rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL>::BUF) * sizeof(float);
+    static_assert(lds >= 4 * EpiLds<2>::FLOATS * sizeof(float), "the epilogue turns the tile around in the stages' LDS");
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
     static bool attr_set = false;
     if (!attr_set) {
@@ -1223,6 +1269,7 @@ int launch_wgrad_cfg(const IgemmProblem &p, hipStream_t stream)
         rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * CPB * (NSL * 64 + 1)) * sizeof(float);
+    static_assert(lds >= 4 * EpiLds<2>::FLOATS * sizeof(float), "the epilogue turns the tile around in the stages' LDS");
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
     static bool attr_set = false;
     if (!attr_set) {
