@@ -30,6 +30,7 @@ SHAPES = {
     "cfg1_layer1": (8, dict(C=3, H=32, M=16, k=3, stride=1, pad=1, groups=1)),
     "cfg1_layer2": (8, dict(C=16, H=32, M=32, k=3, stride=1, pad=1, groups=1)),
     "single_pixel": (1, dict(C=4, H=3, M=4, k=3, stride=1, pad=0, groups=1)),
+    "seven_s2_g2_nopad": (2, dict(C=8, H=21, W=19, M=24, k=7, stride=2, pad=0, groups=2)),
 }
 
 
