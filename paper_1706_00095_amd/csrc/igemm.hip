@@ -302,42 +302,58 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
 #pragma unroll
             for (int r = 0; r < 16; ++r) wlds[((r >> 2) * 8 + h * 4 + (r & 3)) * LS + j * 32 + li] = acc[i][j][r];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // the slab is in LDS (one wave: no barrier)
+        // four row groups at a time: what they read from global memory (gate, C when accumulating)
+        // is loaded before the first of their stores, which the loads could not be moved across
+        constexpr int PB = (32 / RPI) < 4 ? (32 / RPI) : 4;
 #pragma unroll
-        for (int ps = 0; ps < 32 / RPI; ++ps) {
-            const int row = ps * RPI + rr;
-            const uint32_t m = mw + (uint32_t)(i * 32 + row);
-            const float4 q = *reinterpret_cast<const float4 *>(wlds + row * LS + 4 * qd);
-            if (m >= p.M || !ok[0]) continue;
-            float val[4] = {q.x + bcol[0], q.y + bcol[1], q.z + bcol[2], q.w + bcol[3]};
-            const float brow = p.bias_mode == 1 ? bias[m] : 0.f;
+        for (int p0 = 0; p0 < 32 / RPI; p0 += PB) {
+            float4 q[PB];
+            f4u gt[PB], old[PB];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                val[e] += brow;
-                if (p.relu) val[e] = fmaxf(val[e], 0.f);
-            }
-            const int32_t row_off = (int32_t)m * p.c_row_stride;
-            if (quad) {
-                const int32_t idx = row_off + off[0];
-                if (gate) {
-                    const f4u gt = *reinterpret_cast<const f4u *>(gate + idx);
-                    if (!(gt.x > 0.f)) val[0] = 0.f;
-                    if (!(gt.y > 0.f)) val[1] = 0.f;
-                    if (!(gt.z > 0.f)) val[2] = 0.f;
-                    if (!(gt.w > 0.f)) val[3] = 0.f;
+            for (int u = 0; u < PB; ++u) {
+                const int row = (p0 + u) * RPI + rr;
+                const uint32_t m = mw + (uint32_t)(i * 32 + row);
+                q[u] = *reinterpret_cast<const float4 *>(wlds + row * LS + 4 * qd);
+                gt[u] = f4u{1.f, 1.f, 1.f, 1.f};
+                old[u] = f4u{0.f, 0.f, 0.f, 0.f};
+                if (m < p.M) {
+                    const int32_t row_off = (int32_t)m * p.c_row_stride;
+                    if (quad) {
+                        if (gate) gt[u] = *reinterpret_cast<const f4u *>(gate + row_off + off[0]);
+                        if (p.accumulate) old[u] = *reinterpret_cast<const f4u *>(c_base + row_off + off[0]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (gate && ok[e]) gt[u][e] = gate[row_off + off[e]];
+                            if (p.accumulate && ok[e]) old[u][e] = c_base[row_off + off[e]];
+                        }
+                    }
                 }
-                f4u out = {val[0], val[1], val[2], val[3]};
-                if (p.accumulate) out += *reinterpret_cast<const f4u *>(c_base + idx);
-                *reinterpret_cast<f4u *>(c_base + idx) = out;
-            } else {
+            }
+#pragma unroll
+            for (int u = 0; u < PB; ++u) {
+                const int row = (p0 + u) * RPI + rr;
+                const uint32_t m = mw + (uint32_t)(i * 32 + row);
+                if (m >= p.M || !ok[0]) continue;
+                float val[4] = {q[u].x + bcol[0], q[u].y + bcol[1], q[u].z + bcol[2], q[u].w + bcol[3]};
+                const float brow = p.bias_mode == 1 ? bias[m] : 0.f;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    if (!ok[e]) continue;
-                    const int32_t idx = row_off + off[e];
-                    float v = val[e];
-                    if (gate && !(gate[idx] > 0.f)) v = 0.f;
-                    float *dst = c_base + idx;
-                    if (p.accumulate) v += *dst;
-                    *dst = v;
+                    val[e] += brow;
+                    if (p.relu) val[e] = fmaxf(val[e], 0.f);
+                }
+                const int32_t row_off = (int32_t)m * p.c_row_stride;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (!(gt[u][e] > 0.f)) val[e] = 0.f;
+                f4u out = {val[0], val[1], val[2], val[3]};
+                if (p.accumulate) out += old[u];
+                if (quad) {
+                    *reinterpret_cast<f4u *>(c_base + row_off + off[0]) = out;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ok[e]) c_base[row_off + off[e]] = out[e];
                 }
             }
         }
@@ -1072,7 +1088,7 @@ int pick_mt(uint32_t M, uint32_t N, uint32_t groups)
         const uint64_t tiles = (uint64_t)((M + c - 1) / c) * ((N + 127) / 128) * groups;
         double cost;
         if (tiles < 512) {
-            cost = (double)tiles * (c + 50) / 256.0;                  // cut along K into ~4 blocks per unit
+            cost = (double)tiles * (c + 50) / 256.0;                  // cut along K afterwards into one round of resident blocks
         } else {
             const uint64_t n = (tiles + 255) / 256;
             cost = ((n & 1) ? (double)(n - 1) + 1.2 : (double)n) * (c + 50);
