@@ -115,6 +115,102 @@ __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_des
     }
 }
 
+// Backward-data for strides > 1, by stride phase.  The input pixels with (ih mod s_h, iw mod s_w) =
+// (rh, rw) all see the same filter taps, kh = kh0 + s_h*a and kw = kw0 + s_w*b, and reach dy at
+// oh = ih' + qh - a, ow = iw' + qw - b for ih = s_h*ih' + rh: a stride-1 correlation of dy with the
+// sub-sampled filter.  A block owns one phase, 16 x 16 of its pixels, one image and CT input
+// channels of one group; it walks the group's output channels 16 at a time, with the dy window of
+// the tile (zeros outside dy) and the phase's taps of the 16 filters (zeros for taps a phase does
+// not have) staged in LDS, and every thread accumulates its pixel for the CT channels over a fixed
+// AM x AM sweep, AM = the most taps per dimension any phase has.
+// Made for few input channels per group (the first layer of a net: 3), where a matrix-core tile
+// would multiply mostly padding; more channels take several blocks, each re-reading dy.  Plain
+// vector arithmetic: about a third of the issued instructions are useful multiply-adds (the 11x11
+// stride-4 layer at B = 256: 4.9 ms, 11 TFLOP/s; variants that shared the dy window between the
+// phases of a block were slower, this kernel is bound by instruction issue, not by memory).
+constexpr int PH_T = 16;          // tile edge in phase pixels
+constexpr int PH_MC = 16;         // output channels per LDS stage
+
+template <int CT, int AM>
+__global__ __launch_bounds__(256) void bwd_data_phase_kernel(const cg_conv_desc d, int OH, int OW,
+                                                             const float *__restrict__ dy,
+                                                             const float *__restrict__ w, float *__restrict__ dx,
+                                                             const float *__restrict__ gate, int accumulate, int tiles_x,
+                                                             int chunks)
+{
+    constexpr int WT = PH_T + AM - 1, TAPS = AM * AM, TP = (TAPS + 3) / 4 * 4;
+    __shared__ float dys[PH_MC * WT * WT];
+    __shared__ __align__(16) float wsm[PH_MC * CT * TP];
+    const int Cg = d.C / d.groups, Mg = d.M / d.groups, KK = d.KH * d.KW;
+    const int tile_y = blockIdx.x / tiles_x, tile_x = blockIdx.x % tiles_x;
+    const int rh = blockIdx.y / d.stride_w, rw = blockIdx.y % d.stride_w;
+    int z = blockIdx.z;
+    const int chunk = z % chunks; z /= chunks;
+    const int g = z % d.groups, n = z / d.groups;
+    const int c0 = chunk * CT;
+    // taps and dy displacement of this phase
+    const int kh0 = (rh + d.pad_h) % d.stride_h, kw0 = (rw + d.pad_w) % d.stride_w;
+    const int qh = (rh + d.pad_h) / d.stride_h, qw = (rw + d.pad_w) / d.stride_w;
+    const int ty = threadIdx.x / PH_T, tx = threadIdx.x % PH_T;
+    const int oh_base = tile_y * PH_T + qh - (AM - 1), ow_base = tile_x * PH_T + qw - (AM - 1);
+    float acc[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) acc[c] = 0.f;
+    for (int m0 = 0; m0 < Mg; m0 += PH_MC) {
+        const int mc = min(PH_MC, Mg - m0);
+        __syncthreads();
+        for (int i = threadIdx.x; i < PH_MC * WT * WT; i += 256) {
+            const int ml = i / (WT * WT), r = i - ml * (WT * WT), wy = r / WT, wx = r - wy * WT;
+            const int oh = oh_base + wy, ow = ow_base + wx;
+            float v = 0.f;
+            if (ml < mc && (unsigned)oh < (unsigned)OH && (unsigned)ow < (unsigned)OW)
+                v = dy[(((size_t)n * d.M + g * Mg + m0 + ml) * OH + oh) * OW + ow];
+            dys[i] = v;
+        }
+        for (int i = threadIdx.x; i < PH_MC * CT * TP; i += 256) {
+            const int ml = i / (CT * TP), r = i - ml * (CT * TP), c = r / TP, t = r - c * TP;
+            const int kh = kh0 + (t / AM) * d.stride_h, kw = kw0 + (t % AM) * d.stride_w;
+            float v = 0.f;
+            if (ml < mc && c0 + c < Cg && t < TAPS && kh < d.KH && kw < d.KW)
+                v = w[((size_t)(g * Mg + m0 + ml) * Cg + c0 + c) * KK + kh * d.KW + kw];
+            wsm[i] = v;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int ml = 0; ml < PH_MC; ++ml) {          // channels beyond mc are staged as zeros
+            const float *dp = dys + ml * (WT * WT) + (ty + AM - 1) * WT + (tx + AM - 1);
+            float v[TP];
+#pragma unroll
+            for (int t = 0; t < TP; ++t)              // a tap the phase does not have reads nothing (its weight is 0)
+                v[t] = (t < TAPS && kh0 + (t / AM) * d.stride_h < d.KH && kw0 + (t % AM) * d.stride_w < d.KW)
+                           ? dp[-(t / AM) * WT - (t % AM)] : 0.f;
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                const float4 *wq = reinterpret_cast<const float4 *>(wsm + (ml * CT + c) * TP);
+#pragma unroll
+                for (int t4 = 0; t4 < TP / 4; ++t4) {
+                    const float4 q = wq[t4];
+                    acc[c] += v[4 * t4] * q.x;
+                    acc[c] += v[4 * t4 + 1] * q.y;
+                    acc[c] += v[4 * t4 + 2] * q.z;
+                    acc[c] += v[4 * t4 + 3] * q.w;
+                }
+            }
+        }
+    }
+    const int ih = (tile_y * PH_T + ty) * d.stride_h + rh, iw = (tile_x * PH_T + tx) * d.stride_w + rw;
+    if (ih < d.H && iw < d.W) {
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            if (c0 + c >= Cg) continue;
+            const size_t i = (((size_t)n * d.C + g * Cg + c0 + c) * d.H + ih) * d.W + iw;
+            float v = acc[c];
+            if (gate && !(gate[i] > 0.f)) v = 0.f;
+            dx[i] = accumulate ? dx[i] + v : v;
+        }
+    }
+}
+
 }  // namespace
 
 int conv_check(const cg_conv_desc *d, int *OH, int *OW)
@@ -293,6 +389,36 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
     if (d.stride_h != 1 || d.stride_w != 1) {
+        // by stride phase, for at most four taps per dimension and phase
+        const int Cg = d.C / d.groups;
+        const int Ahm = (d.KH + d.stride_h - 1) / d.stride_h, Awm = (d.KW + d.stride_w - 1) / d.stride_w;
+        const int am = Ahm > Awm ? Ahm : Awm;
+        const int th = ((d.H + d.stride_h - 1) / d.stride_h + PH_T - 1) / PH_T;
+        const int tw = ((d.W + d.stride_w - 1) / d.stride_w + PH_T - 1) / PH_T;
+        const int ct = Cg >= 4 ? 4 : Cg;
+        const int chunks = (Cg + ct - 1) / ct;
+        const uint64_t gz = (uint64_t)d.N * d.groups * chunks;
+        if (am <= 4 && d.stride_h * d.stride_w <= 65535 && gz <= 65535) {
+            const dim3 grid((unsigned)(th * tw), (unsigned)(d.stride_h * d.stride_w), (unsigned)gz);
+#define CG_PHASE(CT_, AM_)                                                                                            \
+    hipLaunchKernelGGL((bwd_data_phase_kernel<CT_, AM_>), grid, dim3(256), 0, stream, d, OH, OW, dy, w, dx, gate,      \
+                       accumulate, tw, chunks)
+#define CG_PHASE_AM(CT_)                                                                                              \
+    do {                                                                                                              \
+        if (am == 1) CG_PHASE(CT_, 1);                                                                                \
+        else if (am == 2) CG_PHASE(CT_, 2);                                                                           \
+        else if (am == 3) CG_PHASE(CT_, 3);                                                                           \
+        else CG_PHASE(CT_, 4);                                                                                        \
+    } while (0)
+            if (ct == 4) CG_PHASE_AM(4);
+            else if (ct == 3) CG_PHASE_AM(3);
+            else if (ct == 2) CG_PHASE_AM(2);
+            else CG_PHASE_AM(1);
+#undef CG_PHASE_AM
+#undef CG_PHASE
+            CG_HIP_TRY(hipGetLastError());
+            return CG_OK;
+        }
         const size_t total = (size_t)d.N * d.C * d.H * d.W;
         const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
         hipLaunchKernelGGL(bwd_data_strided_kernel, dim3(blocks), dim3(256), 0, stream, d, OH, OW, dy, w, dx, gate,
