@@ -30,9 +30,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_net(cg, torch, B, K, seed, n_batches=32):
+def build_net(cg, torch, B, K, seed, n_batches=32, inception=False):
     import cg_synth
-    layers, in_shape = cg_synth.alexnet_layers()
+    layers, in_shape = cg_synth.inception_layers() if inception else cg_synth.alexnet_layers()
     gen = torch.Generator(device="cuda").manual_seed(seed)
     net = cg.Net(layers, B, in_shape)
     # a pool of resident batches, one per step of the run where memory allows: random images with
@@ -202,6 +202,8 @@ def main():
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--skip-update-bench", action="store_true", help="leave out the stand-alone update benchmark")
     ap.add_argument("--update-only", action="store_true", help="only the stand-alone update benchmark (for counter runs)")
+    ap.add_argument("--inception-steps", type=int, default=30,
+                    help="steps of the inception-shaped workload timed after the main one (0 = skip)")
     ap.add_argument("--exclusive-steps", type=int, default=5,
                     help="steps of the extra one-stream pass that times every kernel alone on the GPU (0 = skip)")
     args = ap.parse_args()
@@ -292,6 +294,23 @@ def main():
             v["traffic"] = (t["fetch_bytes"] + t["write_bytes"]) if t else None
     cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
 
+    # ---- the second workload shape of the paper (GoogLeNet-like modules), outside the timed region:
+    # two inception modules on 192 x 28 x 28, B = 32, K = 8 peers; many small layers, launch-bound
+    inception = None
+    if args.inception_steps > 0 and not args.serial:
+        ist = build_net(cg, torch, 32, 8, seed=5, n_batches=8, inception=True)
+        torch.cuda.synchronize()
+        run_steps(cg, torch, ist, sgd, 5, cg.CG_STEP_OVERLAP)
+        sync(torch, ist)
+        t0 = time.perf_counter()
+        run_steps(cg, torch, ist, sgd, args.inception_steps, cg.CG_STEP_OVERLAP)
+        sync(torch, ist)
+        ims = (time.perf_counter() - t0) / args.inception_steps * 1e3
+        inception = {"workload": "inception_stack_192x28x28_B32_K8", "ms_per_step": ims, "images_per_s": 32 / (ims * 1e-3),
+                     "steps": args.inception_steps}
+        del ist
+        torch.cuda.empty_cache()
+
     out = {
         "metric": "images/sec per fwd+bwd+update step (AlexNet-shaped B=256); grad-update HBM GB/s",
         "value": B / (ms_per_step * 1e-3), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
@@ -312,6 +331,7 @@ def main():
         "matrix_core_kernels_exclusive": totals_excl,
         "serial_schedule_ms_per_step": serial_ms,
         "grad_update": grad_update,
+        "inception_step": inception,
         "cpu_baseline": cpu,
         "loss": loss,
         "paper_context_s_per_iter_other_hw": PAPER_ALEXNET_S_PER_ITER,
