@@ -118,6 +118,27 @@ def test_update_of_the_eight_alexnet_buckets_in_one_launch(orc32):
         assert host(devs[name][1]).tobytes() == b["v"].tobytes(), name
 
 
+def test_update_of_a_bucket_beyond_four_gibibytes(orc32):
+    """n = 2^30 + 2^20 + 3 parameters: every buffer is larger than 4 GiB, so element and byte offsets
+    leave 32 bits; K = 1, bit-exact against the oracle over the whole range.  Inputs are drawn on the
+    GPU (seeded) and copied to the host for the oracle."""
+    n = (1 << 30) + (1 << 20) + 3
+    sgd = (0.01, 0.9, 5e-4, 1.0)
+    gen = torch.Generator(device="cuda").manual_seed(33)
+    dw = torch.empty(n, device="cuda").normal_(0.0, 1e-2, generator=gen)
+    dv = torch.empty(n, device="cuda").normal_(0.0, 1e-4, generator=gen)
+    dg = torch.empty(n, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    dp = torch.empty(n, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    w, v, g, p = (t.cpu().numpy() for t in (dw, dv, dg, dp))
+    cg.cg_grad_reduce_sgd(dw, dv, dg, [dp], n, cg.cg_sgd(*sgd))
+    orc32.grad_reduce_sgd(w, v, g, [p], *sgd)
+    gw, gv = dw.cpu().numpy(), dv.cpu().numpy()
+    for got, ref, name in ((gw, w, "w"), (gv, v, "v")):
+        bad = np.flatnonzero(got.view(np.uint32) != ref.view(np.uint32))
+        assert bad.size == 0, (name, bad[:5], bad.size)
+    assert np.array_equal(dg.cpu().numpy().view(np.uint32), g.view(np.uint32))       # inputs untouched
+
+
 def _sample_fwd(x, w, b, c, n, m, oh, ow):
     """One output element from the definition, in double."""
     G = c["groups"]; Cg = c["C"] // G; Mg = c["M"] // G; g = m // Mg
