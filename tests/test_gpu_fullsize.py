@@ -155,10 +155,12 @@ def _sample_fwd(x, w, b, c, n, m, oh, ow):
     return acc
 
 
-@pytest.mark.parametrize("layer", list(cg_synth.ALEXNET_CONVS))
-def test_alexnet_conv_layer_at_b256_samples_and_adjoints(layer):
-    B = 256
-    c, x, w, b, dy = cg_synth.conv_layer_tensors(layer, B, seed=1 + list(cg_synth.ALEXNET_CONVS).index(layer))
+def _dot64(a, b):
+    """<a, b> accumulated in double, one slice of the leading axis at a time."""
+    return float(sum(np.dot(a[i].ravel().astype(np.float64), b[i].ravel().astype(np.float64)) for i in range(a.shape[0])))
+
+
+def _check_layer_by_samples_and_adjoints(c, x, w, b, dy, B, n_samples=40):
     d = cg.conv_desc(B, c["C"], c["H"], c["H"], c["M"], c["k"], stride=c["stride"], pad=c["pad"], groups=c["groups"])
     dx_, dw_, db_, dy_ = dev(x), dev(w), dev(b), dev(dy)
     y = host(conv_fwd(d, dx_, dw_, db_))
@@ -167,20 +169,20 @@ def test_alexnet_conv_layer_at_b256_samples_and_adjoints(layer):
     OH = y.shape[2]
     scale = np.abs(y).max()
     picks = [(0, 0, 0, 0), (B - 1, c["M"] - 1, OH - 1, OH - 1)] + \
-        [tuple(int(rng.integers(0, hi)) for hi in (B, c["M"], OH, OH)) for _ in range(40)]
+        [tuple(int(rng.integers(0, hi)) for hi in (B, c["M"], OH, OH)) for _ in range(n_samples)]
     for (n, m, oh, ow) in picks:
         ref = _sample_fwd(x, w, b, c, n, m, oh, ow)
         assert abs(float(y[n, m, oh, ow]) - ref) <= TOL * scale, (n, m, oh, ow)
     # adjoint identities in double on the host: <conv(x,w), dy> = <x, bwd_data(dy,w)> = <w, bwd_weight(x,dy)>
     y0 = y - b.reshape(1, -1, 1, 1)
-    lhs = float((y0.astype(np.float64) * dy).sum())
+    lhs = _dot64(y0, dy)
     dxg = host(conv_bwd_data(d, dy_, dw_))
     gdw, gdb = conv_bwd_weight(d, dx_, dy_)
     gdw, gdb = host(gdw), host(gdb)
-    norm = float(np.sqrt((y0.astype(np.float64) ** 2).sum()) * np.sqrt((dy.astype(np.float64) ** 2).sum()))
-    assert abs(lhs - float((dxg.astype(np.float64) * x).sum())) <= 1e-4 * norm
-    assert abs(lhs - float((gdw.astype(np.float64) * w).sum())) <= 1e-4 * norm
-    rdb = dy.astype(np.float64).sum(axis=(0, 2, 3))
+    norm = float(np.sqrt(_dot64(y0, y0)) * np.sqrt(_dot64(dy, dy)))
+    assert abs(lhs - _dot64(dxg, x)) <= 1e-4 * norm
+    assert abs(lhs - _dot64(gdw, w)) <= 1e-4 * norm
+    rdb = dy.sum(axis=(0, 2, 3), dtype=np.float64)
     assert max_abs_rel(gdb, rdb) <= TOL
     # sampled backward-weight elements straight from the definition
     Cg = c["C"] // c["groups"]; Mg = c["M"] // c["groups"]
@@ -194,3 +196,35 @@ def test_alexnet_conv_layer_at_b256_samples_and_adjoints(layer):
         xs = x[:, g * Cg + ci, oh_lo * s - p + kh:oh_hi * s - p + kh + 1:s, ow_lo * s - p + kw:ow_hi * s - p + kw + 1:s]
         ref = float((xs.astype(np.float64) * dy[:, m, oh_lo:oh_hi + 1, ow_lo:ow_hi + 1]).sum())
         assert abs(float(gdw[m, ci, kh, kw]) - ref) <= TOL * wscale, (m, ci, kh, kw)
+    # sampled backward-data elements straight from the definition (stride 1 only)
+    if s == 1:
+        xscale = np.abs(dxg).max()
+        for _ in range(6):
+            n, ch, ih, iw = (int(rng.integers(0, hi)) for hi in (B, c["C"], c["H"], c["H"]))
+            g = ch // Cg
+            ref = 0.0
+            for kh in range(c["k"]):
+                for kw in range(c["k"]):
+                    oh, ow = ih + p - kh, iw + p - kw
+                    if 0 <= oh < OH and 0 <= ow < OH:
+                        ref += float(np.dot(dy[n, g * Mg:(g + 1) * Mg, oh, ow].astype(np.float64),
+                                            w[g * Mg:(g + 1) * Mg, ch - g * Cg, kh, kw].astype(np.float64)))
+            assert abs(float(dxg[n, ch, ih, iw]) - ref) <= TOL * xscale, (n, ch, ih, iw)
+
+
+@pytest.mark.parametrize("layer", list(cg_synth.ALEXNET_CONVS))
+def test_alexnet_conv_layer_at_b256_samples_and_adjoints(layer):
+    B = 256
+    c, x, w, b, dy = cg_synth.conv_layer_tensors(layer, B, seed=1 + list(cg_synth.ALEXNET_CONVS).index(layer))
+    _check_layer_by_samples_and_adjoints(c, x, w, b, dy, B)
+
+
+def test_conv_near_the_two_gibibyte_tensor_limit():
+    """The library takes tensors of fewer than 2^29 elements (byte offsets fit 31 bits).  4096 images of
+    160 x 27 x 27 are 477 757 440 elements, 89 % of that: the offsets of the last images use the top of
+    the range in all three passes (5x5 window, padding 2: the kernels that stage raw image rows)."""
+    B = 4096
+    cfg = dict(C=160, H=27, M=16, k=5, stride=1, pad=2, groups=1)
+    c, x, w, b, dy = cg_synth.conv_layer_tensors("near_limit", B, seed=29, cfg=cfg)
+    assert x.size < (1 << 29) and x.size > 0.85 * (1 << 29)
+    _check_layer_by_samples_and_adjoints(c, x, w, b, dy, B, n_samples=24)
