@@ -516,10 +516,14 @@ int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy,
         if (!ws || ws_bytes < split_bytes + bias_bytes) return CG_ENOSPC;
         if (!aligned16(ws)) return CG_EINVAL;
     }
-    const int r = igemm_run(p, ws, split_bytes, stream);
-    if (r) return r;
-    if (db) return bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes, stream);
-    return CG_OK;
+    // The bias sums go first: they need only dy and stream through HBM while another stream's matrix
+    // kernel still runs; behind the weight gradient of a net's first layer they would sit, alone on
+    // the GPU, between that kernel and the update the next iteration waits for.
+    if (db) {
+        const int rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes, stream);
+        if (rb) return rb;
+    }
+    return igemm_run(p, ws, split_bytes, stream);
 }
 
 size_t conv_ws_bytes(const cg_conv_desc &d, int pass)
