@@ -1487,7 +1487,12 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     const int mt = pick_mt(p.M, p.N, p.groups);
     const bool bc = p.B.check != 0;
     const int am = quad_ok(p.A, p.K) ? LD_K4 : p.A.lanes_k ? LD_K : LD_ROWS;
-    const int bm = quad_ok(p.B, p.K) ? LD_K4 : p.B.lanes_k ? LD_K : LD_ROWS;
+    int bm = quad_ok(p.B, p.K) ? LD_K4 : p.B.lanes_k ? LD_K : LD_ROWS;
+    // A quad that reaches beyond K, or into the padding of a run of reduction indices, delivers the
+    // floats that follow in memory (the next row's first elements): harmless only if the other
+    // operand delivers exact zeros there, which the loaders that check every element do and the quad
+    // loader does not.  Quads on both sides need a reduction range without any such position.
+    if (am == LD_K4 && bm == LD_K4 && (p.K % 4 != 0 || p.A.k.r1_lim != 0 || p.B.k.r1_lim != 0)) bm = LD_K;
     if (am == LD_K4 && bm == LD_ROWS) return bc ? launch_modes<LD_K4, LD_ROWS, true>(p, mt, stream) : launch_modes<LD_K4, LD_ROWS, false>(p, mt, stream);
     if (am == LD_K4 && bm == LD_K4) return launch_modes<LD_K4, LD_K4, false>(p, mt, stream);
     if (am == LD_K4 && bm == LD_K) return bc ? launch_modes<LD_K4, LD_K, true>(p, mt, stream) : launch_modes<LD_K4, LD_K, false>(p, mt, stream);

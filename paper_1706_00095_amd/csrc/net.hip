@@ -253,7 +253,6 @@ extern "C" int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_
     Layer &ly = net->layers[layer];
     if (!ly.n_params || !w || !v || !g_local || K < 0 || K > CG_MAX_PEERS || (K > 0 && !g_peers)) return CG_EINVAL;
     if (!aligned16(w) || !aligned16(v) || !aligned16(g_local)) return CG_EINVAL;
-    if (ly.n_weights % 4) return CG_EUNSUPPORTED;   // the bias part of the bucket must stay 16-byte aligned
     for (int k = 0; k < K; ++k)
         if (!g_peers[k] || !aligned16(g_peers[k])) return CG_EINVAL;
     ly.w = w; ly.v = v; ly.g = g_local;
