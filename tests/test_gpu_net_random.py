@@ -1,4 +1,4 @@
-"""Randomised whole-iteration test: 16 seeded random nets (convolutions with groups, strides and
+"""Randomised whole-iteration test: 32 seeded random nets (convolutions with groups, strides and
 paddings, rectifiers in and out of the positions where they are folded, LRN, max-pooling, an
 optional two-branch block joined by a concat, dropout, fully-connected layers, softmax loss), one
 training iteration each against the oracle: loss, every materialised activation, the stored
@@ -11,7 +11,7 @@ import cg_synth
 from test_gpu_fullsize import _check_step
 
 pytestmark = pytest.mark.gpu
-N_NETS = 16
+N_NETS = 32
 
 
 def _random_net(i):
@@ -47,10 +47,11 @@ def _random_net(i):
         t = conv_from(t, relu=rng.random() < 0.85)
         c, h, w = shape_of(t)
         if rng.random() < 0.5:
-            t = add(dict(kind="lrn", inputs=[t], size=int(rng.choice([3, 5])), alpha=1e-2, beta=0.75, kappa=1.0))
+            size = int(rng.choice([3, 5, 5, 7, 4]))
+            t = add(dict(kind="lrn", inputs=[t], size=size, alpha=1e-2, beta=0.75 if size != 7 else 0.6, kappa=1.0))
         if min(h, w) >= 4 and rng.random() < 0.6:
-            k, s = (3, 2) if rng.random() < 0.6 else ((2, 2) if rng.random() < 0.5 else (3, 1))
-            p = int(rng.integers(0, 2)) if k == 3 else 0
+            k, s = [(3, 2), (3, 2), (2, 2), (3, 1), (4, 3)][int(rng.integers(0, 5))]
+            p = int(rng.integers(0, 2)) if k >= 3 else 0
             t = add(dict(kind="maxpool", inputs=[t], k=k, stride=s, pad=p))
     if rng.random() < 0.5:                       # two branches from the same tensor, joined along the channels
         c, h, w = shape_of(t)
@@ -59,7 +60,12 @@ def _random_net(i):
         b = add(dict(kind="conv", inputs=[t], M=int(rng.choice([6, 16])), k=3 if min(h, w) >= 3 else 1, stride=1,
                      pad=1 if min(h, w) >= 3 else 0, groups=1))
         b = add(dict(kind="relu", inputs=[b]))
-        t = add(dict(kind="concat", inputs=[a, b]))
+        branches = [a, b]
+        if min(h, w) >= 3 and rng.random() < 0.5:        # a pooling branch as in an inception module
+            q = add(dict(kind="maxpool", inputs=[t], k=3, stride=1, pad=1))
+            q = add(dict(kind="conv", inputs=[q], M=int(rng.choice([4, 8])), k=1, stride=1, pad=0, groups=1))
+            branches.append(add(dict(kind="relu", inputs=[q])))
+        t = add(dict(kind="concat", inputs=branches))
     if rng.random() < 0.3:
         t = add(dict(kind="avgpool", inputs=[t]))
     classes = int(rng.integers(3, 12))
@@ -70,7 +76,7 @@ def _random_net(i):
             t = add(dict(kind="dropout", inputs=[t], p=0.5))
     t = add(dict(kind="fc", inputs=[t], out=classes))
     add(dict(kind="softmax_ce", inputs=[t]))
-    B, K = int(rng.integers(2, 10)), int(rng.integers(0, 5))
+    B, K = int(rng.integers(1, 18)), int(rng.integers(0, 5))
     return layers, in_shape, classes, B, K
 
 
