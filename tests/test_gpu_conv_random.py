@@ -73,3 +73,33 @@ def test_random_descriptor(orc32, thresholds, i):
     gdw, gdb = conv_bwd_weight(d, dev(x), dev(dy))
     assert max_abs_rel(host(gdw), rdw) <= TOL, ("backward-weight", c)
     assert max_abs_rel(host(gdb), rdb) <= TOL, ("bias gradient", c)
+
+
+def _medium_case(i):
+    """At least 70 000 output pixels: enough tiles for the kernels that stage raw image rows to be the
+    default choice, on image sizes whose 128-pixel tiles start and end anywhere."""
+    rng = np.random.default_rng(31000 + i)
+    g = int(rng.choice([1, 1, 2]))
+    Cg = int(rng.choice([16, 16, 32, 48, 64]))
+    Mg = int(rng.choice([16, 32, 48, 64, 96, 128, 200]))
+    K = int(rng.choice([3, 3, 5]))
+    s = int(rng.choice([1, 1, 1, 2]))
+    p = int(rng.integers(0, K // 2 + 1))
+    H, W = int(rng.integers(7, 34)), int(rng.integers(7, 34))
+    OH, OW = (H + 2 * p - K) // s + 1, (W + 2 * p - K) // s + 1
+    B = int(np.ceil(70000 / (OH * OW))) + int(rng.integers(0, 7))
+    return dict(N=B, C=Cg * g, H=H, W=W, M=Mg * g, KH=K, KW=K, sh=s, sw=s, ph=p, pw=p, groups=g)
+
+
+@pytest.mark.parametrize("i", range(10))
+def test_random_medium_descriptor(orc32, i):
+    c = _medium_case(i)
+    args = (c["N"], c["C"], c["H"], c["W"], c["M"], c["KH"], c["KW"], c["sh"], c["sw"], c["ph"], c["pw"], c["groups"])
+    d, od = cg.cg_conv_desc(*args), ConvDesc(*args)
+    x, w, b, dy = _tensors(c, 41000 + i)
+    assert max_abs_rel(host(conv_fwd(d, dev(x), dev(w), dev(b))), orc32.conv_fwd(od, x, w, b)) <= TOL, ("forward", c)
+    assert max_abs_rel(host(conv_bwd_data(d, dev(dy), dev(w))), orc32.conv_bwd_data(od, dy, w)) <= TOL, ("backward-data", c)
+    rdw, rdb = orc32.conv_bwd_weight(od, x, dy)
+    gdw, gdb = conv_bwd_weight(d, dev(x), dev(dy))
+    assert max_abs_rel(host(gdw), rdw) <= TOL, ("backward-weight", c)
+    assert max_abs_rel(host(gdb), rdb) <= TOL, ("bias gradient", c)
