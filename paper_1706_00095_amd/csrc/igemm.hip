@@ -419,13 +419,13 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NST - 2) * LPT) : "memory");
         const float *a_s = smem + (it % NST) * STAGE, *b_s = a_s + LA::SZ;
         float af[KT / 8][TM][4], bf[KT / 8][TN][4];
+        // the fragments of the tile's first eight k now, those of the second eight behind the first
+        // MFMA step: half the reads are waited for at the start of a tile
 #pragma unroll
-        for (int ks = 0; ks < KT / 8; ++ks) {
+        for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, 0, h, af[0][i]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[ks][i]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, ks, h, bf[ks][j]);
-        }
+        for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, 0, h, bf[0][j]);
+        __builtin_amdgcn_sched_barrier(0);
         // One part of the next tile's loads behind each MFMA step: the address pipeline and the
         // matrix pipeline both stay fed, instead of taking turns.
         static_for<0, NPART>([&](auto PC) {
@@ -435,6 +435,15 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
+            if constexpr (P == 0) {
+#pragma unroll
+                for (int ks2 = 1; ks2 < KT / 8; ++ks2) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks2, h, af[ks2][i]);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, ks2, h, bf[ks2][j]);
+                }
+            }
             issue_part(PC, it + NST - 1);
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -598,15 +607,13 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
         const int py = pg.flip ? pg.KH - 1 - cky : cky, px = pg.flip ? pg.KW - 1 - ckx : ckx;
         const float *b_s = sB + (ccb & 1) * PB::BUF + (py * pg.Wp + px);
         float af[KT / 8][TM][4], bf[KT / 8][TN][4];
+        // Fragments are read one MFMA step ahead (A once per eight k, B per step): only the first step's
+        // reads are waited for at the start of a tile, the others arrive while the matrix pipeline works.
 #pragma unroll
-        for (int ks = 0; ks < KT / 8; ++ks) {
+        for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, 0, h, af[0][i]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[ks][i]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) bf[ks][j][t] = b_s[sig[j] + (8 * ks + t) * PB::CS];
-        }
+        for (int j = 0; j < TN; ++j) bf[0][j][0] = b_s[sig[j]];
+        __builtin_amdgcn_sched_barrier(0);
         const bool do_patch = burst && ct == 0;
         static_for<0, NPART>([&](auto PC) {
             constexpr int Pn = decltype(PC)::value, ks = Pn / 4, s4 = Pn % 4;
@@ -615,6 +622,15 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[ks][i][s4], bf[ks][j][s4], acc[i][j], 0, 0, 0);
+            if constexpr (Pn + 1 < NPART) {
+                constexpr int nks = (Pn + 1) / 4, nt = (Pn + 1) % 4;
+                if constexpr (nt == 0) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, nks, h, af[nks][i]);
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bf[nks][j][nt] = b_s[sig[j] + (8 * nks + nt) * PB::CS];
+            }
             issue_a_part(PC, it + NSTA - 1, icb, it_);
             if (do_patch) issue_patch_part(PC, ccb + 1);
             __builtin_amdgcn_sched_barrier(0);
