@@ -98,6 +98,14 @@ void cgo_grad_reduce_sgd(REAL *w, REAL *v, const REAL *g_local,
                          const REAL *const *g_peers, int K, size_t n,
                          REAL lr, REAL mu, REAL wd, REAL grad_scale);
 
+/* As above, with the K+1 gradients added in binomial-tree association
+ * (section 3.2): rank 0 = local, rank k+1 = peer k; rank r adds the forwarded
+ * sums of ranks r+1, r+2, r+4, ... (below r's lowest set bit, at most K) in
+ * that order to its own gradient. */
+void cgo_grad_reduce_sgd_tree(REAL *w, REAL *v, const REAL *g_local,
+                              const REAL *const *g_peers, int K, size_t n,
+                              REAL lr, REAL mu, REAL wd, REAL grad_scale);
+
 int cgo_num_threads(void);
 void cgo_set_num_threads(int n);
 

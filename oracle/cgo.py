@@ -191,8 +191,9 @@ class Oracle:
         return loss[0], dz
 
     # -- Eq. 1 + solver history ----------------------------------------------------------
-    def grad_reduce_sgd(self, w, v, g_local, g_peers, lr, mu, wd, grad_scale=1.0):
-        """In place on w and v (which must be contiguous arrays of the oracle's dtype)."""
+    def grad_reduce_sgd(self, w, v, g_local, g_peers, lr, mu, wd, grad_scale=1.0, order="sequential"):
+        """In place on w and v (which must be contiguous arrays of the oracle's dtype).
+        order: "sequential" (local, then peers left to right) or "tree" (binomial reduction tree)."""
         assert w.dtype == self.dtype and v.dtype == self.dtype and w.flags.c_contiguous and v.flags.c_contiguous
         g_local = self._a(g_local)
         peers = [self._a(p) for p in g_peers]
@@ -200,5 +201,6 @@ class Oracle:
         assert v.size == n and g_local.size == n and all(p.size == n for p in peers)
         arr = (C.c_void_p * max(len(peers), 1))(*[p.ctypes.data for p in peers])
         r = self.creal
-        self.lib.cgo_grad_reduce_sgd(self._p(w), self._p(v), self._p(g_local), arr, C.c_int(len(peers)),
+        fn = {"sequential": self.lib.cgo_grad_reduce_sgd, "tree": self.lib.cgo_grad_reduce_sgd_tree}[order]
+        fn(self._p(w), self._p(v), self._p(g_local), arr, C.c_int(len(peers)),
                                      C.c_size_t(n), r(lr), r(mu), r(wd), r(grad_scale))

@@ -138,3 +138,103 @@ def test_denormals_and_nonfinite_propagate(orc32):
     g = np.array([tiny, np.inf, np.nan], F32)
     orc32.grad_reduce_sgd(w, v, g, [np.array([tiny, 0, 0], F32)], 1.0, 0.0, 0.0)
     assert v[0] == np.float32(2) * tiny and v[0] != 0 and np.isinf(v[1]) and np.isnan(v[2])
+
+
+# ---- binomial-tree association (section 3.2 "Reduction of the Gradient") -------------------------
+
+def _tree_by_rounds(bufs):
+    """A second formulation of the reduction tree, by message rounds: in the round of distance d
+    every rank whose lowest set bit is d sends its running sum to rank r - d, which adds it.
+    float32 arrays, each addition rounded once.  Returns (sum held by rank 0, number of rounds,
+    list of (sender, receiver))."""
+    acc = [b.astype(F32).copy() for b in bufs]
+    m, d, rounds, msgs = len(acc), 1, 0, []
+    while d < m:
+        for r in range(d, m, 2 * d):
+            acc[r - d] = acc[r - d] + acc[r]
+            msgs.append((r, r - d))
+        d *= 2
+        rounds += 1
+    return acc[0], rounds, msgs
+
+
+def _tree_sum_oracle(orc32, bufs):
+    n = bufs[0].size
+    w, v = np.zeros(n, F32), np.zeros(n, F32)
+    orc32.grad_reduce_sgd(w, v, bufs[0], bufs[1:], 1.0, 0.0, 0.0, order="tree")
+    assert np.array_equal(w, -v)
+    return v
+
+
+@pytest.mark.parametrize("K", list(range(0, 17)) + [23, 31, 32, 63])
+def test_tree_matches_message_rounds(orc32, K):
+    rng = np.random.default_rng(700 + K)
+    bufs = [rng.standard_normal(3001).astype(F32) for _ in range(K + 1)]
+    ref, rounds, msgs = _tree_by_rounds(bufs)
+    assert np.array_equal(_tree_sum_oracle(orc32, bufs), ref)
+    # shape of the tree: every rank but the master sends exactly once, to a lower rank,
+    # and the depth is ceil(log2(K + 1))
+    assert sorted(s for s, _ in msgs) == list(range(1, K + 1)) and all(r < s for s, r in msgs)
+    assert rounds == int(np.ceil(np.log2(K + 1)))
+
+
+def test_tree_rounding_cases_worked_by_hand(orc32):
+    """u = 2^-23 is one unit in the last place of 1.0; ties round to even.
+    Four ranks (1, u/2, u/2, u/2): the tree forms (1 + u/2) + (u/2 + u/2) = 1 + u, while left to
+    right every u/2 is lost.  Eight ranks (1, then seven u/2): ((1+u/2) + u) + 2u = 1 + 3u."""
+    u = F32(2.0 ** -23)
+    one = np.ones(4, F32)
+    half = np.full(4, u / F32(2), F32)
+    assert np.all(_tree_sum_oracle(orc32, [one, half, half, half]) == F32(1) + u)
+    w, v = np.zeros(4, F32), np.zeros(4, F32)
+    orc32.grad_reduce_sgd(w, v, one, [half] * 3, 1.0, 0.0, 0.0)
+    assert np.all(v == F32(1))
+    assert np.all(_tree_sum_oracle(orc32, [one] + [half] * 7) == F32(1) + F32(3) * u)
+
+
+def test_tree_adds_the_nearest_sender_first(orc32):
+    """Three ranks (1, u/2, 3u/4): (1 + u/2) + 3u/4 = 1 + u, but (1 + 3u/4) + u/2 = 1 + 2u."""
+    u = F32(2.0 ** -23)
+    a, b, c = np.ones(2, F32), np.full(2, u * F32(0.5), F32), np.full(2, u * F32(0.75), F32)
+    assert np.all(_tree_sum_oracle(orc32, [a, b, c]) == F32(1) + u)
+    assert np.all(_tree_sum_oracle(orc32, [a, c, b]) == F32(1) + F32(2) * u)
+
+
+@pytest.mark.parametrize("K", [0, 1, 2])
+def test_tree_equals_left_to_right_up_to_three_ranks(orc32, K):
+    rng = np.random.default_rng(710 + K)
+    w, v, g, peers = _mk(rng, 4099, K)
+    w2, v2 = w.copy(), v.copy()
+    orc32.grad_reduce_sgd(w, v, g, peers, 0.01, 0.9, 5e-4, 0.5)
+    orc32.grad_reduce_sgd(w2, v2, g, peers, 0.01, 0.9, 5e-4, 0.5, order="tree")
+    assert w.tobytes() == w2.tobytes() and v.tobytes() == v2.tobytes()
+
+
+@pytest.mark.parametrize("K", [4, 8, 16])
+def test_tree_history_terms_and_reassociation_bound(orc32, K):
+    """The steps after the sum are those of the sequential form (checked through numpy float32 on
+    the message-round sum), and the two associations differ by at most K ulp of the largest
+    partial sum."""
+    rng = np.random.default_rng(720 + K)
+    w, v, g, peers = _mk(rng, 20011, K)
+    s, _, _ = _tree_by_rounds([g] + peers)
+    lr, mu, wd, gs = F32(0.01), F32(0.9), F32(5e-4), F32(0.25)
+    vn = mu * v + lr * (s * gs + wd * w)
+    ew = w - vn
+    w2, v2 = w.copy(), v.copy()
+    orc32.grad_reduce_sgd(w2, v2, g, peers, 0.01, 0.9, 5e-4, 0.25, order="tree")
+    assert w2.tobytes() == ew.tobytes() and v2.tobytes() == vn.tobytes()
+    seq = g.copy()
+    for p in peers:
+        seq = seq + p
+    bound = K * np.spacing(np.abs(np.stack([g] + peers)).sum(0).astype(F32))
+    assert np.all(np.abs(seq.astype(np.float64) - s.astype(np.float64)) <= bound)
+    assert np.any(seq != s)
+
+
+@pytest.mark.parametrize("K", [4, 8, 16])
+def test_tree_exact_inputs_give_the_exact_sum(orc32, K):
+    rng = np.random.default_rng(730 + K)
+    bufs = [(rng.integers(-2048, 2048, 4096) / 1024.0).astype(F32) for _ in range(K + 1)]
+    exact = np.sum(np.stack(bufs).astype(np.float64), 0)
+    assert np.array_equal(_tree_sum_oracle(orc32, bufs).astype(np.float64), exact)
