@@ -103,11 +103,14 @@ def grad_update_standalone(cg, torch, steps, warmup):
         w = torch.empty(n, device="cuda").normal_(0, 1e-2, generator=gen)
         bufs.append(dict(n=n, w=w, v=torch.zeros(n, device="cuda"),
                          g=[torch.empty(n, device="cuda").normal_(0, 1e-3, generator=gen) for _ in range(17)]))
-    for K in (4, 8, 16):
-        # one launch for the eight buckets (the five convolution buckets are launch-bound one by one)
+    for K, fn, tag in [(4, cg.cg_grad_reduce_sgd_multi, ""), (8, cg.cg_grad_reduce_sgd_multi, ""),
+                       (16, cg.cg_grad_reduce_sgd_multi, ""), (4, cg.cg_grad_reduce_sgd_tree_multi, "_tree"),
+                       (16, cg.cg_grad_reduce_sgd_tree_multi, "_tree")]:
+        # one launch for the eight buckets (the five convolution buckets are launch-bound one by one);
+        # "_tree": the sum in binomial-tree association (section 3.2), same traffic
         def one():
-            cg.cg_grad_reduce_sgd_multi([b["w"] for b in bufs], [b["v"] for b in bufs], [b["g"][0] for b in bufs],
-                                        [b["g"][1:K + 1] for b in bufs], [b["n"] for b in bufs], sgd)
+            fn([b["w"] for b in bufs], [b["v"] for b in bufs], [b["g"][0] for b in bufs],
+               [b["g"][1:K + 1] for b in bufs], [b["n"] for b in bufs], sgd)
         for _ in range(warmup):
             one()
         torch.cuda.synchronize()
@@ -122,7 +125,7 @@ def grad_update_standalone(cg, torch, steps, warmup):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
         by = (4.0 * K + 20.0) * sum(sizes)
-        out[f"K{K}"] = dict(gbps=by / ms / 1e6, ms_per_launch=ms, bytes=by, frac_of_peak=by / ms / 1e6 / PEAK_HBM_GBS,
+        out[f"K{K}{tag}"] = dict(gbps=by / ms / 1e6, ms_per_launch=ms, bytes=by, frac_of_peak=by / ms / 1e6 / PEAK_HBM_GBS,
                             launches_per_update=1, buckets=len(sizes))
     return out
 

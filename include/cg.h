@@ -116,6 +116,26 @@ int cg_grad_reduce_sgd_multi(int nb, float *const *w, float *const *v,
                              const float *const *const *g_peers, int K,
                              const size_t *n, const cg_sgd *sgd, void *stream);
 
+/* cg_grad_reduce_sgd / cg_grad_reduce_sgd_multi with the K+1 gradients added in
+ * the association of the binomial reduction tree of section 3.2 ("Reduction of
+ * the Gradient": data travels from higher to lower rank numbers and ends on the
+ * master, each rank adding what it receives to its own gradient before it
+ * forwards the result).  Rank 0 is the local worker, rank k+1 is g_peers[k].
+ * The receiver of rank r > 0 is r with its lowest set bit cleared; rank r
+ * therefore adds the forwarded sums of ranks r+1, r+2, r+4, ... (distances
+ * below r's lowest set bit, ranks at most K), and does so nearest first (the
+ * paper adds in order of arrival; this fixed order gives one bit pattern):
+ *     K = 4:  s = ((g0 + g1) + (g2 + g3)) + g4
+ * Everything after the sum, the arguments, limits and errors are those of the
+ * left-to-right entry points; for K <= 2 the results are identical to theirs. */
+int cg_grad_reduce_sgd_tree(float *w, float *v, const float *g_local,
+                            const float *const *g_peers, int K, size_t n,
+                            const cg_sgd *sgd, void *stream);
+int cg_grad_reduce_sgd_tree_multi(int nb, float *const *w, float *const *v,
+                                  const float *const *g_local,
+                                  const float *const *const *g_peers, int K,
+                                  const size_t *n, const cg_sgd *sgd, void *stream);
+
 /* ---- whole iteration ------------------------------------------------------ */
 
 enum {

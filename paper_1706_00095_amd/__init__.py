@@ -22,7 +22,7 @@ LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc":
 
 EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight",
-    "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
+    "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_grad_reduce_sgd_tree", "cg_grad_reduce_sgd_tree_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
     "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
@@ -76,6 +76,8 @@ def lib():
         L.cg_grad_reduce_sgd.argtypes = [vp, vp, vp, C.POINTER(vp), C.c_int, sz, C.POINTER(cg_sgd), vp]
         L.cg_grad_reduce_sgd_multi.argtypes = [C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                                C.POINTER(C.POINTER(vp)), C.c_int, C.POINTER(sz), C.POINTER(cg_sgd), vp]
+        L.cg_grad_reduce_sgd_tree.argtypes = L.cg_grad_reduce_sgd.argtypes
+        L.cg_grad_reduce_sgd_tree_multi.argtypes = L.cg_grad_reduce_sgd_multi.argtypes
         L.cg_net_create.argtypes = [C.POINTER(cg_layer_desc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.POINTER(vp)]
         L.cg_net_destroy.argtypes = [vp]
@@ -168,14 +170,28 @@ def cg_conv_bwd_weight(d, x, dy, dw, dbias, ws=None, stream=None):
                                     _stream(stream)), "cg_conv_bwd_weight")
 
 
+def _reduce_sgd(name, w, v, g_local, g_peers, n, sgd, stream):
+    K = len(g_peers)
+    _check(getattr(lib(), name)(_ptr(w), _ptr(v), _ptr(g_local), _ptr_array(g_peers), K, n, C.byref(sgd),
+                                _stream(stream)), name)
+
+
 def cg_grad_reduce_sgd(w, v, g_local, g_peers, n, sgd, stream=None):
     """g_peers: sequence of K device tensors; sgd: cg_sgd."""
-    K = len(g_peers)
-    _check(lib().cg_grad_reduce_sgd(_ptr(w), _ptr(v), _ptr(g_local), _ptr_array(g_peers), K, n, C.byref(sgd),
-                                    _stream(stream)), "cg_grad_reduce_sgd")
+    _reduce_sgd("cg_grad_reduce_sgd", w, v, g_local, g_peers, n, sgd, stream)
 
 
-def cg_grad_reduce_sgd_multi(ws, vs, gs, peers, ns, sgd, stream=None):
+def cg_grad_reduce_sgd_tree(w, v, g_local, g_peers, n, sgd, stream=None):
+    """The same arguments; the sum is taken in binomial-tree association."""
+    _reduce_sgd("cg_grad_reduce_sgd_tree", w, v, g_local, g_peers, n, sgd, stream)
+
+
+def cg_grad_reduce_sgd_tree_multi(ws, vs, gs, peers, ns, sgd, stream=None):
+    """cg_grad_reduce_sgd_multi's arguments; the sums are taken in binomial-tree association."""
+    cg_grad_reduce_sgd_multi(ws, vs, gs, peers, ns, sgd, stream, _name="cg_grad_reduce_sgd_tree_multi")
+
+
+def cg_grad_reduce_sgd_multi(ws, vs, gs, peers, ns, sgd, stream=None, _name="cg_grad_reduce_sgd_multi"):
     """One launch for several buckets: ws, vs, gs sequences of device tensors, peers a sequence of
     sequences of K device tensors each, ns the element counts."""
     nb = len(ws)
@@ -186,8 +202,8 @@ def cg_grad_reduce_sgd_multi(ws, vs, gs, peers, ns, sgd, stream=None):
     for i, r in enumerate(rows):
         table[i] = C.cast(r, C.POINTER(C.c_void_p))
     counts = (C.c_size_t * max(nb, 1))(*ns)
-    _check(lib().cg_grad_reduce_sgd_multi(nb, _ptr_array(ws), _ptr_array(vs), _ptr_array(gs), table, K, counts,
-                                          C.byref(sgd), _stream(stream)), "cg_grad_reduce_sgd_multi")
+    _check(getattr(lib(), _name)(nb, _ptr_array(ws), _ptr_array(vs), _ptr_array(gs), table, K, counts,
+                                 C.byref(sgd), _stream(stream)), _name)
 
 
 def cg_debug_patch_min_tiles(tiles):

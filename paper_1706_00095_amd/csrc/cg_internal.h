@@ -215,10 +215,10 @@ int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, 
 
 // ---- gradient aggregation + update (sgd.hip) --------------------------------------------------
 int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *const *g_peers, int K,
-                         size_t n, const cg_sgd &sgd, hipStream_t stream);
+                         size_t n, const cg_sgd &sgd, hipStream_t stream, bool tree = false);
 int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const float *const *g_local,
                                const float *const *const *g_peers, int K, const size_t *n, const cg_sgd &sgd,
-                               hipStream_t stream);
+                               hipStream_t stream, bool tree = false);
 
 // ---- the other layers (layers.hip) -------------------------------------------------------------
 int fc_bias_grad_launch(const float *dy, int B, int OUT, float *db, hipStream_t stream);

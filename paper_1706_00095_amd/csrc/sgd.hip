@@ -3,6 +3,10 @@
 // gradient buffers and from w and v, and w and v are written once -- 4K+20 bytes per
 // parameter, so the kernel is bound by HBM bandwidth and nothing else.
 //
+// Two associations of the sum exist: left to right (local first, then peers 0..K-1), and that of
+// the binomial reduction tree of section 3.2 (rank 0 = local, rank k+1 = peer k; rank r adds the
+// sums forwarded by ranks r+1, r+2, r+4, ... below its own lowest set bit, nearest first).
+//
 // This translation unit is compiled with -ffp-contract=off: the operation order documented in
 // cg.h is also the rounding order, which makes the result bit-reproducible.
 #include <cstdio>
@@ -26,6 +30,37 @@ __device__ __forceinline__ float upd(float w, float v, float s, const cg_sgd c, 
     return w - vn;
 }
 
+__device__ __forceinline__ void add4(f4 &a, const f4 b)
+{
+    a.x = a.x + b.x; a.y = a.y + b.y; a.z = a.z + b.z; a.w = a.w + b.w;
+}
+__device__ __forceinline__ void add4(float &a, const float b) { a = a + b; }
+
+// Sum of rank 0 (s) and ranks 1..KC (q[0..KC-1]).  TREE: the message rounds of the binomial tree,
+// distance 1, 2, 4, ...: in the round of distance d rank r (a multiple of 2d) adds what rank r + d
+// holds.  KC is a compile-time constant, so the array lives in registers.
+template <int KC, bool TREE, typename T>
+__device__ __forceinline__ T rank_sum(const T s, const T *q)
+{
+    if constexpr (!TREE || KC < 3) {
+        T t = s;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) add4(t, q[k]);
+        return t;
+    } else {
+        T a[KC + 1];
+        a[0] = s;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) a[k + 1] = q[k];
+#pragma unroll
+        for (int d = 1; d <= KC; d *= 2) {
+#pragma unroll
+            for (int r = 0; r + d <= KC; r += 2 * d) add4(a[r], a[r + d]);
+        }
+        return a[0];
+    }
+}
+
 // One launch serves up to MAXB buckets: block b belongs to the bucket whose [first, first + blocks)
 // range contains it and updates 2 x 256 consecutive float4 groups there, every load of a group
 // issued before the first use.  No loop: one short-lived block per 8 KB of each stream keeps far
@@ -46,7 +81,7 @@ struct BucketTable {
     Bucket b[MAXB];
 };
 
-template <int KC>
+template <int KC, bool TREE>
 __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, const cg_sgd c)
 {
     int bi = 0;
@@ -74,9 +109,7 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, 
     for (int u = 0; u < UNR; ++u) {
         const size_t i = i0 + (size_t)u * 256;
         if (i < n4) {
-            f4 t = s[u];
-#pragma unroll
-            for (int k = 0; k < KC; ++k) { t.x = t.x + q[u][k].x; t.y = t.y + q[u][k].y; t.z = t.z + q[u][k].z; t.w = t.w + q[u][k].w; }
+            const f4 t = rank_sum<KC, TREE, f4>(s[u], q[u]);
             f4 wo, vo;
             float v0, v1, v2, v3;
             wo.x = upd(wi[u].x, vi[u].x, t.x, c, v0);
@@ -91,9 +124,10 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, 
     // ragged tail (n % 4 elements), handled by the first threads of the bucket's first block
     const size_t tail = n4 * 4 + threadIdx.x;
     if (blockIdx.x == bk.first_block && tail < n) {
-        float t = bk.g[tail];
+        float qt[KC > 0 ? KC : 1];
 #pragma unroll
-        for (int k = 0; k < KC; ++k) t = t + bk.peer[k][tail];
+        for (int k = 0; k < KC; ++k) qt[k] = bk.peer[k][tail];
+        const float t = rank_sum<KC, TREE, float>(bk.g[tail], qt);
         float vn;
         const float wn = upd(bk.w[tail], bk.v[tail], t, c, vn);
         bk.w[tail] = wn;
@@ -101,17 +135,45 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, 
     }
 }
 
+// Run-time K, tree association: ranks are visited from K down to 0.  When rank r is reached the
+// sums of its senders r + 2^j (2^j below r's lowest set bit) are complete, and each is the latest
+// sum filed under its own lowest set bit 2^j; r adds them nearest first and files its own sum
+// under its lowest set bit.  Seven slots cover ranks up to 64.
+template <typename T, typename LOAD>
+__device__ __forceinline__ T tree_sum_anyk(int K, LOAD load)
+{
+    T slot[7];
+    T s = T();
+    for (int r = K; r >= 0; --r) {
+        s = load(r);
+        const int b = r ? __builtin_ctz((unsigned)r) : 7;
+#pragma unroll
+        for (int j = 0; j < 7; ++j)
+            if (j < b && r + (1 << j) <= K) add4(s, slot[j]);
+#pragma unroll
+        for (int j = 0; j < 7; ++j)
+            if (j == b) slot[j] = s;
+    }
+    return s;
+}
+
 // any K up to CG_MAX_PEERS: one bucket, grid-stride
+template <bool TREE>
 __global__ __launch_bounds__(256) void reduce_sgd_anyk_kernel(float *__restrict__ w, float *__restrict__ v,
                                                               const float *__restrict__ g, const PeerTable peers,
                                                               int K, size_t n4, size_t n, const cg_sgd c)
 {
     const size_t stride = (size_t)gridDim.x * 256;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-        f4 s = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g) + i);
-        for (int k = 0; k < K; ++k) {
-            const f4 q = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(peers.p[k]) + i);
-            s.x = s.x + q.x; s.y = s.y + q.y; s.z = s.z + q.z; s.w = s.w + q.w;
+        f4 s;
+        if constexpr (TREE) {
+            s = tree_sum_anyk<f4>(K, [&](int r) {
+                return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r ? peers.p[r - 1] : g) + i);
+            });
+        } else {
+            s = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g) + i);
+            for (int k = 0; k < K; ++k)
+                add4(s, __builtin_nontemporal_load(reinterpret_cast<const f4 *>(peers.p[k]) + i));
         }
         const f4 wi = reinterpret_cast<const f4 *>(w)[i];
         const f4 vi = reinterpret_cast<const f4 *>(v)[i];
@@ -127,8 +189,13 @@ __global__ __launch_bounds__(256) void reduce_sgd_anyk_kernel(float *__restrict_
     }
     const size_t tail = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0 && tail < n) {
-        float s = g[tail];
-        for (int k = 0; k < K; ++k) s = s + peers.p[k][tail];
+        float s;
+        if constexpr (TREE) {
+            s = tree_sum_anyk<float>(K, [&](int r) { return r ? peers.p[r - 1][tail] : g[tail]; });
+        } else {
+            s = g[tail];
+            for (int k = 0; k < K; ++k) s = s + peers.p[k][tail];
+        }
         float vn;
         const float wn = upd(w[tail], v[tail], s, c, vn);
         w[tail] = wn;
@@ -147,10 +214,13 @@ int check_bucket(const float *w, const float *v, const float *g, const float *co
     return CG_OK;
 }
 
-void launch_table(const BucketTable &tab, unsigned blocks, int K, const cg_sgd &c, hipStream_t stream)
+void launch_table(const BucketTable &tab, unsigned blocks, int K, bool tree, const cg_sgd &c, hipStream_t stream)
 {
-    switch (K) {
-#define CG_CASE(k) case k: hipLaunchKernelGGL((reduce_sgd_kernel<k>), dim3(blocks), dim3(256), 0, stream, tab, c); break;
+    // up to three ranks the two associations are the same sum
+    switch (tree && K >= 3 ? 100 + K : K) {
+#define CG_CASE(k)                                                                                         \
+    case k: hipLaunchKernelGGL((reduce_sgd_kernel<k, false>), dim3(blocks), dim3(256), 0, stream, tab, c); break; \
+    case 100 + k: hipLaunchKernelGGL((reduce_sgd_kernel<k, true>), dim3(blocks), dim3(256), 0, stream, tab, c); break;
         CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7) CG_CASE(8)
         CG_CASE(9) CG_CASE(10) CG_CASE(11) CG_CASE(12) CG_CASE(13) CG_CASE(14) CG_CASE(15) CG_CASE(16)
 #undef CG_CASE
@@ -163,7 +233,7 @@ void launch_table(const BucketTable &tab, unsigned blocks, int K, const cg_sgd &
 // nb buckets with the same K and constants; launches ceil(nb / MAXB) kernels
 int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const float *const *g_local,
                                const float *const *const *g_peers, int K, const size_t *n, const cg_sgd &sgd,
-                               hipStream_t stream)
+                               hipStream_t stream, bool tree)
 {
     if (K < 0 || K > CG_MAX_PEERS || nb < 0) return CG_EINVAL;
     if (nb == 0) return CG_OK;
@@ -184,8 +254,12 @@ int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const f
             if (blocks > 4096) blocks = 4096;
             if (blocks == 0) blocks = 1;
             const int rec = prof_on() ? prof_begin("reduce_sgd_kernel<any>", 0.0, (4.0 * K + 20.0) * (double)n[i], stream) : -1;
-            hipLaunchKernelGGL(reduce_sgd_anyk_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w[i], v[i], g_local[i],
-                               pt, K, n[i] / 4, n[i], sgd);
+            if (tree)
+                hipLaunchKernelGGL(reduce_sgd_anyk_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, w[i], v[i],
+                                   g_local[i], pt, K, n[i] / 4, n[i], sgd);
+            else
+                hipLaunchKernelGGL(reduce_sgd_anyk_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, w[i], v[i],
+                                   g_local[i], pt, K, n[i] / 4, n[i], sgd);
             prof_end(rec, stream);
         }
         CG_HIP_TRY(hipGetLastError());
@@ -217,10 +291,10 @@ int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const f
         int rec = -1;
         if (prof_on()) {
             char name[64];
-            snprintf(name, sizeof name, "reduce_sgd_kernel<%d>", K);
+            snprintf(name, sizeof name, tree ? "reduce_sgd_kernel<%d,tree>" : "reduce_sgd_kernel<%d>", K);
             rec = prof_begin(name, 0.0, bytes, stream);
         }
-        launch_table(tab, (unsigned)blocks, K, sgd, stream);
+        launch_table(tab, (unsigned)blocks, K, tree, sgd, stream);
         prof_end(rec, stream);
         CG_HIP_TRY(hipGetLastError());
     }
@@ -228,10 +302,10 @@ int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const f
 }
 
 int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *const *g_peers, int K, size_t n,
-                         const cg_sgd &sgd, hipStream_t stream)
+                         const cg_sgd &sgd, hipStream_t stream, bool tree)
 {
     if (n == 0) return (K < 0 || K > CG_MAX_PEERS) ? CG_EINVAL : CG_OK;
-    return grad_reduce_sgd_multi_impl(1, &w, &v, &g_local, &g_peers, K, &n, sgd, stream);
+    return grad_reduce_sgd_multi_impl(1, &w, &v, &g_local, &g_peers, K, &n, sgd, stream, tree);
 }
 
 }  // namespace cg
@@ -240,7 +314,14 @@ extern "C" int cg_grad_reduce_sgd(float *w, float *v, const float *g_local, cons
                                   size_t n, const cg_sgd *sgd, void *stream)
 {
     if (!sgd) return CG_EINVAL;
-    return cg::grad_reduce_sgd_impl(w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream));
+    return cg::grad_reduce_sgd_impl(w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream), false);
+}
+
+extern "C" int cg_grad_reduce_sgd_tree(float *w, float *v, const float *g_local, const float *const *g_peers, int K,
+                                       size_t n, const cg_sgd *sgd, void *stream)
+{
+    if (!sgd) return CG_EINVAL;
+    return cg::grad_reduce_sgd_impl(w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream), true);
 }
 
 extern "C" int cg_grad_reduce_sgd_multi(int nb, float *const *w, float *const *v, const float *const *g_local,
@@ -248,5 +329,13 @@ extern "C" int cg_grad_reduce_sgd_multi(int nb, float *const *w, float *const *v
                                         void *stream)
 {
     if (!sgd) return CG_EINVAL;
-    return cg::grad_reduce_sgd_multi_impl(nb, w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream));
+    return cg::grad_reduce_sgd_multi_impl(nb, w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream), false);
+}
+
+extern "C" int cg_grad_reduce_sgd_tree_multi(int nb, float *const *w, float *const *v, const float *const *g_local,
+                                             const float *const *const *g_peers, int K, const size_t *n,
+                                             const cg_sgd *sgd, void *stream)
+{
+    if (!sgd) return CG_EINVAL;
+    return cg::grad_reduce_sgd_multi_impl(nb, w, v, g_local, g_peers, K, n, *sgd, static_cast<hipStream_t>(stream), true);
 }

@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 F32 = np.float32
 
 
-def _run_both(orc32, n, K, sgd, seed, v_zero=False, special=None):
+def _run_both(orc32, n, K, sgd, seed, v_zero=False, special=None, order="sequential"):
     rng = np.random.default_rng(seed)
     w = (rng.standard_normal(n) * 1e-2).astype(F32)
     v = np.zeros(n, F32) if v_zero else (rng.standard_normal(n) * 1e-4).astype(F32)
@@ -20,8 +20,9 @@ def _run_both(orc32, n, K, sgd, seed, v_zero=False, special=None):
     if special is not None:
         special(w, v, g, peers)
     dw, dv, dg, dp = dev(w), dev(v), dev(g), [dev(p) for p in peers]
-    cg.cg_grad_reduce_sgd(dw, dv, dg, dp, n, cg.cg_sgd(*sgd))
-    orc32.grad_reduce_sgd(w, v, g, peers, *sgd)
+    fn = cg.cg_grad_reduce_sgd if order == "sequential" else cg.cg_grad_reduce_sgd_tree
+    fn(dw, dv, dg, dp, n, cg.cg_sgd(*sgd))
+    orc32.grad_reduce_sgd(w, v, g, peers, *sgd, order=order)
     gw, gv = host(dw), host(dv)
     if special is not None:
         # a NaN is a NaN: its sign and payload bits are not part of the contract
@@ -94,8 +95,9 @@ def test_two_consecutive_steps_and_stream_argument(orc32):
     assert host(dw).tobytes() == w.tobytes() and host(dv).tobytes() == v.tobytes()
 
 
+@pytest.mark.parametrize("order", ["sequential", "tree"])
 @pytest.mark.parametrize("K", [0, 4, 16, 20])
-def test_multi_bucket_launch_is_bit_exact_per_bucket(orc32, K):
+def test_multi_bucket_launch_is_bit_exact_per_bucket(orc32, K, order):
     """One launch over many layer buckets (ragged sizes, a 1..3-element bucket, an empty one, more
     than eight buckets) gives every bucket exactly what its own cg_grad_reduce_sgd call gives."""
     sgd = (0.01, 0.9, 5e-4, 1.0)
@@ -111,12 +113,52 @@ def test_multi_bucket_launch_is_bit_exact_per_bucket(orc32, K):
         # empty tensors have no device address worth passing: a 4-float dummy stands in
         mk = (lambda a: dev(a) if a.size else torch.zeros(4, device="cuda"))
         dev_sets.append((mk(w), mk(v), mk(g), [mk(p) for p in peers]))
-    cg.cg_grad_reduce_sgd_multi([d[0] for d in dev_sets], [d[1] for d in dev_sets], [d[2] for d in dev_sets],
-                                [d[3] for d in dev_sets], sizes, cg.cg_sgd(*sgd))
+    fn = cg.cg_grad_reduce_sgd_multi if order == "sequential" else cg.cg_grad_reduce_sgd_tree_multi
+    fn([d[0] for d in dev_sets], [d[1] for d in dev_sets], [d[2] for d in dev_sets],
+       [d[3] for d in dev_sets], sizes, cg.cg_sgd(*sgd))
     for (w, v, g, peers), d, n in zip(host_sets, dev_sets, sizes):
         if n == 0:
             continue
-        orc32.grad_reduce_sgd(w, v, g, peers, *sgd)
+        orc32.grad_reduce_sgd(w, v, g, peers, *sgd, order=order)
         assert host(d[0])[:n].tobytes() == w.tobytes()
         assert host(d[1])[:n].tobytes() == v.tobytes()
         assert host(d[2])[:n].tobytes() == g.tobytes()
+
+
+# ---- binomial-tree association (section 3.2 "Reduction of the Gradient") -------------------------
+
+@pytest.mark.parametrize("K", list(range(0, 17)) + [17, 23, 31, 32, 33, 47, 63, 64])
+def test_tree_bit_exact_all_peer_counts(orc32, K):
+    _run_both(orc32, 70003, K, (0.01, 0.9, 5e-4, 1.0), seed=300 + K, order="tree")
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 1027, 4 * 256 * 2048 + 1])
+@pytest.mark.parametrize("K", [4, 20])
+def test_tree_bit_exact_ragged_sizes(orc32, n, K):
+    _run_both(orc32, n, K, (0.01, 0.9, 5e-4, 0.2), seed=n % 1000, order="tree")
+
+
+def test_tree_differs_from_left_to_right_only_in_rounding(orc32):
+    """On the GPU alone: K = 8 random buffers summed both ways differ somewhere, by at most K units
+    in the last place of the sum of magnitudes; exact inputs (12 significant bits) give identical
+    bits."""
+    n, K = 100003, 8
+    rng = np.random.default_rng(17)
+    g = [rng.standard_normal(n).astype(F32) for _ in range(K + 1)]
+    sgd = cg.cg_sgd(1.0, 0.0, 0.0, 1.0)
+    outs = []
+    for fn in (cg.cg_grad_reduce_sgd, cg.cg_grad_reduce_sgd_tree):
+        dw, dv = dev(np.zeros(n, F32)), dev(np.zeros(n, F32))
+        fn(dw, dv, dev(g[0]), [dev(p) for p in g[1:]], n, sgd)
+        outs.append(host(dv))
+    bound = K * np.spacing(np.abs(np.stack(g)).sum(0).astype(F32))
+    assert np.any(outs[0] != outs[1])
+    assert np.all(np.abs(outs[0].astype(np.float64) - outs[1].astype(np.float64)) <= bound)
+    q = [(rng.integers(-2048, 2048, n) / 1024.0).astype(F32) for _ in range(K + 1)]
+    outs = []
+    for fn in (cg.cg_grad_reduce_sgd, cg.cg_grad_reduce_sgd_tree):
+        dw, dv = dev(np.zeros(n, F32)), dev(np.zeros(n, F32))
+        fn(dw, dv, dev(q[0]), [dev(p) for p in q[1:]], n, sgd)
+        outs.append(host(dv))
+    assert outs[0].tobytes() == outs[1].tobytes()
+    assert np.array_equal(outs[0].astype(np.float64), np.sum(np.stack(q).astype(np.float64), 0))

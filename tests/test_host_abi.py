@@ -60,6 +60,11 @@ def test_entry_points_reject_null_and_misaligned_arguments_without_launching():
     assert lib.cg_grad_reduce_sgd(16, 36, 48, None, 0, 8, C.byref(s), None) == cg.CG_EINVAL   # misaligned
     assert lib.cg_grad_reduce_sgd(None, None, None, None, 0, 0, C.byref(s), None) == cg.CG_OK  # n == 0: no-op
     assert lib.cg_grad_reduce_sgd(16, 32, 48, None, 0, 8, None, None) == cg.CG_EINVAL
+    assert lib.cg_grad_reduce_sgd_tree(16, 32, 48, None, 65, 8, C.byref(s), None) == cg.CG_EINVAL
+    assert lib.cg_grad_reduce_sgd_tree(16, 32, 48, None, 3, 8, C.byref(s), None) == cg.CG_EINVAL   # K>0, no peers
+    assert lib.cg_grad_reduce_sgd_tree(16, 36, 48, None, 0, 8, C.byref(s), None) == cg.CG_EINVAL   # misaligned
+    assert lib.cg_grad_reduce_sgd_tree(None, None, None, None, 0, 0, C.byref(s), None) == cg.CG_OK
+    assert lib.cg_grad_reduce_sgd_tree_multi(1, None, None, None, None, 0, None, C.byref(s), None) == cg.CG_EINVAL
 
 
 def test_workspace_sizes():
