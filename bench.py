@@ -30,9 +30,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_net(cg, torch, B, K, seed, n_batches=32, inception=False):
+def build_net(cg, torch, B, K, seed, n_batches=32, workload="alexnet"):
     import cg_synth
-    layers, in_shape = cg_synth.inception_layers() if inception else cg_synth.alexnet_layers()
+    layers, in_shape = {"alexnet": cg_synth.alexnet_layers, "inception": cg_synth.inception_layers,
+                        "googlenet": lambda: cg_synth.googlenet_layers()[:2]}[workload]()
     gen = torch.Generator(device="cuda").manual_seed(seed)
     net = cg.Net(layers, B, in_shape)
     # a pool of resident batches, one per step of the run where memory allows: random images with
@@ -205,6 +206,8 @@ def main():
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--skip-update-bench", action="store_true", help="leave out the stand-alone update benchmark")
     ap.add_argument("--update-only", action="store_true", help="only the stand-alone update benchmark (for counter runs)")
+    ap.add_argument("--googlenet-steps", type=int, default=20,
+                    help="steps of the GoogLeNet-shaped workload timed after the main one (0 = skip)")
     ap.add_argument("--inception-steps", type=int, default=30,
                     help="steps of the inception-shaped workload timed after the main one (0 = skip)")
     ap.add_argument("--exclusive-steps", type=int, default=5,
@@ -301,7 +304,7 @@ def main():
     # two inception modules on 192 x 28 x 28, B = 32, K = 8 peers; many small layers, launch-bound
     inception = None
     if args.inception_steps > 0 and not args.serial:
-        ist = build_net(cg, torch, 32, 8, seed=5, n_batches=8, inception=True)
+        ist = build_net(cg, torch, 32, 8, seed=5, n_batches=8, workload="inception")
         torch.cuda.synchronize()
         run_steps(cg, torch, ist, sgd, 5, cg.CG_STEP_OVERLAP)
         sync(torch, ist)
@@ -312,6 +315,25 @@ def main():
         inception = {"workload": "inception_stack_192x28x28_B32_K8", "ms_per_step": ims, "images_per_s": 32 / (ims * 1e-3),
                      "steps": args.inception_steps}
         del ist
+        torch.cuda.empty_cache()
+
+    # ---- the paper's second benchmark net by shape (Table 1: GoogLeNet, batch 32 per worker): stem,
+    # nine inception modules, 7.0 M parameters in 58 layer buckets, K = 8 peers; context, like the above
+    googlenet = None
+    if args.googlenet_steps > 0 and not args.serial:
+        gst = build_net(cg, torch, 32, 8, seed=6, n_batches=8, workload="googlenet")
+        torch.cuda.synchronize()
+        run_steps(cg, torch, gst, sgd, 5, cg.CG_STEP_OVERLAP)
+        sync(torch, gst)
+        t0 = time.perf_counter()
+        run_steps(cg, torch, gst, sgd, args.googlenet_steps, cg.CG_STEP_OVERLAP)
+        sync(torch, gst)
+        gms = (time.perf_counter() - t0) / args.googlenet_steps * 1e3
+        gflop = 3 * 2 * 1.5827 * 32 - 2 * 0.118 * 32       # forward x 3, minus the first layer's backward-data
+        googlenet = {"workload": "googlenet_shaped_train_step_224_B32_K8", "ms_per_step": gms,
+                     "images_per_s": 32 / (gms * 1e-3), "steps": args.googlenet_steps,
+                     "matrix_core_tflops": gflop / gms, "loss": float(gst["loss"][0].item())}
+        del gst
         torch.cuda.empty_cache()
 
     out = {
@@ -335,6 +357,7 @@ def main():
         "serial_schedule_ms_per_step": serial_ms,
         "grad_update": grad_update,
         "inception_step": inception,
+        "googlenet_step": googlenet,
         "cpu_baseline": cpu,
         "loss": loss,
         "paper_context_s_per_iter_other_hw": PAPER_ALEXNET_S_PER_ITER,

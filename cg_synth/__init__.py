@@ -12,6 +12,6 @@ convolution cost does not depend on the values, so N(0,1) tensors of the same
 shapes stand in for the images.
 """
 from .workloads import (  # noqa: F401
-    ALEXNET_CONVS, ALEXNET_BUCKETS, alexnet_layers, tiny_cnn_layers, inception_layers,
+    ALEXNET_CONVS, ALEXNET_BUCKETS, alexnet_layers, tiny_cnn_layers, inception_layers, googlenet_layers,
     infer_shapes, param_layers, conv_layer_tensors, net_tensors, sgd_buckets, xavier_uniform,
 )

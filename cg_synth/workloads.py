@@ -108,6 +108,56 @@ def inception_layers(modules=2, cin=192, hw=28, num_classes=1000):
     return L, (cin, hw, hw)
 
 
+# (1x1, 3x3 reduce, 3x3, 5x5 reduce, 5x5, pool projection) of the nine modules of the 22-layer
+# inception network (Szegedy et al., "Going deeper with convolutions", 2014, Table 1)
+_INCEPTION_V1_MODULES = [
+    ("3a", 64, 96, 128, 16, 32, 32), ("3b", 128, 128, 192, 32, 96, 64), "pool",
+    ("4a", 192, 96, 208, 16, 48, 64), ("4b", 160, 112, 224, 24, 64, 64), ("4c", 128, 128, 256, 24, 64, 64),
+    ("4d", 112, 144, 288, 32, 64, 64), ("4e", 256, 160, 320, 32, 128, 128), "pool",
+    ("5a", 256, 160, 320, 32, 128, 128), ("5b", 384, 192, 384, 48, 128, 128),
+]
+
+
+def googlenet_layers(num_classes=1000, hw=224):
+    """The paper's second benchmark net (Table 1, GoogLeNet, batch 32) by shape: stem (7x7/2 conv,
+    pool, LRN, 1x1 and 3x3 conv, LRN, pool), nine inception modules with two stride-2 pools
+    between them, global average pool, dropout 0.4, FC, softmax cross-entropy.  Every
+    convolution is followed by ReLU; pools are 3x3 (stride 2 between stages, stride 1 pad 1
+    inside a module).  The two auxiliary classifiers of the training net are left out.
+    Returns (layers, input shape, names) with names[i] the label of parameter layer i."""
+    L, names = [], {}
+
+    def add(layer, name=None):
+        L.append(layer)
+        if name:
+            names[len(L) - 1] = name
+        return len(L) - 1
+
+    def conv(src, M, k, name, stride=1, pad=0):
+        return add(_relu(add(_conv(src, M, k, stride=stride, pad=pad), name)))
+
+    t = conv(-1, 64, 7, "conv1", stride=2, pad=3)
+    t = add(_maxpool(t, 3, 2)); t = add(_lrn(t))
+    t = conv(t, 64, 1, "conv2_reduce")
+    t = conv(t, 192, 3, "conv2", pad=1)
+    t = add(_lrn(t)); t = add(_maxpool(t, 3, 2))
+    for m in _INCEPTION_V1_MODULES:
+        if m == "pool":
+            t = add(_maxpool(t, 3, 2))
+            continue
+        tag, c1, r3, c3, r5, c5, pp = m
+        b1 = conv(t, c1, 1, tag + "_1x1")
+        b2 = conv(conv(t, r3, 1, tag + "_3x3_reduce"), c3, 3, tag + "_3x3", pad=1)
+        b3 = conv(conv(t, r5, 1, tag + "_5x5_reduce"), c5, 5, tag + "_5x5", pad=2)
+        b4 = conv(add(_maxpool(t, 3, 1, 1)), pp, 1, tag + "_pool_proj")
+        t = add(dict(kind="concat", inputs=[b1, b2, b3, b4]))
+    t = add(dict(kind="avgpool", inputs=[t]))
+    t = add(dict(kind="dropout", inputs=[t], p=0.4))
+    t = add(dict(kind="fc", inputs=[t], out=num_classes), "classifier")
+    add(dict(kind="softmax_ce", inputs=[t]))
+    return L, (3, hw, hw), names
+
+
 def _pool_out(H, k, s, p):
     o = -(-(H + 2 * p - k) // s) + 1
     if (o - 1) * s >= H + p:

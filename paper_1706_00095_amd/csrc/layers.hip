@@ -223,6 +223,70 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(const float *__restrict
     }
 }
 
+// Planes too large for the LDS staging (beyond POOL_LDS input elements forward, POOL_LDS / 2
+// outputs backward): the same two gathers straight from global memory, one element per thread,
+// `bpp` blocks per plane.  Window order and tie-break are those of the staged kernels.
+__global__ __launch_bounds__(TB) void maxpool_fwd_direct_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                int32_t *__restrict__ argmax, int H, int W, int OH,
+                                                                int OW, int k, int s, int p, uint32_t bpp,
+                                                                FastDiv divBpp, FastDiv divOW)
+{
+    const uint32_t pl = fdiv(blockIdx.x, divBpp), o = (blockIdx.x - pl * bpp) * TB + threadIdx.x;
+    const uint32_t P = (uint32_t)(OH * OW);
+    if (o >= P) return;
+    const int oh = (int)fdiv(o, divOW), ow = (int)(o - (uint32_t)oh * OW);
+    const float *xp = x + (size_t)pl * (uint32_t)(H * W);
+    int best = -1;
+    float bv = 0.f;
+    for (int kh = 0; kh < k; ++kh) {
+        const int ih = oh * s - p + kh;
+        if (ih < 0 || ih >= H) continue;
+        for (int kw = 0; kw < k; ++kw) {
+            const int iw = ow * s - p + kw;
+            if (iw < 0 || iw >= W) continue;
+            const float val = xp[ih * W + iw];
+            if (best < 0 || val > bv) { best = ih * W + iw; bv = val; }
+        }
+    }
+    y[(size_t)pl * P + o] = bv;
+    argmax[(size_t)pl * P + o] = best;
+}
+
+template <int ACC>
+__global__ __launch_bounds__(TB) void maxpool_bwd_direct_kernel(const float *__restrict__ dy,
+                                                                const int32_t *__restrict__ argmax,
+                                                                float *__restrict__ dx, const float *__restrict__ gate,
+                                                                int H, int W, int OH, int OW, int k, int s, int p,
+                                                                uint32_t bpp, FastDiv divBpp, FastDiv divW, FastDiv divS)
+{
+    const uint32_t pl = fdiv(blockIdx.x, divBpp), q = (blockIdx.x - pl * bpp) * TB + threadIdx.x;
+    const uint32_t Q = (uint32_t)(H * W), P = (uint32_t)(OH * OW);
+    if (q >= Q) return;
+    const uint32_t ih = fdiv(q, divW), iw = q - ih * (uint32_t)W;
+    // windows oh with oh*s - p <= ih <= oh*s - p + k - 1
+    int oh_lo = (int)ih + p - k + 1;
+    oh_lo = oh_lo <= 0 ? 0 : (int)fdiv((uint32_t)(oh_lo + s - 1), divS);
+    int oh_hi = (int)fdiv(ih + (uint32_t)p, divS);
+    if (oh_hi > OH - 1) oh_hi = OH - 1;
+    int ow_lo = (int)iw + p - k + 1;
+    ow_lo = ow_lo <= 0 ? 0 : (int)fdiv((uint32_t)(ow_lo + s - 1), divS);
+    int ow_hi = (int)fdiv(iw + (uint32_t)p, divS);
+    if (ow_hi > OW - 1) ow_hi = OW - 1;
+    const int32_t *ap = argmax + (size_t)pl * P;
+    const float *gp = dy + (size_t)pl * P;
+    const size_t at = (size_t)pl * Q + q;
+    const float gt = gate ? gate[at] : 1.f;
+    const float old = ACC ? dx[at] : 0.f;
+    float acc = 0.f;
+    for (int oh = oh_lo; oh <= oh_hi; ++oh)
+        for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+            const int o = oh * OW + ow;
+            if (ap[o] == (int32_t)q) acc += gp[o];
+        }
+    if (!(gt > 0.f)) acc = 0.f;
+    dx[at] = ACC ? old + acc : acc;
+}
+
 // Backward for a window and stride known at compile time.  A thread owns a cell of ST x ST input
 // elements: the (at most NWC x NWC) windows that can cover any of them are read from LDS once,
 // and every element of the cell adds the dy of the windows that elected it, in ascending window
@@ -737,7 +801,13 @@ int maxpool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, 
     if (OH <= 0 || OW <= 0 || p >= k) return CG_EINVAL;
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
-    if (H * W > POOL_LDS) return CG_EUNSUPPORTED;        // one input plane must fit the LDS staging
+    if (H * W > POOL_LDS) {        // an input plane does not fit the LDS staging
+        const uint32_t bpp = ((uint32_t)(OH * OW) + TB - 1) / TB;
+        if ((uint64_t)planes * bpp >= (1ull << 31)) return CG_EUNSUPPORTED;
+        hipLaunchKernelGGL(maxpool_fwd_direct_kernel, dim3(planes * bpp), dim3(TB), 0, st, x, y, argmax, H, W, OH, OW, k,
+                           s, p, bpp, make_fastdiv(bpp), make_fastdiv((uint32_t)OW));
+        CG_LAUNCH_CHECK();
+    }
     const int ppb = pool_planes_per_block(OH * OW, H * W, POOL_LDS);
     const dim3 grid((planes + ppb - 1) / ppb);
     const size_t lds = ((size_t)ppb * H * W + 4) * sizeof(float);
@@ -760,7 +830,18 @@ int maxpool_bwd_launch(const float *dy, const int32_t *argmax, float *dx, const 
     if (OH <= 0 || OW <= 0) return CG_EINVAL;
     if ((uint64_t)N * C >= (1ull << 31) || (uint64_t)H * W >= (1ull << 24)) return CG_EUNSUPPORTED;
     const uint32_t planes = (uint32_t)N * C;
-    if (OH * OW > POOL_LDS / 2) return CG_EUNSUPPORTED;
+    if (OH * OW > POOL_LDS / 2) {  // dy and the winners of a plane do not fit the LDS staging
+        const uint32_t bpp = ((uint32_t)(H * W) + TB - 1) / TB;
+        if ((uint64_t)planes * bpp >= (1ull << 31)) return CG_EUNSUPPORTED;
+        const FastDiv dB = make_fastdiv(bpp), dW = make_fastdiv((uint32_t)W), dS = make_fastdiv((uint32_t)s);
+        if (accumulate)
+            hipLaunchKernelGGL(maxpool_bwd_direct_kernel<1>, dim3(planes * bpp), dim3(TB), 0, st, dy, argmax, dx, gate, H, W,
+                               OH, OW, k, s, p, bpp, dB, dW, dS);
+        else
+            hipLaunchKernelGGL(maxpool_bwd_direct_kernel<0>, dim3(planes * bpp), dim3(TB), 0, st, dy, argmax, dx, gate, H, W,
+                               OH, OW, k, s, p, bpp, dB, dW, dS);
+        CG_LAUNCH_CHECK();
+    }
     const bool cell = ((k == 3 && (s == 2 || s == 1)) || (k == 2 && s == 2)) && 2 * OH * OW + H * W + 20 <= 2 * POOL_LDS;
     if (cell) {
         // staging of dy and the winners plus an LDS copy of the dx planes

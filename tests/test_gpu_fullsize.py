@@ -102,6 +102,16 @@ def test_inception_stack_at_its_real_shape(orc32):
     _check_step(orc32, layers, in_shape, B, t)
 
 
+def test_googlenet_shaped_iteration(orc32):
+    """The paper's second benchmark net by shape (Table 1, GoogLeNet): stem and nine inception
+    modules on 224 x 224 images, 58 parameter layers, here B = 4 with K = 2 peers, every
+    activation, local gradient and updated bucket against the oracle."""
+    layers, in_shape, _ = cg_synth.googlenet_layers()
+    B = 4
+    t = cg_synth.net_tensors(layers, in_shape, B, 2, seed=6, num_classes=1000)
+    _check_step(orc32, layers, in_shape, B, t)
+
+
 def test_update_of_the_eight_alexnet_buckets_in_one_launch(orc32):
     """Configuration 3 at its real sizes (60 965 224 parameters), K = 4: bit-exact, bucket by bucket."""
     sgd = (0.01, 0.9, 5e-4, 1.0)

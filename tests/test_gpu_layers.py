@@ -67,3 +67,17 @@ def test_layer_variants_match_oracle(orc32, lrn_size, pool, in_shape):
     assert folded_fwd == 3 and folded_bwd == 3        # the three rectifiers, both directions
     for li in grads:
         assert max_abs_rel(host(gn.g[li]), grads[li]) <= TOL, ("g_local", li)
+
+
+@pytest.mark.parametrize("lrn_size,pool,in_shape", [(5, (3, 2, 0), (3, 100, 100)), (3, (3, 1, 1), (2, 90, 100)),
+                                                    (5, (4, 3, 1), (2, 130, 70))])
+def test_pooling_planes_beyond_the_lds_staging(orc32, lrn_size, pool, in_shape):
+    """Planes of 10 000 / 9 000 / 9 100 elements: the pooling kernels read them straight from global
+    memory (forward only in the first case, 2 401 outputs a plane; both directions in the second;
+    a window without a specialised kernel in the third).  With a million window comparisons a
+    last-bit difference in forward can elect another winner, so backward is compared from the
+    GPU's own forward state (the winners must then be the oracle's exactly)."""
+    from test_gpu_fullsize import _check_step
+    layers, in_shape = _net(lrn_size, pool, in_shape)
+    t = cg_synth.net_tensors(layers, in_shape, 3, 2, seed=50 + lrn_size, num_classes=7, init="fan_in", peer_std=1e-3)
+    _check_step(orc32, layers, in_shape, 3, t)

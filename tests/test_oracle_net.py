@@ -137,3 +137,45 @@ def test_weight_gradients_do_not_depend_on_pool_tie_break(orc64):
     g2, _, _ = onet.backward(orc64, layers, t["x"], t["buckets"], t["masks"], acts, aux2)
     for li in g1:
         np.testing.assert_allclose(g1[li], g2[li], atol=1e-15)
+
+
+def test_googlenet_shaped_layer_list():
+    """The second benchmark net of the paper's Table 1 by shape: 7.0 M parameters without the
+    auxiliary classifiers, stage widths 256/480, 512/512/512/528/832, 832/1024 on 28, 14 and 7
+    pixel planes (Szegedy et al. 2014, Table 1), 2 x 1.58 G multiply-adds per image forward."""
+    layers, in_shape, names = cg_synth.googlenet_layers()
+    shapes = cg_synth.infer_shapes(layers, in_shape)
+    cat = [shapes[i] for i, ly in enumerate(layers) if ly["kind"] == "concat"]
+    assert cat == [(256, 28, 28), (480, 28, 28), (512, 14, 14), (512, 14, 14), (512, 14, 14), (528, 14, 14),
+                   (832, 14, 14), (832, 7, 7), (1024, 7, 7)]
+    pl = cg_synth.param_layers(layers, in_shape)
+    assert len(pl) == 58 and sorted(names) == [li for li, _, _ in pl]
+    assert sum(int(np.prod(ws)) + nb for _, ws, nb in pl) == 6998552
+    macs = sum(int(np.prod(ws)) * shapes[li][1] * shapes[li][2] for li, ws, _ in pl)
+    assert abs(macs / 1e9 - 1.58) < 0.01
+    assert shapes[0] == (64, 112, 112) and shapes[2] == (64, 56, 56)      # 3x3/2 pool, ceil mode: 112 -> 56
+
+
+def test_googlenet_shaped_net_gradients_by_finite_differences(orc64):
+    """The whole 142-layer composition (fan-out of one tensor into four branches, concat, clipped
+    pool windows) on a 64 x 64 input: finite differences on a few parameters of early, middle and
+    late layers."""
+    layers, in_shape, names = cg_synth.googlenet_layers(num_classes=11, hw=64)
+    t = _to64(cg_synth.net_tensors(layers, in_shape, 2, 0, seed=9, num_classes=11, init="xavier"))
+    rng = np.random.default_rng(71)
+    for li in t["buckets"]:
+        t["buckets"][li] += rng.standard_normal(t["buckets"][li].size) * 0.02
+    loss, acts, aux = onet.forward(orc64, layers, t["x"], t["buckets"], t["labels"], t["masks"])
+    grads, _, _ = onet.backward(orc64, layers, t["x"], t["buckets"], t["masks"], acts, aux)
+    by_name = {v: k for k, v in names.items()}
+    h = 1e-6
+    for nm in ("conv1", "conv2", "3a_5x5_reduce", "4c_3x3", "4e_pool_proj", "5b_1x1", "classifier"):
+        b = t["buckets"][by_name[nm]]
+        g = grads[by_name[nm]]
+        for i in (int(np.argmax(np.abs(g))), b.size - 1):
+            keep = b[i]
+            b[i] = keep + h; lp = float(onet.loss_only(orc64, layers, t["x"], t["labels"], t["buckets"], t["masks"]))
+            b[i] = keep - h; lm = float(onet.loss_only(orc64, layers, t["x"], t["labels"], t["buckets"], t["masks"]))
+            b[i] = keep
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - g[i]) <= 1e-5 * max(abs(fd), 1e-4), (nm, i, fd, g[i])
