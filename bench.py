@@ -131,6 +131,33 @@ def grad_update_standalone(cg, torch, steps, warmup):
     return out
 
 
+def googlenet_workload(cg, torch, sgd, steps, flags, table=False):
+    """The paper's second benchmark net by shape (Table 1: GoogLeNet, batch 32 per worker): stem, nine
+    inception modules, 7.0 M parameters in 58 layer buckets, K = 8 peers.  Context beside the headline
+    workload: 142 layers, most of them small, so the step is bound by launches as much as by arithmetic."""
+    gst = build_net(cg, torch, 32, 8, seed=6, n_batches=8, workload="googlenet")
+    torch.cuda.synchronize()
+    run_steps(cg, torch, gst, sgd, 5, flags)
+    sync(torch, gst)
+    t0 = time.perf_counter()
+    run_steps(cg, torch, gst, sgd, steps, flags)
+    sync(torch, gst)
+    gms = (time.perf_counter() - t0) / steps * 1e3
+    gflop = 3 * 2 * 1.5827 * 32 - 2 * 0.118 * 32       # forward x 3, minus the first layer's backward-data
+    out = {"workload": "googlenet_shaped_train_step_224_B32_K8", "ms_per_step": gms,
+           "images_per_s": 32 / (gms * 1e-3), "steps": steps, "matrix_core_tflops": gflop / gms,
+           "schedule": "serial" if flags == cg.CG_STEP_SERIAL else "overlap", "loss": float(gst["loss"][0].item())}
+    if table:
+        cg.cg_profile_enable(True)
+        run_steps(cg, torch, gst, sgd, 3, cg.CG_STEP_SERIAL)
+        sync(torch, gst)
+        cg.cg_profile_enable(False)
+        kernel_table(collect_profile(cg), 3)
+    del gst
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(sample_B, K):
     """The oracle's whole iteration on `sample_B` images of the same net (one step incl. update)."""
     import cg_synth
@@ -206,6 +233,7 @@ def main():
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--skip-update-bench", action="store_true", help="leave out the stand-alone update benchmark")
     ap.add_argument("--update-only", action="store_true", help="only the stand-alone update benchmark (for counter runs)")
+    ap.add_argument("--googlenet-only", action="store_true", help="only the GoogLeNet-shaped workload (for profiles)")
     ap.add_argument("--googlenet-steps", type=int, default=20,
                     help="steps of the GoogLeNet-shaped workload timed after the main one (0 = skip)")
     ap.add_argument("--inception-steps", type=int, default=30,
@@ -236,6 +264,10 @@ def main():
         return
 
     flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
+    if args.googlenet_only:
+        print(json.dumps({"googlenet_step": googlenet_workload(cg, torch, sgd, max(args.googlenet_steps, 1), flags,
+                                                               args.kernel_table)}), flush=True)
+        return
     extra = args.exclusive_steps if not args.serial else 0
     st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps + extra)))
     torch.cuda.synchronize()
@@ -317,24 +349,9 @@ def main():
         del ist
         torch.cuda.empty_cache()
 
-    # ---- the paper's second benchmark net by shape (Table 1: GoogLeNet, batch 32 per worker): stem,
-    # nine inception modules, 7.0 M parameters in 58 layer buckets, K = 8 peers; context, like the above
     googlenet = None
     if args.googlenet_steps > 0 and not args.serial:
-        gst = build_net(cg, torch, 32, 8, seed=6, n_batches=8, workload="googlenet")
-        torch.cuda.synchronize()
-        run_steps(cg, torch, gst, sgd, 5, cg.CG_STEP_OVERLAP)
-        sync(torch, gst)
-        t0 = time.perf_counter()
-        run_steps(cg, torch, gst, sgd, args.googlenet_steps, cg.CG_STEP_OVERLAP)
-        sync(torch, gst)
-        gms = (time.perf_counter() - t0) / args.googlenet_steps * 1e3
-        gflop = 3 * 2 * 1.5827 * 32 - 2 * 0.118 * 32       # forward x 3, minus the first layer's backward-data
-        googlenet = {"workload": "googlenet_shaped_train_step_224_B32_K8", "ms_per_step": gms,
-                     "images_per_s": 32 / (gms * 1e-3), "steps": args.googlenet_steps,
-                     "matrix_core_tflops": gflop / gms, "loss": float(gst["loss"][0].item())}
-        del gst
-        torch.cuda.empty_cache()
+        googlenet = googlenet_workload(cg, torch, sgd, args.googlenet_steps, cg.CG_STEP_OVERLAP)
 
     out = {
         "metric": "images/sec per fwd+bwd+update step (AlexNet-shaped B=256); grad-update HBM GB/s",

@@ -196,7 +196,7 @@ int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local,
 /* Device workspace (activations, gradients of activations, kernel scratch). */
 size_t cg_net_workspace_bytes(const cg_net *net);
 
-enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1 };
+enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2 };
 
 /* One SGD iteration of this worker (Fig. 1 with the turn-based schedule of
  * Fig. 3): forward through layers 1..L, loss, then for l = L..1 the local
@@ -209,9 +209,18 @@ enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1 };
  *  the array may be NULL if the net has no dropout layer), loss_dev: 1 float.
  *  flags: CG_STEP_SERIAL runs the same kernels in the same order on
  *  compute_stream alone (the separate-phases schedule the paper improves on).
+ * Backward-weight passes run beside backward-data on a stream the net owns.
  * The loss and the local gradients are valid in compute_stream order, the
  * updated w and v in update_stream order.
- * The two streams must differ unless CG_STEP_SERIAL is given. */
+ * The two streams must differ unless CG_STEP_SERIAL is given.
+ *  CG_STEP_JOIN (with the overlapped schedule): at the end of the call
+ *  compute_stream also waits for the last update, so that every stream the call
+ *  used has joined compute_stream and the next call depends on no event of this
+ *  one.  That is the form a caller can record into a HIP graph by stream capture
+ *  on compute_stream (the call allocates nothing and synchronises nothing);
+ *  the call before the captured one must have been made with this flag as
+ *  well, or be complete, and cg_profile_enable must be off.  The price is the
+ *  overlap of the last layers' updates with the next call's forward. */
 int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                   const uint8_t *const *dropout_masks, const cg_sgd *sgd,
                   void *ws, size_t ws_bytes, void *compute_stream, void *update_stream,
@@ -223,6 +232,15 @@ int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
  * lives inside a workspace of base address ws after a step; for inspection by
  * tests.  count receives the number of 4-byte elements. */
 int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, float **ptr, size_t *count);
+
+/* Elements between consecutive images of a layer's output (which = 0 above).
+ * C*H*W for a dense tensor.  A convolution whose rectifier feeds only a concat
+ * layer writes straight into its channel slice of the concat's output: for it
+ * and for that rectifier this is the concat's C*H*W, ptr above is the slice of
+ * image 0 and count spans up to the end of the last image's slice.  (The
+ * concat's backward then also applies that rectifier's gate, so the gradient
+ * with respect to the rectifier's output is not materialised.) */
+long long cg_net_tensor_image_stride(const cg_net *net, int layer);
 
 /* Test hook: forward and stride-1 backward-data convolutions with enough
  * output tiles to fill the chip without cutting the reduction (512 by default)

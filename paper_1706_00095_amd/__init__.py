@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("CG_LIB_PATH", os.path.join(_HERE, "libcg.so"))
 
 CG_OK, CG_EINVAL, CG_ENOSPC, CG_EUNSUPPORTED, CG_EHIP = 0, -1, -2, -3, -4
 CG_PASS_FWD, CG_PASS_BWD_DATA, CG_PASS_BWD_WEIGHT = 0, 1, 2
-CG_STEP_OVERLAP, CG_STEP_SERIAL = 0, 1
+CG_STEP_OVERLAP, CG_STEP_SERIAL, CG_STEP_JOIN = 0, 1, 2
 CG_MAX_PEERS = 64
 LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc": 5, "dropout": 6,
                "concat": 7, "softmax_ce": 8}
@@ -23,7 +23,7 @@ LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc":
 EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight",
     "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_grad_reduce_sgd_tree", "cg_grad_reduce_sgd_tree_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
-    "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
+    "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_net_tensor_image_stride", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
 
@@ -86,6 +86,8 @@ def lib():
         L.cg_net_param_count.restype = C.c_longlong
         L.cg_net_layer_fused.argtypes = [vp, C.c_int]
         L.cg_net_layer_fused.restype = C.c_int
+        L.cg_net_tensor_image_stride.argtypes = [vp, C.c_int]
+        L.cg_net_tensor_image_stride.restype = C.c_longlong
         L.cg_net_bind.argtypes = [vp, C.c_int, vp, vp, vp, C.POINTER(vp), C.c_int]
         L.cg_net_workspace_bytes.argtypes = [vp]
         L.cg_net_workspace_bytes.restype = sz
@@ -273,6 +275,7 @@ class Net:
 
     def __init__(self, layers, B, in_shape):
         self.layers = layers
+        self.B = B
         self.handle = C.c_void_p()
         descs = layer_descs(layers)
         _check(lib().cg_net_create(descs, len(layers), B, *in_shape, C.byref(self.handle)), "cg_net_create")
@@ -332,4 +335,10 @@ def cg_net_tensor(net, layer, which, ws):
     p, n = C.c_void_p(), C.c_size_t()
     _check(lib().cg_net_tensor(net.handle, layer, which, _ptr(ws), C.byref(p), C.byref(n)), "cg_net_tensor")
     off = (p.value - ws.data_ptr()) // 4
-    return ws.view(torch.float32)[off:off + n.value]
+    flat = ws.view(torch.float32)[off:off + n.value]
+    if which == 0:
+        stride = int(lib().cg_net_tensor_image_stride(net.handle, layer))
+        per_image = n.value - (net.B - 1) * stride
+        if per_image != stride:       # a channel slice of a wider tensor: gathered into a dense copy
+            return torch.as_strided(flat, (net.B, per_image), (stride, 1)).reshape(-1)
+    return flat

@@ -201,7 +201,7 @@ size_t conv_ws_bytes(const cg_conv_desc &d, int pass);
 size_t fc_ws_bytes(int B, int IN, int OUT, int pass);
 // relu != 0: y = max(conv + bias, 0), the rectifier that follows folded into the store
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, int relu, hipStream_t stream);
+                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream);
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
@@ -246,6 +246,6 @@ int softmax_ce_launch(const float *z, const int32_t *labels, float *loss, float 
                       hipStream_t st);
 // dst[n][c_off + c][hw] = src[n][c][hw]  (forward of a channel concat) or the reverse slice copy
 int concat_copy_launch(const float *src, float *dst, int N, int Csrc, int Cdst, int c_off, int HW, int to_concat,
-                       int accumulate, hipStream_t st);
+                       int accumulate, const float *gate, hipStream_t st);
 
 }  // namespace cg

@@ -234,7 +234,7 @@ int conv_check(const cg_conv_desc *d, int *OH, int *OW)
 }
 
 static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const float *x, const float *w,
-                                const float *bias, float *y)
+                                const float *bias, float *y, int64_t y_img_stride = 0)
 {
     const int G = d.groups, Cg = d.C / G, Mg = d.M / G, Kg = Cg * d.KH * d.KW, P = OH * OW;
     IgemmProblem p{};
@@ -255,7 +255,7 @@ static IgemmProblem fwd_problem(const cg_conv_desc &d, int OH, int OW, const flo
     p.B.check = (d.pad_h || d.pad_w) ? 1 : 0;
     p.c_ptr = y;
     p.c_row_stride = P;
-    p.c_col = split_map((uint32_t)d.N * P, P, d.M * P, 1);
+    p.c_col = split_map((uint32_t)d.N * P, P, y_img_stride ? (int32_t)y_img_stride : d.M * P, 1);
     p.c_gstride = (int64_t)Mg * P;
     p.bias = bias; p.bias_mode = bias ? 1 : 0; p.bias_gstride = Mg;
     p.M = Mg; p.N = (uint32_t)d.N * P; p.K = Kg;
@@ -316,13 +316,17 @@ static void tap_major_filters(IgemmProblem &p, const float *m, int rows, int K, 
 }
 
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, int relu, hipStream_t stream)
+                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride)
 {
     ProfTag tag("conv_fwd", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
-    IgemmProblem p = fwd_problem(d, OH, OW, x, w, bias, y);
+    // y_img_stride: elements between the images of y when y is a channel slice of a wider tensor
+    // (0 = dense, M*OH*OW); the whole wider tensor must stay below 2^31 elements
+    if (y_img_stride < 0 || (y_img_stride && (y_img_stride < (int64_t)d.M * OH * OW ||
+                                              y_img_stride * (int64_t)d.N >= (1ll << 31)))) return CG_EINVAL;
+    IgemmProblem p = fwd_problem(d, OH, OW, x, w, bias, y, y_img_stride);
     p.relu = relu;
     if (fwd_patch(d, OH, OW, x, p)) {
         const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW;

@@ -1740,14 +1740,16 @@ int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, 
 {
     if (!dy || !db || N <= 0 || M <= 0 || P <= 0) return CG_EINVAL;
     if (!ws || ws_bytes < bias_grad_ws_bytes(N, M)) return CG_ENOSPC;
-    const int S = bias_slices(N, M);
+    // a small layer: one block per channel sums all images and writes db itself (one launch)
+    const int S = (uint64_t)N * P <= 32768 ? 1 : bias_slices(N, M);
     const int n_per = (N + S - 1) / S;
     const int S2 = (N + n_per - 1) / n_per;
     float *part = static_cast<float *>(ws);
     if ((uint64_t)n_per * (uint64_t)((P + 3) / 4) >= (1ull << 31)) return CG_EUNSUPPORTED;     // 32-bit pair index
     hipLaunchKernelGGL(bias_grad_partial_kernel, dim3(M, S2), dim3(256), 0, stream, dy, N, M, P, n_per,
-                       make_fastdiv((uint32_t)(P + 3) / 4), part);
+                       make_fastdiv((uint32_t)(P + 3) / 4), S2 == 1 ? db : part);
     CG_HIP_TRY(hipGetLastError());
+    if (S2 == 1) return CG_OK;
     hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, part, M, S2, db);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;

@@ -711,16 +711,23 @@ __global__ __launch_bounds__(TB) void mean_kernel(const float *__restrict__ v, f
 }
 
 __global__ __launch_bounds__(TB) void concat_copy_kernel(const float *__restrict__ src, float *__restrict__ dst,
-                                                         size_t total, int Csrc, int Cdst, int c_off, int HW,
-                                                         int to_concat, int accumulate)
+                                                         const float *__restrict__ gate, size_t total, int Csrc,
+                                                         int Cdst, int c_off, int HW, int to_concat, int accumulate)
 {
-    // `total` runs over the slice [N][Csrc][HW]; the concat tensor is [N][Cdst][HW]
+    // `total` runs over the slice [N][Csrc][HW]; the concat tensor is [N][Cdst][HW].  `gate` (from the
+    // concat tensor to the slice only) is a tensor of the concat's shape holding the output of the
+    // rectifier that produced the slice: the result is the gradient of that rectifier's input.
     const size_t plane = (size_t)Csrc * HW;
     for (size_t i = (size_t)blockIdx.x * TB + threadIdx.x; i < total; i += (size_t)gridDim.x * TB) {
         const size_t n = i / plane, r = i - n * plane;
         const size_t big = (n * Cdst + c_off) * HW + r;
-        if (to_concat) dst[big] = src[i];
-        else dst[i] = accumulate ? dst[i] + src[big] : src[big];
+        if (to_concat) {
+            dst[big] = src[i];
+        } else {
+            float val = src[big];
+            if (gate && !(gate[big] > 0.f)) val = 0.f;
+            dst[i] = accumulate ? dst[i] + val : val;
+        }
     }
 }
 
@@ -975,11 +982,11 @@ int softmax_ce_launch(const float *z, const int32_t *labels, float *loss, float 
 }
 
 int concat_copy_launch(const float *src, float *dst, int N, int Csrc, int Cdst, int c_off, int HW, int to_concat,
-                       int accumulate, hipStream_t st)
+                       int accumulate, const float *gate, hipStream_t st)
 {
     const size_t total = (size_t)N * Csrc * HW;
-    hipLaunchKernelGGL(concat_copy_kernel, dim3(grid_for(total)), dim3(TB), 0, st, src, dst, total, Csrc, Cdst, c_off,
-                       HW, to_concat, accumulate);
+    hipLaunchKernelGGL(concat_copy_kernel, dim3(grid_for(total)), dim3(TB), 0, st, src, dst, gate, total, Csrc, Cdst,
+                       c_off, HW, to_concat, accumulate);
     CG_LAUNCH_CHECK();
 }
 

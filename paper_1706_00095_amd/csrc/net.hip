@@ -30,6 +30,8 @@ struct cg_net {
         hipEvent_t ev_grad = nullptr, ev_upd = nullptr;
         hipEvent_t ev_dy = nullptr, ev_bd = nullptr;   // gradient of the output complete / backward-data done
         bool upd_pending = false;             // an update of this layer was enqueued by a previous step
+        hipEvent_t upd_event = nullptr;       // the event that update completes with: this layer's ev_upd, or that of
+                                              // the last layer of the launch the update went out with
         bool grad_written = false;            // per step: has anything been written to this layer's gradient?
         bool needs_grad = false;              // false when no parameter lies upstream of this output
         // A rectifier that is the only consumer of a convolution or fully-connected layer is folded
@@ -45,12 +47,21 @@ struct cg_net {
         // the consumer knows the rectifier by gate_from.
         bool bwd_folded = false;
         int gate_from = -1;
+        // A convolution whose folded rectifier feeds nothing but one concat writes straight into its
+        // channel slice of the concat's output (out_img_stride = elements between images there; its
+        // and the rectifier's act_off point at the slice), and the concat's backward gates the slice of
+        // its gradient with that output on the way to the convolution's gradient (the rectifier is
+        // bwd_folded with in_concat = the concat layer).
+        long long out_img_stride = 0;
+        int in_concat = -1;
     };
+
     int B = 0, C = 0, H = 0, W = 0;
     std::vector<Layer> layers;
     size_t scratch_off = 0, scratch_bytes = 0;   // kernel scratch (filter copies, split-K partials): two regions of
                                                  // scratch_bytes, one per stream that launches matrix kernels
     hipStream_t wgrad_stream = nullptr;          // backward-weight passes run here, beside backward-data
+    hipEvent_t ev_join = nullptr;                // tail of the update stream (CG_STEP_JOIN)
     size_t loss_off = 0;                         // B floats of per-sample loss
     size_t ws_floats = 0;
 };
@@ -193,6 +204,34 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
             net->layers[who].gate_from = r;
         }
     }
+    if (rc == CG_OK) {
+        for (int j = 0; j < L; ++j) {
+            Layer &cat = net->layers[j];
+            if (cat.d.kind != CG_LAYER_CONCAT) continue;
+            int c_off = 0;
+            for (int k = 0; k < cat.d.n_inputs; ++k) {
+                const int r = cat.d.inputs[k];
+                int c, h, w;
+                in_shape(*net, r, &c, &h, &w);
+                const int my_off = c_off;
+                c_off += c;
+                if (r < 0) continue;
+                Layer &rl = net->layers[r];
+                if (rl.d.kind != CG_LAYER_RELU || rl.alias_of < 0 || net->layers[rl.alias_of].d.kind != CG_LAYER_CONV) continue;
+                int consumers = 0;
+                for (int j2 = 0; j2 < L; ++j2)
+                    for (int k2 = 0; k2 < net->layers[j2].d.n_inputs; ++k2)
+                        if (net->layers[j2].d.inputs[k2] == r) ++consumers;
+                // the slice must start on a 16-byte boundary like every tensor the kernels are given
+                if (consumers != 1 || cat.out_elems >= (1ull << 31) || ((size_t)my_off * cat.H * cat.W) % 4 != 0) continue;
+                Layer &cv = net->layers[rl.alias_of];
+                cv.out_img_stride = rl.out_img_stride = (long long)cat.C * cat.H * cat.W;
+                cv.act_off = rl.act_off = cat.act_off + (size_t)my_off * cat.H * cat.W;
+                cv.in_concat = rl.in_concat = j;
+                if (cv.needs_grad) rl.bwd_folded = true;
+            }
+        }
+    }
     if (rc == CG_OK && net->layers[L - 1].d.kind != CG_LAYER_SOFTMAX_CE) rc = CG_EINVAL;
     if (rc == CG_OK) {
         // the logits feed the loss only: its gradient is written by the loss kernel
@@ -214,6 +253,7 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
                     hipEventCreateWithFlags(&ly.ev_bd, hipEventDisableTiming) != hipSuccess) { rc = CG_EHIP; break; }
             }
         if (rc == CG_OK && hipStreamCreateWithFlags(&net->wgrad_stream, hipStreamNonBlocking) != hipSuccess) rc = CG_EHIP;
+        if (rc == CG_OK && hipEventCreateWithFlags(&net->ev_join, hipEventDisableTiming) != hipSuccess) rc = CG_EHIP;
     }
     if (rc != CG_OK) { cg_net_destroy(net); return rc; }
     *out = net;
@@ -230,6 +270,7 @@ extern "C" int cg_net_destroy(cg_net *net)
         if (ly.ev_bd) (void)hipEventDestroy(ly.ev_bd);
     }
     if (net->wgrad_stream) (void)hipStreamDestroy(net->wgrad_stream);
+    if (net->ev_join) (void)hipEventDestroy(net->ev_join);
     delete net;
     return CG_OK;
 }
@@ -276,7 +317,16 @@ extern "C" int cg_net_tensor(const cg_net *net, int layer, int which, void *ws, 
     else if (which == 2) *ptr = base + ly.aux_off;
     else return CG_EINVAL;
     *count = which == 2 ? ly.aux_elems : ly.out_elems;
+    if (which == 0 && ly.out_img_stride)
+        *count = (size_t)(net->B - 1) * (size_t)ly.out_img_stride + (size_t)ly.C * ly.H * ly.W;
     return CG_OK;
+}
+
+extern "C" long long cg_net_tensor_image_stride(const cg_net *net, int layer)
+{
+    if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
+    const Layer &ly = net->layers[layer];
+    return ly.out_img_stride ? ly.out_img_stride : (long long)ly.C * ly.H * ly.W;
 }
 
 extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels, const uint8_t *const *masks,
@@ -309,6 +359,8 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
     auto act = [&](int i) -> const float * { return i < 0 ? x : base + net->layers[i].act_off; };
     int rc = CG_OK;
 
+    hipEvent_t waited_upd = nullptr;             // the update event the compute stream waited for last
+
     // ---- forward, layers 1..L --------------------------------------------------------------
     for (int i = 0; i < L && rc == CG_OK; ++i) {
         Layer &ly = net->layers[i];
@@ -319,13 +371,15 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         ProfTag tag("", i);
         if (ly.n_params && ly.upd_pending) {
             // finalize, per layer: the model of this layer must have received its update
-            CG_HIP_TRY(hipStreamWaitEvent(S0, ly.ev_upd, 0));
+            if (ly.upd_event != waited_upd) CG_HIP_TRY(hipStreamWaitEvent(S0, ly.upd_event, 0));
+            waited_upd = ly.upd_event;
             ly.upd_pending = false;
         }
         const size_t in_elems = (size_t)B * ly.inC * ly.inH * ly.inW;
         switch (d.kind) {
         case CG_LAYER_CONV:
-            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, ly.fused_relu, S0);
+            rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, ly.fused_relu, S0,
+                               ly.out_img_stride);
             break;
         case CG_LAYER_FC:
             rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, scratch,
@@ -348,7 +402,8 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             for (int k = 0; k < d.n_inputs && rc == CG_OK; ++k) {
                 int c, h, w;
                 in_shape(*net, d.inputs[k], &c, &h, &w);
-                rc = concat_copy_launch(act(d.inputs[k]), out, B, c, ly.C, c_off, ly.H * ly.W, 1, 0, S0);
+                const bool in_place = d.inputs[k] >= 0 && net->layers[d.inputs[k]].in_concat == i;
+                if (!in_place) rc = concat_copy_launch(act(d.inputs[k]), out, B, c, ly.C, c_off, ly.H * ly.W, 1, 0, nullptr, S0);
                 c_off += c;
             }
             break;
@@ -363,6 +418,52 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         }
     }
     if (rc) return rc;
+
+    // Layers whose gradients are complete (in stream order) and whose updates have not been launched yet.
+    std::vector<int> pend;
+    size_t pend_params = 0;
+    constexpr long long kBatchParams = 1ll << 20;
+    auto flush_updates = [&]() -> int {
+        if (pend.empty()) return CG_OK;
+        Layer &last = net->layers[pend.back()];
+        if (!serial) {
+            // the update overwrites the models backward-data reads and consumes the gradients
+            // backward-weight writes: it waits for both streams, which run the layers in turn order
+            CG_HIP_TRY(hipEventRecord(last.ev_grad, S2));
+            CG_HIP_TRY(hipEventRecord(last.ev_bd, S0));
+            CG_HIP_TRY(hipStreamWaitEvent(S1, last.ev_grad, 0));
+            CG_HIP_TRY(hipStreamWaitEvent(S1, last.ev_bd, 0));
+            last_wgrad = last.ev_grad;
+        }
+        float *w[8], *v[8];
+        const float *g[8];
+        const float *const *peers[8];
+        size_t n[8];
+        const int nb = (int)pend.size();
+        for (int k = 0; k < nb; ++k) {
+            Layer &l = net->layers[pend[k]];
+            w[k] = l.w; v[k] = l.v; g[k] = l.g; peers[k] = l.peers.data(); n[k] = (size_t)l.n_params;
+        }
+        const int rcu = grad_reduce_sgd_multi_impl(nb, w, v, g, peers, (int)last.peers.size(), n, *sgd, S1);
+        if (rcu) return rcu;
+        if (!serial) {
+            CG_HIP_TRY(hipEventRecord(last.ev_upd, S1));
+            for (int k = 0; k < nb; ++k) {
+                net->layers[pend[k]].upd_event = last.ev_upd;
+                net->layers[pend[k]].upd_pending = true;
+            }
+        }
+        pend.clear();
+        pend_params = 0;
+        return CG_OK;
+    };
+
+    // the layer whose gradient concat layer `cat` writes for its input `sk`: the input itself, or,
+    // where the input is a rectifier folded into this concat, the rectifier's producer
+    auto concat_target = [&](int cat, int sk) -> int {
+        const Layer &src = net->layers[sk];
+        return src.bwd_folded && src.in_concat == cat ? src.d.inputs[0] : sk;
+    };
 
     // ---- backward, layers L..1, one turn per layer ----------------------------------------
     for (int i = L - 2; i >= 0 && rc == CG_OK; --i) {
@@ -429,10 +530,13 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                 in_shape(*net, d.inputs[k], &c, &h, &w);
                 const int sk = d.inputs[k];
                 if (sk >= 0 && net->layers[sk].needs_grad) {
-                    Layer &src = net->layers[sk];
-                    rc = concat_copy_launch(dy, base + src.grad_off, B, c, ly.C, c_off, ly.H * ly.W, 0,
-                                            src.grad_written ? 1 : 0, S0);
-                    src.grad_written = true;
+                    const int t = concat_target(i, sk);
+                    Layer &T = net->layers[t];
+                    // through a folded rectifier: gated by the rectifier's output, which is this
+                    // layer's own output slice
+                    rc = concat_copy_launch(dy, base + T.grad_off, B, c, ly.C, c_off, ly.H * ly.W, 0,
+                                            T.grad_written ? 1 : 0, t != sk ? base + ly.act_off : nullptr, S0);
+                    T.grad_written = true;
                 }
                 c_off += c;
             }
@@ -444,27 +548,38 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         if (want_dx && d.kind != CG_LAYER_CONCAT) net->layers[tgt].grad_written = true;
 
         if (ly.n_params) {
-            // the turn's second half: aggregate this layer's gradient over the ranks and update its model
-            if (!serial) {
-                // the update overwrites the model backward-data reads and consumes the gradient
-                // backward-weight writes: it waits for both
-                CG_HIP_TRY(hipEventRecord(ly.ev_grad, S2));
-                CG_HIP_TRY(hipEventRecord(ly.ev_bd, S0));
-                CG_HIP_TRY(hipStreamWaitEvent(S1, ly.ev_grad, 0));
-                CG_HIP_TRY(hipStreamWaitEvent(S1, ly.ev_bd, 0));
-                last_wgrad = ly.ev_grad;
+            // the turn's second half: aggregate this layer's gradient over the ranks and update its model.
+            // Small layers wait for their neighbours: up to eight of them, or a million parameters, go out
+            // in one launch (a net of many small layers is bound by the number of launches, and the
+            // layer-wise update does not care how many layers a launch carries); a large layer goes at once.
+            const bool big = ly.n_params >= kBatchParams;
+            if (!pend.empty() && (big || net->layers[pend[0]].peers.size() != ly.peers.size())) {
+                rc = flush_updates();
+                if (rc) return rc;
             }
-            rc = grad_reduce_sgd_impl(ly.w, ly.v, ly.g, ly.peers.data(), (int)ly.peers.size(), (size_t)ly.n_params,
-                                      *sgd, S1);
+            pend.push_back(i);
+            pend_params += (size_t)ly.n_params;
+            if (big || pend.size() == 8 || pend_params >= (size_t)kBatchParams) rc = flush_updates();
             if (rc) return rc;
-            if (!serial) {
-                CG_HIP_TRY(hipEventRecord(ly.ev_upd, S1));
-                ly.upd_pending = true;
-            }
         }
     }
+    if (rc == CG_OK) rc = flush_updates();
+    if (rc) return rc;
     // the local gradients are promised in compute-stream order, and the next call's forward may
     // overwrite what the last backward-weight still reads
     if (!serial && last_wgrad) CG_HIP_TRY(hipStreamWaitEvent(S0, last_wgrad, 0));
+    if (rc == CG_OK && !serial && (flags & CG_STEP_JOIN)) {
+        // the update stream joins the compute stream as well: nothing of this step is left on a stream
+        // the caller has not passed, and the next call waits for no event of this one
+        bool any = false;
+        for (Layer &ly : net->layers) {
+            any = any || ly.upd_pending;
+            ly.upd_pending = false;
+        }
+        if (any) {
+            CG_HIP_TRY(hipEventRecord(net->ev_join, S1));
+            CG_HIP_TRY(hipStreamWaitEvent(S0, net->ev_join, 0));
+        }
+    }
     return rc;
 }
