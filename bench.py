@@ -30,6 +30,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+_STREAMS = []
+
+
 def build_net(cg, torch, B, K, seed, n_batches=32, workload="alexnet"):
     import cg_synth
     layers, in_shape = {"alexnet": cg_synth.alexnet_layers, "inception": cg_synth.inception_layers,
@@ -61,7 +64,11 @@ def build_net(cg, torch, B, K, seed, n_batches=32, workload="alexnet"):
             st["masks"][i] = (torch.rand((B, C * H * W), device="cuda", generator=gen) >= ly["p"]).to(torch.uint8)
     st["ws"] = torch.empty(cg.cg_net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
     st["loss"] = torch.zeros(4, device="cuda")
-    st["s0"], st["s1"] = torch.cuda.Stream(), torch.cuda.Stream()
+    # every workload of a run uses the same two streams: a process gets few hardware queues, and
+    # streams made later may share one with each other
+    if not _STREAMS:
+        _STREAMS.extend([torch.cuda.Stream(), torch.cuda.Stream()])
+    st["s0"], st["s1"] = _STREAMS
     return st
 
 
@@ -330,7 +337,6 @@ def main():
         for k, v in grad_update.items():
             t = traffic.get(f"standalone_update_{k}")
             v["traffic"] = (t["fetch_bytes"] + t["write_bytes"]) if t else None
-    cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
 
     # ---- the second workload shape of the paper (GoogLeNet-like modules), outside the timed region:
     # two inception modules on 192 x 28 x 28, B = 32, K = 8 peers; many small layers, launch-bound
@@ -352,6 +358,10 @@ def main():
     googlenet = None
     if args.googlenet_steps > 0 and not args.serial:
         googlenet = googlenet_workload(cg, torch, sgd, args.googlenet_steps, cg.CG_STEP_OVERLAP)
+
+    # the oracle last: its OpenMP workers keep spinning for a while after their last loop and would
+    # take host cores from the launch-bound workloads above
+    cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
 
     out = {
         "metric": "images/sec per fwd+bwd+update step (AlexNet-shaped B=256); grad-update HBM GB/s",
