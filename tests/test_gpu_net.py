@@ -84,6 +84,50 @@ def test_overlapped_schedule_is_bit_identical_to_serial(name):
     assert not torch.equal(a.w[max(a.w)], GpuNet(layers, in_shape, B, t).w[max(a.w)])
 
 
+@pytest.mark.parametrize("name", ["alexnet_like", "inception"])
+def test_joined_step_recorded_into_a_hip_graph_replays_bit_identically(name):
+    """CG_STEP_JOIN leaves nothing on a stream the caller did not pass and depends on no event of the
+    call before, so stream capture on the compute stream records the whole iteration (three streams,
+    their events) into one HIP graph.  Every replay, with eager work and synchronisation between
+    replays, must give the bits of the eager iteration with the same number."""
+    layers, in_shape, B, t = _build(name)
+    a, b = GpuNet(layers, in_shape, B, t), GpuNet(layers, in_shape, B, t)
+    ref = []
+    for _ in range(5):
+        a.step(SGD, cg.CG_STEP_JOIN)
+        a.sync()
+        ref.append((a.loss[:1].clone(), {li: (a.w[li].clone(), a.v[li].clone(), a.g[li].clone()) for li in a.w}))
+    # and the joined form itself changes nothing against the plain overlapped schedule
+    c = GpuNet(layers, in_shape, B, t)
+    for _ in range(5):
+        c.step(SGD, cg.CG_STEP_OVERLAP)
+    c.sync()
+    assert all(torch.equal(c.w[li], a.w[li]) and torch.equal(c.v[li], a.v[li]) for li in a.w)
+
+    def same(k):
+        loss, state = ref[k]
+        assert torch.equal(b.loss[:1], loss), k
+        for li, (w, v, g) in state.items():
+            assert torch.equal(b.w[li], w) and torch.equal(b.v[li], v) and torch.equal(b.g[li], g), (k, li)
+
+    b.step(SGD, cg.CG_STEP_JOIN)          # iteration 0 eagerly: the captured call follows a joined one
+    b.sync()
+    same(0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=b.s0):
+        b.step(SGD, cg.CG_STEP_JOIN)      # recorded, not run
+    b.sync()
+    same(0)
+    for k in range(1, 5):
+        with torch.cuda.stream(b.s0):
+            graph.replay()
+        b.sync()
+        same(k)
+        junk = torch.randn(1 << 16, device="cuda")       # eager work between replays
+        assert bool(torch.isfinite(junk.sum()))
+        torch.cuda.synchronize()
+
+
 def test_loss_decreases_over_iterations_on_fixed_batch():
     layers, in_shape, B, t = _build("tiny_cnn_cfg1")
     for li in t["peers"]:
