@@ -1095,7 +1095,7 @@ bool quad_ok(const Operand &o, uint32_t)
 // odd one out runs alone and a little slower than a pair) times a block's duration, rows + a fixed
 // per-block part; problems with few tiles are cut along K afterwards, which fills the chip for any
 // tile height, so there only the per-block efficiency counts.
-int pick_mt(uint32_t M, uint32_t N, uint32_t groups)
+int pick_mt(uint32_t M, uint32_t N, uint32_t groups, uint32_t K = 0)
 {
     const int cand[6] = {256, 192, 128, 96, 64, 32};
     int best = 32;
@@ -1103,7 +1103,14 @@ int pick_mt(uint32_t M, uint32_t N, uint32_t groups)
     for (int c : cand) {
         const uint64_t tiles = (uint64_t)((M + c - 1) / c) * ((N + 127) / 128) * groups;
         double cost;
-        if (tiles < 512) {
+        if (tiles < 512 && K && K / 128 < kSplitBlocks / tiles) {
+            // a short reduction cannot be cut into enough slices to fill the chip: the blocks all run
+            // at once (or two to a unit), and what counts is how long one of them takes, in the same
+            // unit as below (block duration per K-tile of the whole reduction, blocks per unit)
+            const uint64_t splits = K / 128 >= 2 ? K / 128 : 1;
+            const uint64_t kt = (K + KT - 1) / KT, kt_per = (kt + splits - 1) / splits;
+            cost = (double)((tiles * splits + 255) / 256) * (c + 50) * (double)kt_per / (double)kt;
+        } else if (tiles < 512) {
             cost = (double)tiles * (c + 50) / 256.0;                  // cut along K afterwards into one round of resident blocks
         } else {
             const uint64_t n = (tiles + 255) / 256;
@@ -1500,7 +1507,7 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     if (!p.A.check) { p.A.limA = p.A.limB = 1; }
     if (!p.B.check) { p.B.limA = p.B.limB = 1; }
 
-    const int mt = pick_mt(p.M, p.N, p.groups);
+    const int mt = pick_mt(p.M, p.N, p.groups, p.K);
     const bool bc = p.B.check != 0;
     const int am = quad_ok(p.A, p.K) ? LD_K4 : p.A.lanes_k ? LD_K : LD_ROWS;
     int bm = quad_ok(p.B, p.K) ? LD_K4 : p.B.lanes_k ? LD_K : LD_ROWS;
@@ -1594,7 +1601,7 @@ template <int ROWS> __global__ __launch_bounds__(256) void splitk_finish_kernel(
 SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups)
 {
     SplitPlan pl{1, K, 0};
-    const uint32_t mt = (uint32_t)pick_mt(M, N, groups);
+    const uint32_t mt = (uint32_t)pick_mt(M, N, groups, K);
     const uint64_t tiles = (uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups;
     if (tiles >= 512) return pl;
     uint64_t want = kSplitBlocks / tiles;
