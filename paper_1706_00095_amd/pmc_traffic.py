@@ -13,7 +13,8 @@ the library's per-launch profile uses, and the result is the mean over a label's
     python3 paper_1706_00095_amd/pmc_traffic.py --merge <step.json> <update_only.json> <out.json>
 
 joins the summary of a whole-step run with that of a `bench.py --update-only` run, whose
-reduce_sgd_kernel<K> entries become standalone_update_K<K> (the stand-alone eight-bucket launches).
+reduce_sgd_kernel<K> entries become standalone_update_K<K> (the stand-alone eight-bucket launches;
+<K,tree> entries standalone_update_K<K>_tree).
 """
 import collections
 import csv
@@ -44,6 +45,9 @@ def label(name):
         wm, wn, tm, tn = (int(m.group(i)) for i in (1, 2, 3, 4))
         code = {"KLoader4": "4", "KLoader": "k", "RowsLoader": "r"}
         return f"igemm_kernel<{wm * tm * 32}x{wn * tn * 32},{code[m.group(6)]}{code[m.group(9)]}{'c' if m.group(11) == 'true' else '-'}>"
+    m = re.match(r"cg::reduce_sgd_kernel<(\d+), (\w+)>", name)
+    if m:       # as the library's own launch log names it: <K> left to right, <K,tree> tree association
+        return f"reduce_sgd_kernel<{m.group(1)}{',tree' if m.group(2) == 'true' else ''}>"
     m = re.match(r"cg::(\w+)(<[^(]*>)?", name)
     if m:
         return m.group(1) + (m.group(2) or "").replace(" ", "")
@@ -64,9 +68,9 @@ def load(path):
 def merge(step_json, update_json, out_json):
     a, b = json.load(open(step_json)), json.load(open(update_json))
     for lab, v in b["kernels"].items():
-        m = re.match(r"reduce_sgd_kernel<(\d+)>", lab)
+        m = re.match(r"reduce_sgd_kernel<(\d+)(,tree)?>", lab)
         if m:
-            a["kernels"][f"standalone_update_K{m.group(1)}"] = v
+            a["kernels"][f"standalone_update_K{m.group(1)}{'_tree' if m.group(2) else ''}"] = v
     a["note"] = ("bytes per launch behind L2 (FETCH_SIZE / WRITE_SIZE scaled by a 256 MiB copy); in-step kernels from the "
                  "one-stream run, standalone_update_K* from bench.py --update-only; the .txt summaries beside this file "
                  "give the commands")
