@@ -220,6 +220,26 @@ def kernel_rooflines(agg, steps, traffic):
     return roofline, update, totals
 
 
+def per_layer_tflops(agg, layers):
+    """TFLOP/s of every convolution / FC layer's three passes (algorithmic FLOP of the pass's matrix-core
+    launches over their summed durations), keyed by layer name."""
+    names, nconv, nfc = {}, 0, 0
+    for i, ly in enumerate(layers):
+        if ly["kind"] == "conv":
+            nconv += 1; names[i] = f"conv{nconv}"
+        elif ly["kind"] == "fc":
+            nfc += 1; names[i] = f"fc{nfc + 5}"
+    acc = {}
+    for a in agg.values():
+        for key, p in a["passes"].items():
+            ps, li = key.split("@")
+            if int(li) not in names or not p["flops"]:
+                continue
+            e = acc.setdefault(names[int(li)], {}).setdefault(ps.split("_", 1)[1], [0.0, 0.0])
+            e[0] += p["flops"]; e[1] += p["ms"]
+    return {n: {ps: round(f / ms / 1e9, 1) for ps, (f, ms) in v.items()} for n, v in sorted(acc.items())}
+
+
 def kernel_table(agg, steps):
     log(f"{'kernel':34s} {'pass@layer':24s} {'launch/step':>11s} {'avg ms':>9s} {'TFLOP/s':>9s} {'GB/s':>9s}")
     for k, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
@@ -313,6 +333,7 @@ def main():
         cg.cg_profile_enable(False)
         agg1 = collect_profile(cg)
         roofline_excl, update_excl, totals_excl = kernel_rooflines(agg1, extra, traffic)
+        totals_excl["per_layer_tflops"] = per_layer_tflops(agg1, st["layers"])
         roofline_excl["measured"] = update_excl["measured"] = (
             f"HIP events around every launch of {extra} further iterations run right after the timed region with "
             "the one-stream schedule (CG_STEP_SERIAL: same kernels, same order, one at a time)")
