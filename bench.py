@@ -133,6 +133,19 @@ def grad_update_standalone(cg, torch, steps, warmup):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
         by = (4.0 * K + 20.0) * sum(sizes)
+        if K == 4 and not tag:
+            # bucket by bucket, one launch each: the five convolution buckets are bound by the launch
+            per = {}
+            for name, b in zip(cg_synth.ALEXNET_BUCKETS, bufs):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                cg.cg_grad_reduce_sgd(b["w"], b["v"], b["g"][0], b["g"][1:K + 1], b["n"], sgd)
+                e0.record()
+                for _ in range(steps):
+                    cg.cg_grad_reduce_sgd(b["w"], b["v"], b["g"][0], b["g"][1:K + 1], b["n"], sgd)
+                e1.record()
+                torch.cuda.synchronize()
+                per[name] = round((4.0 * K + 20.0) * b["n"] / (e0.elapsed_time(e1) / steps) / 1e6, 1)
+            out["per_bucket_gbps_K4"] = per
         out[f"K{K}{tag}"] = dict(gbps=by / ms / 1e6, ms_per_launch=ms, bytes=by, frac_of_peak=by / ms / 1e6 / PEAK_HBM_GBS,
                             launches_per_update=1, buckets=len(sizes))
     return out
@@ -356,6 +369,8 @@ def main():
     grad_update = None if args.skip_update_bench else grad_update_standalone(cg, torch, max(args.steps, 5), args.warmup)
     if grad_update:
         for k, v in grad_update.items():
+            if "bytes" not in v:
+                continue        # the per-bucket table
             t = traffic.get(f"standalone_update_{k}")
             v["traffic"] = (t["fetch_bytes"] + t["write_bytes"]) if t else None
 

@@ -1,12 +1,13 @@
 // One worker's SGD iteration with the turn-based, barrier-free schedule (section 2.3, Fig. 3).
 //
-// Two HIP streams.  The compute stream runs forward 1..L, the loss, and backward L..1.  As soon
-// as the local gradient of layer l is complete an event is recorded; the update stream waits
-// for it and runs that layer's (K+1)-buffer gradient sum + model update while the compute
-// stream continues with layer l-1 -- the paper's overlap of the reduction/update of one layer
-// with the gradient computation of the layers below it.  "Finalize" is per layer as well: the
-// next iteration's forward of layer l waits only on layer l's own update event, so there is no
-// device-wide synchronisation anywhere (design principle 2, section 2.2).
+// The compute stream runs forward 1..L, the loss, and backward L..1.  As soon as the local
+// gradient of layer l is complete an event is recorded; the update stream waits for it and runs
+// that layer's (K+1)-buffer gradient sum + model update while the compute stream continues with
+// layer l-1 -- the paper's overlap of the reduction/update of one layer with the gradient
+// computation of the layers below it.  "Finalize" is per layer as well: the next iteration's
+// forward of layer l waits only on the event of layer l's own update, so there is no device-wide
+// synchronisation anywhere (design principle 2, section 2.2).  Small layers share update launches
+// (and with them events): up to eight of them, or a million parameters, per launch.
 //
 // Within a layer's turn backward-data and backward-weight are independent and run side by side
 // (backward-weight on a third stream owned by the net); the update waits for both, because it
