@@ -196,7 +196,7 @@ int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local,
 /* Device workspace (activations, gradients of activations, kernel scratch). */
 size_t cg_net_workspace_bytes(const cg_net *net);
 
-enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2 };
+enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2, CG_STEP_TREE_SUM = 4 };
 
 /* One SGD iteration of this worker (Fig. 1 with the turn-based schedule of
  * Fig. 3): forward through layers 1..L, loss, then for l = L..1 the local
@@ -213,6 +213,9 @@ enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2 };
  * The loss and the local gradients are valid in compute_stream order, the
  * updated w and v in update_stream order.
  * The two streams must differ unless CG_STEP_SERIAL is given.
+ *  CG_STEP_TREE_SUM: the K+1 gradients of every layer are added in the
+ *  association of the binomial reduction tree (cg_grad_reduce_sgd_tree) instead
+ *  of left to right.
  *  CG_STEP_JOIN (with the overlapped schedule): at the end of the call
  *  compute_stream also waits for the last update, so that every stream the call
  *  used has joined compute_stream and the next call depends on no event of this

@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("CG_LIB_PATH", os.path.join(_HERE, "libcg.so"))
 
 CG_OK, CG_EINVAL, CG_ENOSPC, CG_EUNSUPPORTED, CG_EHIP = 0, -1, -2, -3, -4
 CG_PASS_FWD, CG_PASS_BWD_DATA, CG_PASS_BWD_WEIGHT = 0, 1, 2
-CG_STEP_OVERLAP, CG_STEP_SERIAL, CG_STEP_JOIN = 0, 1, 2
+CG_STEP_OVERLAP, CG_STEP_SERIAL, CG_STEP_JOIN, CG_STEP_TREE_SUM = 0, 1, 2, 4
 CG_MAX_PEERS = 64
 LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc": 5, "dropout": 6,
                "concat": 7, "softmax_ce": 8}

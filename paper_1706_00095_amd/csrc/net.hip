@@ -445,7 +445,8 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             Layer &l = net->layers[pend[k]];
             w[k] = l.w; v[k] = l.v; g[k] = l.g; peers[k] = l.peers.data(); n[k] = (size_t)l.n_params;
         }
-        const int rcu = grad_reduce_sgd_multi_impl(nb, w, v, g, peers, (int)last.peers.size(), n, *sgd, S1);
+        const int rcu = grad_reduce_sgd_multi_impl(nb, w, v, g, peers, (int)last.peers.size(), n, *sgd, S1,
+                                                   (flags & CG_STEP_TREE_SUM) != 0);
         if (rcu) return rcu;
         if (!serial) {
             CG_HIP_TRY(hipEventRecord(last.ev_upd, S1));

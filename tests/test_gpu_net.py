@@ -128,6 +128,26 @@ def test_joined_step_recorded_into_a_hip_graph_replays_bit_identically(name):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("flags", [cg.CG_STEP_TREE_SUM, cg.CG_STEP_TREE_SUM | cg.CG_STEP_SERIAL])
+def test_step_with_tree_ordered_gradient_sum(orc32, flags):
+    """CG_STEP_TREE_SUM: every layer's update is the tree-order oracle's, bit for bit, on the local
+    gradient the step produced (K = 8 peers, where the two associations differ); the local
+    gradients themselves are those of the plain step."""
+    layers, in_shape, B, t = _build("inception")
+    a, b = GpuNet(layers, in_shape, B, t), GpuNet(layers, in_shape, B, t)
+    a.step(SGD, flags)
+    b.step(SGD, flags & cg.CG_STEP_SERIAL)
+    a.sync(); b.sync()
+    differs = False
+    for li in a.w:
+        assert torch.equal(a.g[li], b.g[li])
+        w, v = t["buckets"][li].copy(), np.zeros_like(t["buckets"][li])
+        orc32.grad_reduce_sgd(w, v, host(a.g[li]), t["peers"][li], *SGD, order="tree")
+        assert host(a.w[li]).tobytes() == w.tobytes() and host(a.v[li]).tobytes() == v.tobytes(), li
+        differs = differs or not torch.equal(a.v[li], b.v[li])
+    assert differs
+
+
 def test_loss_decreases_over_iterations_on_fixed_batch():
     layers, in_shape, B, t = _build("tiny_cnn_cfg1")
     for li in t["peers"]:
