@@ -1243,6 +1243,10 @@ int patch_launch_tiles(const IgemmProblem &p, int mt, hipStream_t stream)
         if (mt == 128) return launch_patch_cfg<2, 4, 4>(p, stream);
         return launch_patch_cfg<1, 4, 4>(p, stream);
     }
+    if (p.patch.nsl == 6) {      // 2 x 50 KB of patch buffers: no 192-row tile beside them
+        if (mt >= 128) return launch_patch_cfg<2, 3, 6>(p, stream);
+        return launch_patch_cfg<1, 4, 6>(p, stream);
+    }
     if (mt == 192) return launch_patch_cfg<3, 3, 5>(p, stream);
     if (mt == 128) return launch_patch_cfg<2, 4, 5>(p, stream);
     return launch_patch_cfg<1, 4, 5>(p, stream);
@@ -1258,7 +1262,8 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
         return tm == 3 ? launch_patch16_cfg<3, 4, 5>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 5>(p, stream)
                                                                           : launch_patch16_cfg<1, 4, 5>(p, stream);
     }
-    const int mt = patch_mt(p.M, p.N, p.groups);
+    int mt = patch_mt(p.M, p.N, p.groups);
+    if (p.patch.nsl == 6 && mt > 128) mt = 128;
     // Two blocks are resident per compute unit, so blocks run in rounds of g_resident_blocks that
     // start and end together.  When the last round would be less than three quarters full, the
     // pixel tiles of the whole rounds go out as one launch and the rest as a second launch of
@@ -1426,8 +1431,10 @@ bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
         const int64_t sl = slots(n0, (n0 + 127 < P - 1) ? n0 + 127 : P - 1);
         if (sl > amax) amax = sl;
     }
-    if (amax > 5 * 64) return false;
-    g.nsl = 5;
+    // six chunks (planes 56 wide with a 3x3 window: four pixel rows, 348 slots) leave room for 128-row
+    // tiles with a three-stage filter ring; the 16-row-tile kernel has no such instance
+    if (amax > 6 * 64 || (amax > 5 * 64 && M <= 48)) return false;
+    g.nsl = amax > 5 * 64 ? 6 : 5;
     g.tiles_per_img = (int32_t)((P + 127) / 128);
     g.divTpi = make_fastdiv((uint32_t)g.tiles_per_img);
     return true;

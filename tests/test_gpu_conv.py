@@ -181,6 +181,27 @@ def test_patch_kernel_two_launches(orc32, patch_path, B, M, groups, resident):
     assert max_abs_rel(got, ref) <= TOL
 
 
+@pytest.mark.parametrize("B,C,M,W", [(2, 16, 64, 56), (1, 64, 160, 56), (2, 32, 128, 52)])
+def test_patch_kernel_six_chunks(orc32, patch_path, B, C, M, W):
+    """Planes 56 (52) wide with a 3x3 window: the 128 pixels of a block span four pixel rows, 348 (324)
+    patch slots a channel, which take the six-chunk instances (64- and 128-row tiles) in forward and,
+    where the group has more than 48 input channels, in backward-data."""
+    cfg = dict(C=C, H=56, W=W, M=M, k=3, stride=1, pad=1, groups=1)
+    c, x, w, b, dy = cg_synth.conv_layer_tensors("six_chunks", B, seed=B * 100 + M, cfg=cfg)
+    d = cg.conv_desc(B, C, 56, W, M, 3, stride=1, pad=1, groups=1)
+    od = odesc(B, C, 56, W, M, 3, 1, 1, 1)
+    cg.cg_profile_enable(True)
+    try:
+        y = host(conv_fwd(d, dev(x), dev(w), dev(b)))
+        dx = host(conv_bwd_data(d, dev(dy), dev(w)))
+        names = [cg.cg_profile_get(i)["kernel"] for i in range(cg.cg_profile_count())]
+    finally:
+        cg.cg_profile_enable(False)
+    assert len([n for n in names if n.startswith("igemm_patch_kernel") and n.endswith(",6>")]) == (2 if C > 48 else 1), names
+    assert max_abs_rel(y, orc32.conv_fwd(od, x, w, b)) <= TOL
+    assert max_abs_rel(dx, orc32.conv_bwd_data(od, dy, w)) <= TOL
+
+
 def test_patch_and_gather_kernels_agree(orc32):
     """The same forward convolution through both kernels: equal up to summation order."""
     d, od, x, w, b, dy = _setup_patch("p3x3_13_c32_m128")
