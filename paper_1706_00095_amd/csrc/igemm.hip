@@ -1263,7 +1263,8 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
                                                                           : launch_patch16_cfg<1, 4, 5>(p, stream);
     }
     int mt = patch_mt(p.M, p.N, p.groups);
-    if (p.patch.nsl == 6 && mt > 128) mt = 128;
+    // six chunks: no 192-row instance; 128-row tiles unless they would pad the rows by half a tile or more
+    if (p.patch.nsl == 6 && mt > 64) mt = (p.M + 127) / 128 * 128 - p.M >= 64 ? 64 : 128;
     // Two blocks are resident per compute unit, so blocks run in rounds of g_resident_blocks that
     // start and end together.  When the last round would be less than three quarters full, the
     // pixel tiles of the whole rounds go out as one launch and the rest as a second launch of
