@@ -238,3 +238,24 @@ def test_tree_exact_inputs_give_the_exact_sum(orc32, K):
     bufs = [(rng.integers(-2048, 2048, 4096) / 1024.0).astype(F32) for _ in range(K + 1)]
     exact = np.sum(np.stack(bufs).astype(np.float64), 0)
     assert np.array_equal(_tree_sum_oracle(orc32, bufs).astype(np.float64), exact)
+
+
+def test_tree_rounding_cases_from_the_fixture(orc32):
+    """tests/golden/tree_sum_rounding.txt: sums worked by hand, tree order and left to right."""
+    import os
+    u = F32(2.0 ** -23)
+    path = os.path.join(os.path.dirname(__file__), "golden", "tree_sum_rounding.txt")
+    cases = 0
+    for line in open(path):
+        if not line.startswith("ranks"):
+            continue
+        tok = line.split()
+        vals = tok[1:tok.index("tree")]
+        tree, seq = float(tok[tok.index("tree") + 1]), float(tok[tok.index("seq") + 1])
+        bufs = [np.full(3, F32(1) if v == "1" and i == 0 else F32(float(v)) * u, F32) for i, v in enumerate(vals)]
+        assert np.all(_tree_sum_oracle(orc32, bufs) == F32(1) + F32(tree) * u), line
+        w, v = np.zeros(3, F32), np.zeros(3, F32)
+        orc32.grad_reduce_sgd(w, v, bufs[0], bufs[1:], 1.0, 0.0, 0.0)
+        assert np.all(v == F32(1) + F32(seq) * u), line
+        cases += 1
+    assert cases == 5
