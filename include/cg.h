@@ -276,8 +276,9 @@ int cg_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
  * implicit-GEMM view of a convolution pass reads for operand A (0) or B (1) at
  * (row, k) of the given group.  elem_offset is in floats from the tensor's base
  * (forward: A = w, B = x; backward-data, stride 1 only: A = the group-wise
- * transposed filter copy [g][c][m][kh][kw], B = dy; backward-weight: A = dy,
- * B = x); valid = 0 means the element is a zero-padding tap. */
+ * transposed filter copy [g][c][m][kh][kw], or w itself for a 1x1 window
+ * without padding, B = dy; backward-weight: A = dy, B = x); valid = 0 means the
+ * element is a zero-padding tap. */
 int cg_debug_conv_operand(const cg_conv_desc *d, int pass, int operand, unsigned row, unsigned k,
                           unsigned group, long long *elem_offset, int *valid);
 

@@ -341,6 +341,14 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
     return igemm_run(p, ws, ws_bytes, stream);
 }
 
+// A 1x1 window without padding at stride 1: backward-data is the plain product of the transposed
+// filter matrix with dy, and the transposed matrix can be read from w with the loader that runs the
+// row index along the lanes (as the fully-connected layers do), so no transposed copy is made.
+static bool bwd_data_reads_filters_in_place(const cg_conv_desc &d)
+{
+    return d.KH == 1 && d.KW == 1 && d.pad_h == 0 && d.pad_w == 0 && d.stride_h == 1 && d.stride_w == 1;
+}
+
 static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, const float *dy, const float *wt,
                                      float *dx, int accumulate)
 {
@@ -354,6 +362,12 @@ static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, cons
     p.A.gstride = (int64_t)Cg * Kp;
     p.A.elems = (uint64_t)d.M * Cg * KK;
     p.A.lanes_k = 1;
+    if (bwd_data_reads_filters_in_place(d)) {
+        // one tap: A(c, m) is w[m][c] itself, rows (input channels) along the lanes -- `wt` is then w
+        p.A.row = linear_map(Cg, 1);
+        p.A.k = linear_map(Mg, Cg);
+        p.A.lanes_k = 0;
+    }
     // dy seen from an input pixel (n, ih, iw): origin (ih + p, iw + p), taps subtract (kh, kw)
     p.B.ptr = dy;
     IndexMap pix{};
@@ -445,13 +459,14 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
             return igemm_run(pp, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
         }
     }
-    {
+    const bool in_place = bwd_data_reads_filters_in_place(d);
+    if (!in_place) {
         const size_t total = (size_t)d.M * Cg * KK;
         const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
         hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
         CG_HIP_TRY(hipGetLastError());
     }
-    IgemmProblem p = bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate);
+    IgemmProblem p = bwd_data_problem(d, OH, OW, dy, in_place ? w : wt, dx, accumulate);
     p.gate = gate;
     return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
 }
