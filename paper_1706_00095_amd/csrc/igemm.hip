@@ -70,13 +70,26 @@ __device__ __forceinline__ void load_to_lds(BufferRsrc rsrc, const float *lds, u
                  ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff))
                  : "memory", "m0");
 }
-// 64 lanes x 16 bytes: lane l's four elements land at lds + 16*l.
-__device__ __forceinline__ void load4_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff, uint32_t soff)
+// The same without a scalar offset: no scalar register a vector instruction may just have written is
+// read, and the one wait state M0 needs is enough.  A load with its set-up costs the matrix pipeline
+// about 6 % of a four-MFMA step with four wait states and 4 % with one (measured on a loop of MFMAs).
+__device__ __forceinline__ void load_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff)
 {
     const uint32_t lds_addr = (uint32_t)(size_t)(const lds_float *)lds;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff))
-                 : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 ::"s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+}
+// 64 lanes x 16 bytes: lane l's four elements land at lds + 16*l.
+template <int WS = 1>
+__device__ __forceinline__ void load4_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff)
+{
+    const uint32_t lds_addr = (uint32_t)(size_t)(const lds_float *)lds;
+    if constexpr (WS == 1)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     ::"s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     ::"s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
 }
 #pragma clang diagnostic pop
 
@@ -185,7 +198,7 @@ template <int R, bool CHECK> struct KLoader {
                 const bool ok = (uint32_t)(ra[j] + kq.a) < op.limA && (uint32_t)(rb[j] + kq.b) < op.limB;
                 voff = ok ? voff : OOB_ROW;
             }
-            load_to_lds(rsrc, stage + (wave * NJ + j) * GS, voff, 0u);
+            load_to_lds(rsrc, stage + (wave * NJ + j) * GS, voff);
         }
     }
     __device__ __forceinline__ static void frag(const float *stage, int row, int ks, int h, float out[4])
@@ -203,7 +216,7 @@ template <int R, bool CHECK> struct KLoader {
 // only 4-byte alignment, and the range check is per float: a quad that reaches beyond K, a run or
 // the tensor delivers the floats that exist and zeros (or the neighbouring row's values) for the
 // rest, which meet zeros of operand B.
-template <int R> struct KLoader4 {
+template <int R, int WS = 1> struct KLoader4 {       // WS: wait states behind the M0 set-up of a load (1 or 4)
     static constexpr int NJ = (R + 63) / 64;     // load instructions per tile and wave
     static constexpr int SZ = 4 * NJ * 256;      // rows beyond R are loaded as zeros
     static constexpr int LPT = NJ;
@@ -234,7 +247,7 @@ template <int R> struct KLoader4 {
         }
 #pragma unroll
         for (int j = P * LPT / NPART; j < (P + 1) * LPT / NPART; ++j)
-            load4_to_lds(rsrc, stage + (wave * NJ + j) * 256, roff[j] + koff, 0u);
+            load4_to_lds<WS>(rsrc, stage + (wave * NJ + j) * 256, roff[j] + koff);
     }
     __device__ __forceinline__ static void frag(const float *stage, int row, int ks, int h, float out[4])
     {
@@ -485,7 +498,7 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
 {
     static_assert(WM * WN == 4 && WN * TN == 4, "four waves, 128 pixels per block");
     constexpr int MT = WM * TM * 32, NT = 128;
-    using LA = KLoader4<MT>;
+    using LA = KLoader4<MT, 4>;
     using PB = PatchB<NSL>;
     constexpr int LAW = LA::LPT, NB = PB::NB;
     static_assert((NSTA - 1) * LAW + NB <= 63, "the vector-memory counter holds 63 loads");
@@ -662,7 +675,7 @@ template <int TM, int NSTA, int NSL>
 __global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProblem p)
 {
     constexpr int MT = TM * 16, NT = 128, TN = 2;
-    using LA = KLoader4<MT>;
+    using LA = KLoader4<MT, 4>;
     using PB = PatchB<NSL, 4>;
     constexpr int LAW = LA::LPT, NB = PB::NB;
     static_assert(TM >= 1 && TM <= 3 && LA::NJ == 1, "at most 48 rows: one A load per wave and K-tile");
@@ -958,7 +971,7 @@ __global__ __launch_bounds__(256, 2) void igemm_wgrad_kernel(const IgemmProblem 
         }
 #pragma unroll
         for (int j = Pn * LAW / NPART; j < (Pn + 1) * LAW / NPART; ++j)
-            load4_to_lds(rsrcA, smem + (tile % NSTA) * LA::SZ + (wave * LA::NJ + j) * 256, la.roff[j] + la.koff, 0u);
+            load4_to_lds(rsrcA, smem + (tile % NSTA) * LA::SZ + (wave * LA::NJ + j) * 256, la.roff[j] + la.koff);
     };
     auto tiles_of = [&](int u) {
         int img, oy0, rows;
@@ -1178,7 +1191,7 @@ template <int TM, int NSTA, int NSL>
 int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
 {
     constexpr int MT = 2 * TM * 32;
-    using LA = KLoader4<MT>;
+    using LA = KLoader4<MT, 4>;
     dim3 grid(p.patch.tile_count ? p.patch.tile_count : patch_pixel_tiles(p), (p.M + MT - 1) / MT, p.groups);
     if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
     int rec = -1;
@@ -1206,7 +1219,7 @@ template <int TM, int NSTA, int NSL>
 int launch_patch16_cfg(const IgemmProblem &p, hipStream_t stream)
 {
     constexpr int MT = TM * 16;
-    using LA = KLoader4<MT>;
+    using LA = KLoader4<MT, 4>;
     dim3 grid(p.patch.tile_count ? p.patch.tile_count : patch_pixel_tiles(p), (p.M + MT - 1) / MT, p.groups);
     if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
     int rec = -1;
