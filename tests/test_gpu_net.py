@@ -148,6 +148,21 @@ def test_step_with_tree_ordered_gradient_sum(orc32, flags):
     assert differs
 
 
+@pytest.mark.parametrize("name", ["alexnet_like", "inception"])
+def test_schedules_mixed_from_call_to_call_agree_with_the_serial_one(name):
+    """Overlapped, joined and one-stream calls in any succession: each call waits for exactly what
+    the call before left pending, so five mixed iterations give the bits of five serial ones."""
+    layers, in_shape, B, t = _build(name)
+    a, b = GpuNet(layers, in_shape, B, t), GpuNet(layers, in_shape, B, t)
+    for flags in (cg.CG_STEP_OVERLAP, cg.CG_STEP_JOIN, cg.CG_STEP_SERIAL, cg.CG_STEP_OVERLAP, cg.CG_STEP_JOIN):
+        a.step(SGD, flags)
+        b.step(SGD, cg.CG_STEP_SERIAL)
+    a.sync(); b.sync()
+    assert torch.equal(a.loss[:1], b.loss[:1])
+    for li in a.w:
+        assert torch.equal(a.w[li], b.w[li]) and torch.equal(a.v[li], b.v[li]) and torch.equal(a.g[li], b.g[li])
+
+
 def test_loss_decreases_over_iterations_on_fixed_batch():
     layers, in_shape, B, t = _build("tiny_cnn_cfg1")
     for li in t["peers"]:
