@@ -13,5 +13,5 @@ shapes stand in for the images.
 """
 from .workloads import (  # noqa: F401
     ALEXNET_CONVS, ALEXNET_BUCKETS, alexnet_layers, tiny_cnn_layers, inception_layers, googlenet_layers,
-    infer_shapes, param_layers, conv_layer_tensors, net_tensors, sgd_buckets, xavier_uniform,
+    infer_shapes, param_layers, conv_layer_tensors, conv_layer_int_tensors, net_tensors, sgd_buckets, xavier_uniform,
 )

@@ -233,10 +233,31 @@ def conv_layer_tensors(name, B, seed, cfg=None):
     return c, x, w, bias, dy
 
 
-def net_tensors(layers, in_shape, B, K, seed, num_classes, init="fan_in", peer_std=1e-3):
+def conv_layer_int_tensors(cfg, B, seed, lim=3):
+    """Small-integer tensors for one convolution layer: x, w, bias, dy uniform on the integers
+    -lim..lim, stored as float32.  Every product and every partial sum of up to 2^24 / lim^2 terms is
+    then an integer that fp32 represents exactly, so any summation order gives the same bits.
+    Returns (cfg, x, w, bias, dy)."""
+    c = dict(cfg)
+    rng = np.random.default_rng(seed)
+    Cg = c["C"] // c["groups"]
+    W_ = c.get("W", c["H"])
+    OH = (c["H"] + 2 * c["pad"] - c["k"]) // c["stride"] + 1
+    OW = (W_ + 2 * c["pad"] - c["k"]) // c["stride"] + 1
+
+    def draw(shape):
+        return rng.integers(-lim, lim + 1, size=shape).astype(np.float32)
+
+    return (c, draw((B, c["C"], c["H"], W_)), draw((c["M"], Cg, c["k"], c["k"])), draw((c["M"],)),
+            draw((B, c["M"], OH, OW)))
+
+
+def net_tensors(layers, in_shape, B, K, seed, num_classes, init="fan_in", peer_std=1e-3, bias_std=0.1):
     """Inputs of one training iteration: x ~ N(0,1), labels uniform, one parameter bucket
     (weights then bias, contiguous) per conv/fc layer, zero history, K peer gradient
-    buckets ~ N(0, peer_std) per layer, Bernoulli(1-p) keep masks for dropout layers."""
+    buckets ~ N(0, peer_std) per layer, Bernoulli(1-p) keep masks for dropout layers.
+    Biases ~ N(0, bias_std): a model in the middle of training has non-zero biases, and with zeros the
+    per-row and per-column bias paths of the kernels would add nothing that a test could see."""
     rng = np.random.default_rng(seed)
     x = rng.standard_normal((B,) + tuple(in_shape), dtype=np.float32)
     labels = rng.integers(0, num_classes, size=B).astype(np.int32)
@@ -245,11 +266,10 @@ def net_tensors(layers, in_shape, B, K, seed, num_classes, init="fan_in", peer_s
     for li, wshape, nb in param_layers(layers, in_shape):
         if init == "xavier":
             w = xavier_uniform(rng, wshape)
-            b = np.zeros(nb, np.float32)
         else:
             fan_in = int(np.prod(wshape[1:]))
             w = rng.standard_normal(wshape, dtype=np.float32) / np.float32(math.sqrt(fan_in))
-            b = np.zeros(nb, np.float32)
+        b = rng.standard_normal(nb, dtype=np.float32) * np.float32(bias_std)
         buckets[li] = np.concatenate([w.ravel(), b]).astype(np.float32)
         peers[li] = [(rng.standard_normal(buckets[li].size, dtype=np.float32) * np.float32(peer_std))
                      for _ in range(K)]

@@ -87,8 +87,9 @@ def test_zero_classifier_gives_log_num_classes(orc32):
 
 
 def test_xavier_init_loss_is_near_log10(orc32):
+    """Xavier-uniform weights with zero biases (a freshly initialised model): small logits."""
     layers, in_shape = cg_synth.tiny_cnn_layers()
-    t = cg_synth.net_tensors(layers, in_shape, 8, 4, seed=0, num_classes=10, init="xavier", peer_std=1e-2)
+    t = cg_synth.net_tensors(layers, in_shape, 8, 4, seed=0, num_classes=10, init="xavier", peer_std=1e-2, bias_std=0.0)
     loss = onet.loss_only(orc32, layers, t["x"], t["labels"], t["buckets"], t["masks"])
     assert abs(float(loss) - math.log(10.0)) < 0.3
 
