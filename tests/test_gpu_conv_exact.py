@@ -102,7 +102,9 @@ def patch_path():
 def test_patch_kernels_exact(orc32, patch_path, name):
     B, cfg = PATCH_SHAPES[name]
     d, names = _all_three(orc32, B, cfg, seed=sum(map(ord, name)), bwd_data=cfg["stride"] == 1, bwd_weight=False)
-    assert names and all(n.startswith("igemm_patch") for n in names), names
+    # forward always; backward-data where the output channels of a group (its reduction) come in blocks of 16
+    expect = 1 + (1 if cfg["stride"] == 1 and (cfg["M"] // cfg["groups"]) % 16 == 0 else 0)
+    assert len([n for n in names if n.startswith("igemm_patch")]) == expect, names
     if cfg["M"] <= 48:
         assert any(n.startswith("igemm_patch16_kernel") for n in names), names
 
@@ -133,7 +135,9 @@ def test_band_kernel_exact(orc32, name):
         d, names = _all_three(orc32, B, cfg, seed=sum(map(ord, name)), fwd=False, bwd_data=False)
     finally:
         cg.cg_debug_band_kernel(False)
-    assert names and all(n.startswith("igemm_wgrad_kernel") for n in names), names
+    # one shape's last band of rows is shorter than the band kernel's pipeline needs: the gathered kernel takes it
+    family = "igemm_kernel" if name == "b3x3_s2_p1" else "igemm_wgrad_kernel"
+    assert names and all(n.startswith(family) for n in names), names
 
 
 @pytest.mark.parametrize("B,IN,OUT", [(5, 37, 11), (64, 256, 1000), (130, 513, 70)])
