@@ -88,6 +88,21 @@ int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w,
 int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const float *dy,
                        float *dw, float *dbias, void *ws, size_t ws_bytes, void *stream);
 
+/* cg_conv_bwd_weight for callers that can hand over no workspace and may not
+ * allocate one: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  The partial sums of the pass live in a device array
+ * of CG_NOALLOC_SCRATCH_BYTES that belongs to the library (one copy per GPU,
+ * held from the moment the library is loaded until the process ends); the call
+ * allocates and frees nothing.  Results are bit-identical to cg_conv_bwd_weight.
+ * Returns CG_ENOSPC, launching nothing, if the descriptor needs more than that
+ * (cg_conv_workspace_bytes(d, CG_PASS_BWD_WEIGHT) tells).  All calls on one GPU
+ * share the array: calls that overlap on one GPU (two streams, two threads)
+ * race and must be serialised by the caller.  The device current at the call
+ * must be the one the tensors live on. */
+#define CG_NOALLOC_SCRATCH_BYTES (64u << 20)
+int cg_conv_bwd_weight_noalloc(const cg_conv_desc *d, const float *x, const float *dy,
+                               float *dw, float *dbias, void *stream);
+
 /* Gradient aggregation over s = K+1 ranks fused with the model update of one
  * layer (Eq. 1; "reduced (added to) with its own gradient data", section 3.2;
  * update on the reduced gradient, section 3.2 first paragraph).  Per element

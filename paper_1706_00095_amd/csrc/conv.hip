@@ -5,6 +5,7 @@
 // Backward-weight:  dW[m][(c,kh,kw)]  = sum_{(n,oh,ow)} dY[m][(n,oh,ow)] * X(n,c,oh*s-p+kh,ow*s-p+kw)
 // (section 2.1: forward propagation, backward propagation, gradient on the weights; the last
 // one is the "compute local gradient" step of every turn in Fig. 3).
+#include <mutex>
 #include "cg_internal.h"
 
 namespace cg {
@@ -732,4 +733,53 @@ extern "C" int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const f
     if (!d || !x || !dy || !dw) return CG_EINVAL;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CG_EINVAL;
     return conv_bwd_weight_impl(*d, x, dy, dw, dbias, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---- backward-weight without a caller's workspace ------------------------------------------------
+//
+// The partial sums of the K slices and of the bias gradient live in a device array that is part of
+// the library's code object: every GPU the library runs on holds its own copy, at its own address,
+// from the moment the module is loaded until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the address that call returns for the current device is
+// what the kernels are given.  Nothing has to start at zero: the matrix kernel writes every partial
+// sum the finishing kernels read.  All calls on one GPU share the array, so two calls that overlap
+// on that GPU (different streams, or threads) race.
+static __device__ __align__(256) unsigned char scratch[CG_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];       // per device, filled on the first call with that device current
+
+int scratch_for_current_device(void **out)
+{
+    int dev = -1;
+    CG_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CG_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        CG_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || !aligned16(ptr)) return CG_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CG_OK;
+}
+}  // namespace
+
+extern "C" int cg_conv_bwd_weight_noalloc(const cg_conv_desc *d, const float *x, const float *dy, float *dw,
+                                          float *dbias, void *stream)
+{
+    if (!d || !x || !dy || !dw) return CG_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CG_EINVAL;
+    int OH, OW;
+    const int rc = conv_check(d, &OH, &OW);
+    if (rc) return rc;
+    if (conv_ws_bytes(*d, CG_PASS_BWD_WEIGHT) > (size_t)CG_NOALLOC_SCRATCH_BYTES) return CG_ENOSPC;
+    void *ptr = nullptr;
+    const int rs = scratch_for_current_device(&ptr);
+    if (rs) return rs;
+    return conv_bwd_weight_impl(*d, x, dy, dw, dbias, ptr, (size_t)CG_NOALLOC_SCRATCH_BYTES,
+                                static_cast<hipStream_t>(stream));
 }
