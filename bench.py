@@ -98,7 +98,73 @@ def collect_profile(cg):
     return agg
 
 
-def grad_update_standalone(cg, torch, steps, warmup):
+def hbm_achievable(cg, torch, reps=20):
+    """What the memory system reaches with the simplest streaming kernels (one float4 per thread, all
+    accesses non-temporal) on arrays of the eight buckets' total size: the measured ceilings to read
+    the update kernel's fraction of the published 8 TB/s against."""
+    n = 60965224 // 4 * 4
+    bufs = [torch.zeros(n, device="cuda") for _ in range(6)]
+    out = {}
+    for name, mode, nbytes in (("read", 1, 4 * n), ("fill", 2, 4 * n), ("copy", 0, 8 * n), ("triad", 3, 12 * n)):
+        def one(i):
+            a, b, c = bufs[(3 * i) % 6], bufs[(3 * i + 1) % 6], bufs[(3 * i + 2) % 6]
+            cg.cg_debug_stream(a, b, c, 4 * n, mode)
+        for i in range(3):
+            one(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            one(i)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_gbps"] = round(nbytes / (e0.elapsed_time(e1) / reps) / 1e6, 1)
+    out["what"] = ("244 MB arrays, one float4 per thread, non-temporal loads and stores, launches back to back between "
+                   "two events; bytes counted once per array read or written")
+    return out
+
+
+def conv_layers_standalone(cg, torch, B, reps=10):
+    """Configuration 2: every AlexNet-shaped convolution layer alone, forward / backward-data /
+    backward-weight through the C ABI (the first layer's backward-data included, which a net skips),
+    TFLOP/s of useful work 2*M*N*K*groups over the mean of `reps` back-to-back calls."""
+    import cg_synth
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    out = {}
+    for name, c in cg_synth.ALEXNET_CONVS.items():
+        d = cg.conv_desc(B, c["C"], c["H"], c["H"], c["M"], c["k"], stride=c["stride"], pad=c["pad"], groups=c["groups"])
+        OH, OW = cg.cg_conv_out_shape(d)
+        Cg = c["C"] // c["groups"]
+        fan = Cg * c["k"] ** 2
+        x = torch.randn((B, c["C"], c["H"], c["H"]), device="cuda", generator=gen) * fan ** -0.5
+        w = torch.randn((c["M"], Cg, c["k"], c["k"]), device="cuda", generator=gen) * fan ** -0.5
+        b = torch.randn(c["M"], device="cuda", generator=gen) * 0.1
+        dy = torch.randn((B, c["M"], OH, OW), device="cuda", generator=gen) * fan ** -0.5
+        y, dx, dw, db = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w), torch.empty_like(b)
+        ws = [torch.empty(max(cg.cg_conv_workspace_bytes(d, p), 16), dtype=torch.uint8, device="cuda") for p in range(3)]
+        flop = 2.0 * c["M"] * Cg * c["k"] ** 2 * B * OH * OW
+        calls = {"fwd": lambda: cg.cg_conv_fwd(d, x, w, b, y, ws[0]),
+                 "bwd_data": lambda: cg.cg_conv_bwd_data(d, dy, w, dx, ws[1]),
+                 "bwd_weight": lambda: cg.cg_conv_bwd_weight(d, x, dy, dw, db, ws[2])}
+        res = {}
+        for ps, fn in calls.items():
+            fn(); fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            res[ps] = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1)}
+        out[name] = res
+    out["what"] = (f"B={B}, each pass alone on the GPU through cg_conv_fwd / cg_conv_bwd_data / cg_conv_bwd_weight (filter "
+                   "permutation, K-slice sums and bias gradient included in the time), useful FLOP = 2*M*N*K*groups")
+    return out
+
+
+def grad_update_standalone(cg, torch, steps, warmup, per_bucket=True):
     """Configuration 3: the eight AlexNet parameter buckets, K in {4, 8, 16}; GB/s of
     algorithmic traffic (4K+20 bytes per parameter) over the kernels' own durations."""
     import cg_synth
@@ -124,16 +190,21 @@ def grad_update_standalone(cg, torch, steps, warmup):
         torch.cuda.synchronize()
         # `steps` launches back to back between two events on the launch stream: the per-launch time
         # includes the gaps between launches but not the event markers' own latency, which at a few
-        # hundred microseconds per launch would otherwise cost several percent
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            one()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+        # hundred microseconds per launch would otherwise cost several percent.  Five such rounds, the
+        # median reported and all five listed: early in a process a round now and then runs at half speed
+        # (seen on any K, never in a sustained run of seconds), which says nothing about the kernel.
+        rounds = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                one()
+            e1.record()
+            torch.cuda.synchronize()
+            rounds.append(e0.elapsed_time(e1) / steps)
+        ms = sorted(rounds)[len(rounds) // 2]
         by = (4.0 * K + 20.0) * sum(sizes)
-        if K == 4 and not tag:
+        if K == 4 and not tag and per_bucket:
             # bucket by bucket, one launch each: the five convolution buckets are bound by the launch
             per = {}
             for name, b in zip(cg_synth.ALEXNET_BUCKETS, bufs):
@@ -147,7 +218,8 @@ def grad_update_standalone(cg, torch, steps, warmup):
                 per[name] = round((4.0 * K + 20.0) * b["n"] / (e0.elapsed_time(e1) / steps) / 1e6, 1)
             out["per_bucket_gbps_K4"] = per
         out[f"K{K}{tag}"] = dict(gbps=by / ms / 1e6, ms_per_launch=ms, bytes=by, frac_of_peak=by / ms / 1e6 / PEAK_HBM_GBS,
-                            launches_per_update=1, buckets=len(sizes))
+                            launches_per_update=1, buckets=len(sizes), launches_per_round=steps,
+                            rounds_ms=[round(r, 4) for r in rounds])
     return out
 
 
@@ -191,8 +263,7 @@ def cpu_baseline(sample_B, K):
     onet.train_step(orc, layers, t["x"], t["labels"], t["buckets"], hist, t["peers"], t["masks"], 0.01, 0.9, 5e-4)
     dt = time.perf_counter() - t0
     return dict(value=sample_B / dt, unit="images/s", cores=orc.num_threads(), kind="oracle",
-                sample=f"same AlexNet-shaped net and K={K}, one whole iteration at B={sample_B} "
-                       f"({dt:.1f} s of CPU time; time scales linearly in B except the update)")
+                sample=f"same AlexNet-shaped net and K={K}, one whole iteration at B={sample_B} ({dt:.1f} s of CPU time)")
 
 
 def load_traffic():
@@ -264,11 +335,12 @@ def kernel_table(agg, steps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--peers", type=int, default=4)
-    ap.add_argument("--cpu-sample", type=int, default=64, help="images in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="images in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--skip-layer-bench", action="store_true", help="leave out the stand-alone per-layer and B=64 figures")
     ap.add_argument("--serial", action="store_true", help="one-stream schedule (no overlap) in the timed region")
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--skip-update-bench", action="store_true", help="leave out the stand-alone update benchmark")
@@ -300,7 +372,9 @@ def main():
     torch.cuda.synchronize()
     del cal
     if args.update_only:
-        print(json.dumps({"grad_update": grad_update_standalone(cg, torch, max(args.steps, 1), args.warmup)}), flush=True)
+        # the eight-bucket launches only, so that a profiler's per-kernel means are means over one launch shape
+        print(json.dumps({"grad_update": grad_update_standalone(cg, torch, max(args.steps, 1), args.warmup, per_bucket=False),
+                          "hbm_achievable": hbm_achievable(cg, torch)}), flush=True)
         return
 
     flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
@@ -366,7 +440,8 @@ def main():
     # free the net before the stand-alone update benchmark
     del st
     torch.cuda.empty_cache()
-    grad_update = None if args.skip_update_bench else grad_update_standalone(cg, torch, max(args.steps, 5), args.warmup)
+    grad_update = None if args.skip_update_bench else grad_update_standalone(cg, torch, min(max(args.steps, 5), 50), args.warmup)
+    achievable = None if args.skip_update_bench else hbm_achievable(cg, torch)
     if grad_update:
         for k, v in grad_update.items():
             if "bytes" not in v:
@@ -395,6 +470,25 @@ def main():
     if args.googlenet_steps > 0 and not args.serial:
         googlenet = googlenet_workload(cg, torch, sgd, args.googlenet_steps, cg.CG_STEP_OVERLAP)
 
+    # ---- configuration 2 stand-alone (every layer's three passes, the first layer's backward-data included)
+    # and the other per-worker batch configuration 4 names (B = 64), as context beside the headline
+    layer_bench = b64 = None
+    if not args.skip_layer_bench and not args.serial:
+        layer_bench = conv_layers_standalone(cg, torch, B)
+        if B != 64:
+            st64 = build_net(cg, torch, 64, K, seed=4, n_batches=16)
+            torch.cuda.synchronize()
+            run_steps(cg, torch, st64, sgd, 5, cg.CG_STEP_OVERLAP)
+            sync(torch, st64)
+            t0 = time.perf_counter()
+            run_steps(cg, torch, st64, sgd, 50, cg.CG_STEP_OVERLAP)
+            sync(torch, st64)
+            ms64 = (time.perf_counter() - t0) / 50 * 1e3
+            b64 = {"workload": f"alexnet_shaped_train_step_B64_K{K}", "ms_per_step": ms64, "images_per_s": 64 / (ms64 * 1e-3),
+                   "steps": 50}
+            del st64
+            torch.cuda.empty_cache()
+
     # the oracle last: its OpenMP workers keep spinning for a while after their last loop and would
     # take host cores from the launch-bound workloads above
     cpu = cpu_baseline(args.cpu_sample, K) if args.cpu_sample > 0 else None
@@ -419,6 +513,9 @@ def main():
         "matrix_core_kernels_exclusive": totals_excl,
         "serial_schedule_ms_per_step": serial_ms,
         "grad_update": grad_update,
+        "hbm_achievable": achievable,
+        "conv_layers_standalone": layer_bench,
+        "alexnet_b64_step": b64,
         "inception_step": inception,
         "googlenet_step": googlenet,
         "cpu_baseline": cpu,

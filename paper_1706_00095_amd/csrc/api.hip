@@ -1,4 +1,5 @@
 // Error strings, version and the per-thread record of the last HIP failure.
+#include <atomic>
 #include <cstdio>
 #include <mutex>
 #include <vector>
@@ -27,7 +28,7 @@ struct ProfRec {
 std::mutex g_prof_mu;
 std::vector<ProfRec> g_prof;      // records of the current session (events are reused across sessions)
 size_t g_prof_used = 0;
-bool g_prof_enabled = false;
+std::atomic<bool> g_prof_enabled{false};
 thread_local const char *g_pass = "";
 thread_local int g_layer = -1;
 }  // namespace
@@ -114,6 +115,49 @@ extern "C" int cg_debug_copy(void *dst, const void *src, size_t bytes, void *str
     if ((n4 + 255) / 256 >= (1ull << 31)) return CG_EUNSUPPORTED;
     hipLaunchKernelGGL(cg::debug_copy_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<float4 *>(dst), static_cast<const float4 *>(src), n4);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
+// The simplest streaming kernels, for the rates the memory system reaches (quoted beside the
+// published peak): one float4 per thread, non-temporal, one short-lived block per 4 KB.
+namespace cg {
+typedef float f4nt __attribute__((ext_vector_type(4)));
+template <int MODE>
+__global__ __launch_bounds__(256) void debug_stream_kernel(f4nt *__restrict__ dst, const f4nt *__restrict__ src,
+                                                           const f4nt *__restrict__ src2, size_t n4)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    if (MODE == 0) {
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    } else if (MODE == 1) {
+        const f4nt a = __builtin_nontemporal_load(src + i);
+        if (a.x + a.y + a.z + a.w == 123.456f) dst[0] = a;
+    } else if (MODE == 2) {
+        __builtin_nontemporal_store(f4nt{1.f, 2.f, 3.f, 4.f}, dst + i);
+    } else {
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i) + 3.f * __builtin_nontemporal_load(src2 + i), dst + i);
+    }
+}
+}  // namespace cg
+
+extern "C" int cg_debug_stream(void *dst, const void *src, const void *src2, size_t bytes, int mode, void *stream)
+{
+    if (mode < 0 || mode > 3 || !dst || !cg::aligned16(dst) || bytes % 16) return CG_EINVAL;
+    if (mode != 2 && (!src || !cg::aligned16(src))) return CG_EINVAL;
+    if (mode == 3 && (!src2 || !cg::aligned16(src2))) return CG_EINVAL;
+    if (bytes == 0) return CG_OK;
+    const size_t n4 = bytes / 16;
+    if ((n4 + 255) / 256 >= (1ull << 31)) return CG_EUNSUPPORTED;
+    const dim3 grid((unsigned)((n4 + 255) / 256));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    cg::f4nt *d = static_cast<cg::f4nt *>(dst);
+    const cg::f4nt *a = static_cast<const cg::f4nt *>(src), *b = static_cast<const cg::f4nt *>(src2);
+    if (mode == 0) hipLaunchKernelGGL(cg::debug_stream_kernel<0>, grid, dim3(256), 0, s, d, a, b, n4);
+    else if (mode == 1) hipLaunchKernelGGL(cg::debug_stream_kernel<1>, grid, dim3(256), 0, s, d, a, b, n4);
+    else if (mode == 2) hipLaunchKernelGGL(cg::debug_stream_kernel<2>, grid, dim3(256), 0, s, d, a, b, n4);
+    else hipLaunchKernelGGL(cg::debug_stream_kernel<3>, grid, dim3(256), 0, s, d, a, b, n4);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include "cg.h"
+#include "cg_debug.h"
 
 namespace cg {
 

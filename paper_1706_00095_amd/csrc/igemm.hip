@@ -13,6 +13,7 @@
 // element that is zero padding, lies beyond the tile's rows or beyond K gets an offset outside the
 // buffer descriptor's range, for which the hardware writes 0.  The loads of tile it+NST-1 are
 // issued while tile it is multiplied; one s_barrier per K-tile.
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
@@ -35,7 +36,26 @@ namespace {
 #define CG_SPLIT_BLOCKS 512
 #endif
 constexpr uint64_t kSplitBlocks = CG_SPLIT_BLOCKS;
-static uint32_t g_resident_blocks = 512;      // 256 compute units x 2 blocks of the matrix kernels (tests lower it)
+// Blocks of the matrix kernels the GPU keeps resident at once: two per compute unit of the current
+// device (512 on the 256 units of an MI355X), unless a test has set a lower count.
+static std::atomic<uint32_t> g_resident_override{0};
+uint32_t resident_blocks()
+{
+    const uint32_t o = g_resident_override.load(std::memory_order_relaxed);
+    if (o) return o;
+    static std::atomic<uint32_t> cached{0};
+    uint32_t c = cached.load(std::memory_order_relaxed);
+    if (!c) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            c = 2u * (uint32_t)cus;
+        else
+            c = 512;
+        cached.store(c, std::memory_order_relaxed);
+    }
+    return c;
+}
 
 constexpr int KT = 16;                       // reduction indices per LDS stage (a ring of NST stages)
 constexpr int NPART = KT / 2;                // MFMA steps per tile = parts the loads of a tile are issued in
@@ -1060,11 +1080,11 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
     constexpr size_t lds = (size_t)NST * (LA::SZ + LB::SZ) * sizeof(float);
     static_assert(lds >= 4 * EpiLds<TN>::FLOATS * sizeof(float), "the epilogue turns the tile around in the stages' LDS");
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
-    static bool attr_set = false;      // raising the dynamic-LDS limit is a per-kernel, one-time host call
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};      // raising the dynamic-LDS limit: once per kernel (repeating it is harmless)
+    if (!attr_set.load(std::memory_order_acquire)) {
         CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_kernel<WM, WN, TM, TN, NST, LA, LB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, NST, LA, LB>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
@@ -1203,11 +1223,11 @@ int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL>::BUF) * sizeof(float);
     static_assert(lds >= 4 * EpiLds<2>::FLOATS * sizeof(float), "the epilogue turns the tile around in the stages' LDS");
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
@@ -1230,11 +1250,11 @@ int launch_patch16_cfg(const IgemmProblem &p, hipStream_t stream)
     }
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL, 4>::BUF) * sizeof(float);
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_patch16_kernel<TM, NSTA, NSL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((igemm_patch16_kernel<TM, NSTA, NSL>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
@@ -1286,6 +1306,7 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
     // backward-data shares the GPU with backward-weight on another stream, whose blocks already
     // fill those compute units, and a second dependent launch then only delays it (measured).
     if (mt > 64 && p.patch.tile_count == 0 && !p.patch.flip) {
+        const uint32_t g_resident_blocks = resident_blocks();
         const uint32_t px = patch_pixel_tiles(p), per_px = ((p.M + mt - 1) / mt) * p.groups;
         const uint64_t blocks = (uint64_t)px * per_px;
         const uint32_t rounds = (uint32_t)(blocks / g_resident_blocks);
@@ -1329,11 +1350,11 @@ int launch_wgrad_cfg(const IgemmProblem &p, hipStream_t stream)
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * CPB * (NSL * 64 + 1)) * sizeof(float);
     static_assert(lds >= 4 * EpiLds<2>::FLOATS * sizeof(float), "the epilogue turns the tile around in the stages' LDS");
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_wgrad_kernel<2, 2, TM, 2, NSTA, CPB, NSL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((igemm_wgrad_kernel<2, 2, TM, 2, NSTA, CPB, NSL>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
@@ -1358,14 +1379,14 @@ int wgrad_launch(const IgemmProblem &p, hipStream_t stream)
 
 }  // namespace
 
-static uint32_t g_wgrad_enabled = 0;
-void wgrad_set_enabled(int on) { g_wgrad_enabled = on ? 1 : 0; }
+static std::atomic<uint32_t> g_wgrad_enabled{0};
+void wgrad_set_enabled(int on) { g_wgrad_enabled.store(on ? 1 : 0, std::memory_order_relaxed); }
 
 bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t images, uint32_t *splits)
 {
     g.cpb = g.nsl = 0;
     const int KK = g.KH * g.KW;
-    if (!g_wgrad_enabled || KK < 9 || g.s <= 0 || g.Cg <= 0 || images == 0) return false;
+    if (!g_wgrad_enabled.load(std::memory_order_relaxed) || KK < 9 || g.s <= 0 || g.Cg <= 0 || images == 0) return false;
     if (g.x_elems * 4 > kMaxBufferBytes || (uint64_t)images * g.M * g.OH * g.OW * 4 > kMaxBufferBytes) return false;
     g.Wp = (g.OW - 1) * g.s + g.KW;
     // channels a block of 128 columns can touch: at most 127/KK + 2
@@ -1400,9 +1421,9 @@ bool wgrad_plan(WgradGeom &g, uint32_t M, uint32_t N, uint32_t groups, uint32_t 
     return true;
 }
 
-static uint32_t g_patch_min_tiles = 512;
-void patch_set_min_tiles(uint32_t t) { g_patch_min_tiles = t; }
-void patch_set_resident_blocks(uint32_t b) { g_resident_blocks = b; }
+static std::atomic<uint32_t> g_patch_min_tiles{512};
+void patch_set_min_tiles(uint32_t t) { g_patch_min_tiles.store(t, std::memory_order_relaxed); }
+void patch_set_resident_blocks(uint32_t b) { g_resident_override.store(b, std::memory_order_relaxed); }
 
 bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
 {
@@ -1421,7 +1442,7 @@ bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
     g.divRfull = make_fastdiv((uint32_t)g.Rfull);
     // enough tiles to fill the chip without cutting K (the patch kernel has no K slices)
     const int mt = patch_mt(M, N, groups);
-    if ((uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups < g_patch_min_tiles) return false;
+    if ((uint64_t)((M + mt - 1) / mt) * ((N + 127) / 128) * groups < g_patch_min_tiles.load(std::memory_order_relaxed)) return false;
     // The largest patch any block needs: a fragment read reaches (KH-1)*Wp + KW-1 beyond sigma, and
     // sigma + that stays below the slot count of the block's segments, which is what is counted.
     auto slots = [&](uint32_t n0, uint32_t n1) {

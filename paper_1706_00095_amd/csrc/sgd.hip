@@ -62,12 +62,18 @@ __device__ __forceinline__ T rank_sum(const T s, const T *q)
 }
 
 // One launch serves up to MAXB buckets: block b belongs to the bucket whose [first, first + blocks)
-// range contains it and updates 2 x 256 consecutive float4 groups there, every load of a group
-// issued before the first use.  No loop: one short-lived block per 8 KB of each stream keeps far
+// range contains it and updates UNR x 256 consecutive float4 groups there, every load of a group
+// issued before the first use.  No loop: one short-lived block per few KB of each stream keeps far
 // more loads in flight than a persistent grid does, which is what the memory system rewards here.
+// Every access is non-temporal, the reads of w and v and the two stores included: each byte is
+// touched once per launch, and with the model and its history read through the caches and written
+// back through them the same kernel ran 5 % slower (K = 4: 72 -> 76 % of 8 TB/s on one array of
+// the eight buckets' size; either hint alone gained nothing or lost).
 constexpr int MAXB = 8;          // buckets per launch
 constexpr int KMAX_TAB = 16;     // peers per bucket in the table (more: the run-time-K kernel)
-constexpr int UNR = 2;
+// float4 groups per thread: the more streams a thread reads, the fewer groups it needs in flight
+// (measured on the same array: K = 8 with four groups 75 %, with two 72 %; K = 16 with one 73 %, with two 72 %)
+constexpr int unr_for(int K) { return K <= 4 ? 2 : K <= 8 ? 4 : 1; }
 
 struct Bucket {
     float *w, *v;
@@ -84,6 +90,7 @@ struct BucketTable {
 template <int KC, bool TREE>
 __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, const cg_sgd c)
 {
+    constexpr int UNR = unr_for(KC);
     int bi = 0;
 #pragma unroll
     for (int j = 1; j < MAXB; ++j)
@@ -101,10 +108,14 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, 
             s[u] = __builtin_nontemporal_load(g4 + i);
 #pragma unroll
             for (int k = 0; k < KC; ++k) q[u][k] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(bk.peer[k]) + i);
-            wi[u] = w4[i];
-            vi[u] = v4[i];
+            wi[u] = __builtin_nontemporal_load(w4 + i);
+            vi[u] = __builtin_nontemporal_load(v4 + i);
         }
     }
+    // every load above is issued before the first addition below: left to itself the instruction
+    // scheduler saves registers by adding each peer's values as they arrive, which halves the loads a
+    // thread has in flight (K = 16, one group per thread: 1.71 ms instead of 0.89 for the eight buckets)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
         const size_t i = i0 + (size_t)u * 256;
@@ -117,8 +128,8 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, 
             wo.z = upd(wi[u].z, vi[u].z, t.z, c, v2);
             wo.w = upd(wi[u].w, vi[u].w, t.w, c, v3);
             vo.x = v0; vo.y = v1; vo.z = v2; vo.w = v3;
-            w4[i] = wo;
-            v4[i] = vo;
+            __builtin_nontemporal_store(wo, w4 + i);
+            __builtin_nontemporal_store(vo, v4 + i);
         }
     }
     // ragged tail (n % 4 elements), handled by the first threads of the bucket's first block
@@ -175,8 +186,8 @@ __global__ __launch_bounds__(256) void reduce_sgd_anyk_kernel(float *__restrict_
             for (int k = 0; k < K; ++k)
                 add4(s, __builtin_nontemporal_load(reinterpret_cast<const f4 *>(peers.p[k]) + i));
         }
-        const f4 wi = reinterpret_cast<const f4 *>(w)[i];
-        const f4 vi = reinterpret_cast<const f4 *>(v)[i];
+        const f4 wi = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(w) + i);
+        const f4 vi = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(v) + i);
         f4 wo, vo;
         float v0, v1, v2, v3;
         wo.x = upd(wi.x, vi.x, s.x, c, v0);
@@ -184,8 +195,8 @@ __global__ __launch_bounds__(256) void reduce_sgd_anyk_kernel(float *__restrict_
         wo.z = upd(wi.z, vi.z, s.z, c, v2);
         wo.w = upd(wi.w, vi.w, s.w, c, v3);
         vo.x = v0; vo.y = v1; vo.z = v2; vo.w = v3;
-        reinterpret_cast<f4 *>(w)[i] = wo;
-        reinterpret_cast<f4 *>(v)[i] = vo;
+        __builtin_nontemporal_store(wo, reinterpret_cast<f4 *>(w) + i);
+        __builtin_nontemporal_store(vo, reinterpret_cast<f4 *>(v) + i);
     }
     const size_t tail = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0 && tail < n) {
@@ -205,12 +216,22 @@ __global__ __launch_bounds__(256) void reduce_sgd_anyk_kernel(float *__restrict_
 
 namespace {
 
-int check_bucket(const float *w, const float *v, const float *g, const float *const *peers, int K)
+// [a, a+n) and [b, b+n) share an element
+bool overlap(const float *a, const float *b, size_t n)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b), len = n * sizeof(float);
+    return x < y + len && y < x + len;
+}
+
+// w and v are written while every gradient buffer is still being read by other blocks: none of the
+// gradients may share memory with w or v, nor w with v (gradient buffers may alias each other)
+int check_bucket(const float *w, const float *v, const float *g, const float *const *peers, int K, size_t n)
 {
     if (!w || !v || !g || (K > 0 && !peers)) return CG_EINVAL;
-    if (!aligned16(w) || !aligned16(v) || !aligned16(g) || w == v) return CG_EINVAL;
+    if (!aligned16(w) || !aligned16(v) || !aligned16(g)) return CG_EINVAL;
+    if (overlap(w, v, n) || overlap(g, w, n) || overlap(g, v, n)) return CG_EINVAL;
     for (int k = 0; k < K; ++k)
-        if (!peers[k] || !aligned16(peers[k])) return CG_EINVAL;
+        if (!peers[k] || !aligned16(peers[k]) || overlap(peers[k], w, n) || overlap(peers[k], v, n)) return CG_EINVAL;
     return CG_OK;
 }
 
@@ -240,7 +261,7 @@ int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const f
     if (!w || !v || !g_local || !n || (K > 0 && !g_peers)) return CG_EINVAL;
     for (int i = 0; i < nb; ++i) {
         if (n[i] == 0) continue;
-        const int rc = check_bucket(w[i], v[i], g_local[i], K > 0 ? g_peers[i] : nullptr, K);
+        const int rc = check_bucket(w[i], v[i], g_local[i], K > 0 ? g_peers[i] : nullptr, K, n[i]);
         if (rc) return rc;
         if (n[i] >= (1ull << 40)) return CG_EUNSUPPORTED;
     }
@@ -272,7 +293,8 @@ int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const f
         double bytes = 0.0;
         while (i < nb && tab.nb < MAXB) {
             if (n[i] == 0) { ++i; continue; }
-            const unsigned long long bb = (n[i] / 4 + 256 * UNR - 1) / (256 * UNR);
+            const unsigned long long per_block = 256ull * unr_for(K);
+            const unsigned long long bb = (n[i] / 4 + per_block - 1) / per_block;
             const unsigned long long need = bb ? bb : 1;           // a bucket of 1..3 elements still needs its tail block
             if (blocks + need >= (1ull << 31)) break;
             Bucket &bk = tab.b[tab.nb++];

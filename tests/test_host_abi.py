@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "cg.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(cg_[a-z_0-9]+)\s*\(", text)))
 
@@ -57,6 +57,10 @@ def test_entry_points_reject_null_and_misaligned_arguments_without_launching():
     assert lib.cg_grad_reduce_sgd(16, 32, 48, None, 65, 8, C.byref(s), None) == cg.CG_EINVAL
     assert lib.cg_grad_reduce_sgd(16, 32, 48, None, 2, 8, C.byref(s), None) == cg.CG_EINVAL   # K>0, no peers
     assert lib.cg_grad_reduce_sgd(16, 16, 48, None, 0, 8, C.byref(s), None) == cg.CG_EINVAL   # w aliases v
+    assert lib.cg_grad_reduce_sgd(16, 4096, 32, None, 0, 8, C.byref(s), None) == cg.CG_EINVAL  # g_local inside w's range
+    assert lib.cg_grad_reduce_sgd(4096, 16, 32, None, 0, 8, C.byref(s), None) == cg.CG_EINVAL  # g_local inside v's range
+    peers = (C.c_void_p * 2)(8192, 4096 + 16)
+    assert lib.cg_grad_reduce_sgd(4096, 16384, 32768, peers, 2, 8, C.byref(s), None) == cg.CG_EINVAL  # a peer overlaps w
     assert lib.cg_grad_reduce_sgd(16, 36, 48, None, 0, 8, C.byref(s), None) == cg.CG_EINVAL   # misaligned
     assert lib.cg_grad_reduce_sgd(None, None, None, None, 0, 0, C.byref(s), None) == cg.CG_OK  # n == 0: no-op
     assert lib.cg_grad_reduce_sgd(16, 32, 48, None, 0, 8, None, None) == cg.CG_EINVAL
