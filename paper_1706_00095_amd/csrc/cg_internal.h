@@ -150,6 +150,13 @@ struct IgemmProblem {
     float *c_ptr;
     int32_t c_row_stride;     // C row m lives at m * c_row_stride (+ column offset)
     IndexMap c_col;           // column n -> offset
+    // Scattered output (c_scatter != 0): row m lives at map_info(c_row, m).off instead, and element
+    // (m, n) exists only if (unsigned)(row.a + col.a) < c_limA && (unsigned)(row.b + col.b) < c_limB
+    // (backward-data of a strided convolution: rows are (channel, stride phase), columns are cells of
+    // stride x stride input pixels, and phases that fall outside the image are not stored).
+    int c_scatter;
+    IndexMap c_row;
+    uint32_t c_limA, c_limB;
     int64_t c_gstride, c_split_stride;
     const float *bias;        // per row (bias_mode 1) or per column (2); NULL / 0 = none
     int bias_mode;

@@ -79,6 +79,28 @@ __global__ __launch_bounds__(256) void permute_filters_kernel(const float *__res
     }
 }
 
+// Filters as the matrix of strided backward-data (see bwd_data_strided_problem): row (c, rh, rw),
+// reduction index (m, a, b) with filter tap kh = rh + sh*a, kw = rw + sw*b (zero where that tap
+// does not exist).  tap_major = 1: dst[g][row][t = a*Aw + b][m] (the patch kernel's order);
+// 0: dst[g][row][m][t] (the gathered kernel's).
+__global__ __launch_bounds__(256) void strided_filters_kernel(const float *__restrict__ w, float *__restrict__ dst,
+                                                              int G, int Mg, int Cg, int KH, int KW, int sh, int sw,
+                                                              int Ah, int Aw, int tap_major)
+{
+    const int R = Cg * sh * sw, T = Ah * Aw;
+    const size_t total = (size_t)G * R * T * Mg;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        int m, t;
+        size_t q;
+        if (tap_major) { m = (int)(i % Mg); q = i / Mg; t = (int)(q % T); q /= T; }
+        else { t = (int)(i % T); q = i / T; m = (int)(q % Mg); q /= Mg; }
+        const int row = (int)(q % R), g = (int)(q / R);
+        const int rw = row % sw, rh = (row / sw) % sh, c = row / (sw * sh);
+        const int kh = rh + sh * (t / Aw), kw = rw + sw * (t % Aw);
+        dst[i] = (kh < KH && kw < KW) ? w[(((size_t)g * Mg + m) * Cg + c) * KH * KW + kh * KW + kw] : 0.f;
+    }
+}
+
 // General-stride backward-data, gather form, one thread per dx element.  Only the taps with
 // (ih + p - kh) divisible by the stride contribute.
 __global__ __launch_bounds__(256) void bwd_data_strided_kernel(const cg_conv_desc d, int OH, int OW,
@@ -400,6 +422,115 @@ static IgemmProblem bwd_data_problem(const cg_conv_desc &d, int OH, int OW, cons
     return p;
 }
 
+// Backward-data of a convolution with stride (sh, sw) > 1 as ONE stride-1 problem on the matrix
+// cores.  Write an input row as ih + ph = sh*i + rh (cell i, phase rh < sh).  Only the taps
+// kh = rh + sh*a reach it, from output row oh = i - a, so
+//   dx[n, c, sh*i + rh - ph, sw*j + rw - pw] = sum_{m, a, b} dy[n, m, i - a, j - b] * w[m, c, rh + sh*a, rw + sw*b]:
+// a correlation of dy with Ah x Aw = ceil(KH/sh) x ceil(KW/sw) taps whose "output channels" are the
+// Cg * sh * sw pairs (channel, phase), the filters rearranged accordingly (zeros for taps beyond
+// the window), and whose result is scattered cell by cell into dx (depth to space; phases outside
+// the image are dropped).  Every dx element is the row/column pair of exactly one cell and phase,
+// so dx is overwritten completely.  The first layer of the benchmark net (3 channels, 11x11,
+// stride 4) becomes 48 rows x 864 reduction indices, of which 121/144 multiply a real tap.
+struct StridedGeom { int sh, sw, Ah, Aw, Ch, Cw, R, Kp; uint32_t Np; };
+
+static bool strided_geom(const cg_conv_desc &d, StridedGeom &s)
+{
+    s.sh = d.stride_h; s.sw = d.stride_w;
+    s.Ah = (d.KH + s.sh - 1) / s.sh; s.Aw = (d.KW + s.sw - 1) / s.sw;
+    s.Ch = (d.H - 1 + d.pad_h) / s.sh + 1; s.Cw = (d.W - 1 + d.pad_w) / s.sw + 1;
+    const int64_t R = (int64_t)(d.C / d.groups) * s.sh * s.sw, Kp = (int64_t)(d.M / d.groups) * s.Ah * s.Aw;
+    const int64_t Np = (int64_t)d.N * s.Ch * s.Cw;
+    if (R < 8 || R >= (1 << 20) || Kp >= (1 << 28) || Np >= (1ll << 30) || R * Kp * d.groups >= (1ll << 29)) return false;
+    s.R = (int)R; s.Kp = (int)Kp; s.Np = (uint32_t)Np;
+    return true;
+}
+
+static IgemmProblem bwd_data_strided_problem(const cg_conv_desc &d, const StridedGeom &sg, int OH, int OW, const float *dy,
+                                             const float *wt, float *dx, int accumulate)
+{
+    const int G = d.groups, Cg = d.C / G, Mg = d.M / G, P = OH * OW, T = sg.Ah * sg.Aw;
+    IgemmProblem p{};
+    p.A.ptr = wt;
+    p.A.row = linear_map((uint32_t)sg.R, sg.Kp);
+    p.A.k = linear_map((uint32_t)sg.Kp, 1);
+    p.A.limA = p.A.limB = 1;
+    p.A.gstride = (int64_t)sg.R * sg.Kp;
+    p.A.elems = (uint64_t)G * sg.R * sg.Kp;
+    p.A.lanes_k = 1;
+    // dy seen from a cell (n, i, j): origin (i, j), tap (m, a, b) subtracts (a, b)
+    p.B.ptr = dy;
+    IndexMap cell{};
+    cell.count = sg.Np;
+    cell.d1 = make_fastdiv((uint32_t)sg.Ch * sg.Cw);
+    cell.d2 = make_fastdiv((uint32_t)sg.Cw);
+    cell.s1 = d.M * P; cell.s2 = OW; cell.s3 = 1;
+    cell.sa = 1; cell.sb = 1;
+    IndexMap tap{};
+    tap.count = (uint32_t)sg.Kp;
+    tap.d1 = make_fastdiv((uint32_t)T);
+    tap.d2 = make_fastdiv((uint32_t)sg.Aw);
+    tap.s1 = P; tap.s2 = -OW; tap.s3 = -1;
+    tap.sa = -1; tap.sb = -1;
+    p.B.row = cell; p.B.k = tap;
+    p.B.limA = OH; p.B.limB = OW;
+    p.B.gstride = (int64_t)Mg * P;
+    p.B.elems = (uint64_t)d.N * d.M * P;
+    p.B.lanes_k = 0;
+    p.B.check = 1;
+    // C: row (c, rh, rw) and cell (n, i, j) -> dx[n, c, sh*i + rh - ph, sw*j + rw - pw]
+    const int HW = d.H * d.W;
+    p.c_ptr = dx;
+    p.c_scatter = 1;
+    p.c_row = IndexMap{};
+    p.c_row.count = (uint32_t)sg.R;
+    p.c_row.d1 = make_fastdiv((uint32_t)sg.sh * sg.sw);
+    p.c_row.d2 = make_fastdiv((uint32_t)sg.sw);
+    p.c_row.s1 = HW; p.c_row.s2 = d.W; p.c_row.s3 = 1; p.c_row.o0 = -d.pad_h * d.W - d.pad_w;
+    p.c_row.sa = 1; p.c_row.a0 = -d.pad_h; p.c_row.sb = 1; p.c_row.b0 = -d.pad_w;
+    p.c_col = IndexMap{};
+    p.c_col.count = sg.Np;
+    p.c_col.d1 = make_fastdiv((uint32_t)sg.Ch * sg.Cw);
+    p.c_col.d2 = make_fastdiv((uint32_t)sg.Cw);
+    p.c_col.s1 = d.C * HW; p.c_col.s2 = sg.sh * d.W; p.c_col.s3 = sg.sw;
+    p.c_col.sa = sg.sh; p.c_col.sb = sg.sw;
+    p.c_limA = d.H; p.c_limB = d.W;
+    p.c_gstride = (int64_t)Cg * HW;
+    p.M = (uint32_t)sg.R; p.N = sg.Np; p.K = (uint32_t)sg.Kp;
+    p.flops = 2.0 * Mg * Cg * d.KH * d.KW * ((double)d.N * P) * G;
+    p.groups = G; p.splits = 1; p.k_per_split = p.K;
+    p.accumulate = accumulate;
+    return p;
+}
+
+// dy as the patch operand of that problem: cells are the pixels, the taps are mirrored
+static bool bwd_data_strided_patch(const cg_conv_desc &d, const StridedGeom &sg, int OH, int OW, const float *dy,
+                                   IgemmProblem &p)
+{
+    const int G = d.groups, Mg = d.M / G;
+    PatchGeom g{};
+    g.src = dy; g.src_elems = (uint64_t)d.N * d.M * OH * OW;
+    g.gstride = (int64_t)Mg * OH * OW;
+    g.Cred = (uint32_t)Mg; g.Hs = OH; g.Ws = OW; g.chan_stride = OH * OW; g.img_stride = d.M * OH * OW;
+    g.OHo = sg.Ch; g.OWo = sg.Cw; g.s = 1; g.oy0 = -(sg.Ah - 1); g.ox0 = -(sg.Aw - 1);
+    g.KH = sg.Ah; g.KW = sg.Aw; g.flip = 1;
+    if (!patch_plan(g, (uint32_t)sg.R, sg.Np, (uint32_t)G)) return false;
+    p.patch = g; p.use_patch = 1;
+    return true;
+}
+
+static int strided_filters(const float *w, float *dst, const cg_conv_desc &d, const StridedGeom &sg, int tap_major,
+                           hipStream_t stream)
+{
+    const int G = d.groups;
+    const size_t total = (size_t)G * sg.R * sg.Kp;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(strided_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, dst, G, d.M / G, d.C / G, d.KH, d.KW,
+                       sg.sh, sg.sw, sg.Ah, sg.Aw, tap_major);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream)
 {
@@ -407,8 +538,21 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
+    StridedGeom sg;
+    if ((d.stride_h != 1 || d.stride_w != 1) && strided_geom(d, sg)) {
+        const size_t wt_bytes = round256((size_t)d.groups * sg.R * sg.Kp * sizeof(float));
+        if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
+        if (!aligned16(ws)) return CG_EINVAL;
+        float *wt = static_cast<float *>(ws);
+        IgemmProblem p = bwd_data_strided_problem(d, sg, OH, OW, dy, wt, dx, accumulate);
+        p.gate = gate;
+        const bool patch = bwd_data_strided_patch(d, sg, OH, OW, dy, p);
+        const int rc2 = strided_filters(w, wt, d, sg, patch ? 1 : 0, stream);
+        if (rc2) return rc2;
+        return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
+    }
     if (d.stride_h != 1 || d.stride_w != 1) {
-        // by stride phase, for at most four taps per dimension and phase
+        // few rows (channels x phases): by stride phase, for at most four taps per dimension and phase
         const int Cg = d.C / d.groups;
         const int Ahm = (d.KH + d.stride_h - 1) / d.stride_h, Awm = (d.KW + d.stride_w - 1) / d.stride_w;
         const int am = Ahm > Awm ? Ahm : Awm;
@@ -556,6 +700,12 @@ size_t conv_ws_bytes(const cg_conv_desc &d, int pass)
         return igemm_ws_bytes(p);
     }
     if (pass == CG_PASS_BWD_DATA) {
+        StridedGeom sg;
+        if ((d.stride_h != 1 || d.stride_w != 1) && strided_geom(d, sg)) {
+            IgemmProblem p = bwd_data_strided_problem(d, sg, OH, OW, nullptr, nullptr, nullptr, 0);
+            bwd_data_strided_patch(d, sg, OH, OW, nullptr, p);
+            return round256((size_t)d.groups * sg.R * sg.Kp * sizeof(float)) + igemm_ws_bytes(p);
+        }
         if (d.stride_h != 1 || d.stride_w != 1) return 0;
         return round256((size_t)d.M * (d.C / d.groups) * d.KH * d.KW * sizeof(float)) +
                igemm_ws_bytes(bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0));

@@ -318,16 +318,18 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
     const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
     const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
     const uint32_t n = nw + 4u * (uint32_t)qd;
-    int32_t off[4];
+    int32_t off[4], ca[4], cb[4];
     bool ok[4];
     float bcol[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         ok[e] = n + (uint32_t)e < n_end;
-        off[e] = ok[e] ? map_info(p.c_col, n + (uint32_t)e).off : 0;
+        const Info ci = map_info(p.c_col, ok[e] ? n + (uint32_t)e : 0u);
+        off[e] = ok[e] ? ci.off : 0;
+        ca[e] = ci.a; cb[e] = ci.b;
         bcol[e] = (p.bias_mode == 2 && ok[e]) ? bias[n + (uint32_t)e] : 0.f;
     }
-    const bool quad = ok[3] && off[1] == off[0] + 1 && off[2] == off[0] + 2 && off[3] == off[0] + 3;
+    const bool quad = !p.c_scatter && ok[3] && off[1] == off[0] + 1 && off[2] == off[0] + 2 && off[3] == off[0] + 3;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -342,6 +344,8 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
         for (int p0 = 0; p0 < 32 / RPI; p0 += PB) {
             float4 q[PB];
             f4u gt[PB], old[PB];
+            int32_t roff[PB];
+            bool okm[PB][4];
 #pragma unroll
             for (int u = 0; u < PB; ++u) {
                 const int row = (p0 + u) * RPI + rr;
@@ -349,16 +353,26 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
                 q[u] = *reinterpret_cast<const float4 *>(wlds + row * LS + 4 * qd);
                 gt[u] = f4u{1.f, 1.f, 1.f, 1.f};
                 old[u] = f4u{0.f, 0.f, 0.f, 0.f};
+                roff[u] = (int32_t)m * p.c_row_stride;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) okm[u][e] = ok[e] && m < p.M;
+                if (p.c_scatter && m < p.M) {
+                    const Info ri = map_info(p.c_row, m);
+                    roff[u] = ri.off;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        okm[u][e] = ok[e] && (uint32_t)(ri.a + ca[e]) < p.c_limA && (uint32_t)(ri.b + cb[e]) < p.c_limB;
+                }
                 if (m < p.M) {
-                    const int32_t row_off = (int32_t)m * p.c_row_stride;
+                    const int32_t row_off = roff[u];
                     if (quad) {
                         if (gate) gt[u] = *reinterpret_cast<const f4u *>(gate + row_off + off[0]);
                         if (p.accumulate) old[u] = *reinterpret_cast<const f4u *>(c_base + row_off + off[0]);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            if (gate && ok[e]) gt[u][e] = gate[row_off + off[e]];
-                            if (p.accumulate && ok[e]) old[u][e] = c_base[row_off + off[e]];
+                            if (gate && okm[u][e]) gt[u][e] = gate[row_off + off[e]];
+                            if (p.accumulate && okm[u][e]) old[u][e] = c_base[row_off + off[e]];
                         }
                     }
                 }
@@ -375,7 +389,7 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
                     val[e] += brow;
                     if (p.relu) val[e] = fmaxf(val[e], 0.f);
                 }
-                const int32_t row_off = (int32_t)m * p.c_row_stride;
+                const int32_t row_off = roff[u];
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if (!(gt[u][e] > 0.f)) val[e] = 0.f;
@@ -386,7 +400,7 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (ok[e]) c_base[row_off + off[e]] = out[e];
+                        if (okm[u][e]) c_base[row_off + off[e]] = out[e];
                 }
             }
         }
@@ -840,7 +854,8 @@ __global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProble
     for (int j = 0; j < TN; ++j) {
         const uint32_t n = n0 + (uint32_t)((wave * TN + j) * 16 + l16);
         if (n > n1) continue;
-        const int32_t coff = map_info(p.c_col, n).off;
+        const Info ci = map_info(p.c_col, n);
+        const int32_t coff = ci.off;
         const float bcol = p.bias_mode == 2 ? bias[n] : 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -848,10 +863,15 @@ __global__ __launch_bounds__(256, 2) void igemm_patch16_kernel(const IgemmProble
             for (int r = 0; r < 4; ++r) {
                 const uint32_t m = m0 + (uint32_t)(i * 16 + q * 4 + r);
                 if (m < p.M) {
+                    int32_t idx = (int32_t)m * p.c_row_stride + coff;
+                    if (p.c_scatter) {
+                        const Info ri = map_info(p.c_row, m);
+                        if (!((uint32_t)(ri.a + ci.a) < p.c_limA && (uint32_t)(ri.b + ci.b) < p.c_limB)) continue;
+                        idx = ri.off + coff;
+                    }
                     float val = acc[i][j][r] + bcol;
                     if (p.bias_mode == 1) val += bias[m];
                     if (p.relu) val = fmaxf(val, 0.f);
-                    const int32_t idx = (int32_t)m * p.c_row_stride + coff;
                     if (gate && !(gate[idx] > 0.f)) val = 0.f;
                     float *dst = c_base + idx;
                     if (p.accumulate) val += *dst;
@@ -1292,6 +1312,9 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
         if (p.patch.nsl == 4)
             return tm == 3 ? launch_patch16_cfg<3, 4, 4>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 4>(p, stream)
                                                                               : launch_patch16_cfg<1, 4, 4>(p, stream);
+        if (p.patch.nsl == 6)
+            return tm == 3 ? launch_patch16_cfg<3, 4, 6>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 6>(p, stream)
+                                                                              : launch_patch16_cfg<1, 4, 6>(p, stream);
         return tm == 3 ? launch_patch16_cfg<3, 4, 5>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 5>(p, stream)
                                                                           : launch_patch16_cfg<1, 4, 5>(p, stream);
     }
@@ -1467,8 +1490,8 @@ bool patch_plan(PatchGeom &g, uint32_t M, uint32_t N, uint32_t groups)
         if (sl > amax) amax = sl;
     }
     // six chunks (planes 56 wide with a 3x3 window: four pixel rows, 348 slots) leave room for 128-row
-    // tiles with a three-stage filter ring; the 16-row-tile kernel has no such instance
-    if (amax > 6 * 64 || (amax > 5 * 64 && M <= 48)) return false;
+    // tiles with a three-stage filter ring
+    if (amax > 6 * 64) return false;
     g.nsl = amax > 5 * 64 ? 6 : 5;
     g.tiles_per_img = (int32_t)((P + 127) / 128);
     g.divTpi = make_fastdiv((uint32_t)g.tiles_per_img);
@@ -1578,6 +1601,9 @@ struct FinishArgs {
     float *c_ptr;
     int32_t c_row_stride;
     IndexMap c_col;
+    int c_scatter;
+    IndexMap c_row;
+    uint32_t c_limA, c_limB;
     int64_t c_gstride;
     const float *bias;
     int bias_mode;
@@ -1602,7 +1628,13 @@ __device__ __forceinline__ void finish_store(const FinishArgs &a, uint32_t i, fl
     else if (a.bias_mode == 2) s += a.bias[(int64_t)g * a.bias_gstride + n];
     if (a.relu) s = fmaxf(s, 0.f);
     const Info ci = map_info(a.c_col, n);
-    const int64_t idx = (int64_t)g * a.c_gstride + ((int32_t)m * a.c_row_stride + ci.off);
+    int32_t in_group = (int32_t)m * a.c_row_stride + ci.off;
+    if (a.c_scatter) {
+        const Info ri = map_info(a.c_row, m);
+        if (!((uint32_t)(ri.a + ci.a) < a.c_limA && (uint32_t)(ri.b + ci.b) < a.c_limB)) return;
+        in_group = ri.off + ci.off;
+    }
+    const int64_t idx = (int64_t)g * a.c_gstride + in_group;
     if (a.gate && !(a.gate[idx] > 0.f)) s = 0.f;
     float *dst = a.c_ptr + idx;
     if (a.accumulate) s += *dst;
@@ -1687,6 +1719,7 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
     p.c_col = linear_map(p0.N, 1);
     p.c_gstride = (int64_t)p0.M * p0.N;
     p.c_split_stride = (int64_t)p0.groups * p0.M * p0.N;
+    p.c_scatter = 0;
     p.bias = nullptr; p.bias_mode = 0; p.accumulate = 0; p.relu = 0; p.gate = nullptr;
     p.splits = pl.splits; p.k_per_split = pl.k_per_split;
     const int rc = igemm_launch(p, stream);
@@ -1696,6 +1729,7 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
     a.plane = p.c_split_stride;
     a.splits = (int)pl.splits;
     a.c_ptr = p0.c_ptr; a.c_row_stride = p0.c_row_stride; a.c_col = p0.c_col; a.c_gstride = p0.c_gstride;
+    a.c_scatter = p0.c_scatter; a.c_row = p0.c_row; a.c_limA = p0.c_limA; a.c_limB = p0.c_limB;
     a.bias = p0.bias; a.bias_mode = p0.bias_mode; a.bias_gstride = p0.bias_gstride;
     a.M = p0.M; a.N = p0.N;
     a.divN = make_fastdiv(p0.N);

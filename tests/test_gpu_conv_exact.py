@@ -22,8 +22,16 @@ from test_gpu_conv import BAND_SHAPES, PATCH_SHAPES, SHAPES
 pytestmark = pytest.mark.gpu
 
 EXTRA_SHAPES = {
-    # backward-data with more than four taps per dimension and stride phase: the one-thread-per-element kernel
+    # strided backward-data as a stride-1 problem with 6 x 6 taps and 8 rows (2 channels x 4 phases)
     "eleven_s2": (2, dict(C=4, H=29, M=8, k=11, stride=2, pad=3, groups=2)),
+    # fewer than 8 (channel, phase) rows: backward-data by stride phase, and, with more than four taps per
+    # dimension and phase, by the one-thread-per-element kernel
+    "phase_s2_c1": (3, dict(C=1, H=17, M=12, k=3, stride=2, pad=1, groups=1)),
+    "phase_s3_c2_g2": (2, dict(C=2, H=20, M=6, k=5, stride=3, pad=2, groups=2)),
+    "eleven_s2_c1": (2, dict(C=2, H=29, M=8, k=11, stride=2, pad=3, groups=2)),
+    # strided backward-data through the kernel that stages raw rows of dy (16 output channels a group, 3 x 3 taps)
+    "strided_patch_s4": (2, dict(C=3, H=51, M=32, k=11, stride=4, pad=2, groups=1)),
+    "strided_patch_s2_g2": (3, dict(C=16, H=23, M=64, k=5, stride=2, pad=2, groups=2)),
     # backward-weight reductions cut into 2, ~10 and more than 16 K slices (both finishing kernels)
     "splitk_few": (8, dict(C=32, H=13, M=384, k=3, stride=1, pad=1, groups=1)),
     "splitk_many": (24, dict(C=8, H=13, M=32, k=3, stride=1, pad=1, groups=1)),
@@ -82,8 +90,16 @@ def _all_three(orc32, B, cfg, seed, fwd=True, bwd_data=True, bwd_weight=True):
 @pytest.mark.parametrize("name", list(SHAPES) + list(EXTRA_SHAPES))
 def test_gathered_and_strided_kernels_exact(orc32, name):
     B, cfg = {**SHAPES, **EXTRA_SHAPES}[name]
-    d, names = _all_three(orc32, B, cfg, seed=sum(map(ord, name)))
-    assert all(n.startswith("igemm_kernel") for n in names), names
+    if name.startswith("strided_patch"):
+        cg.cg_debug_patch_min_tiles(1)
+    try:
+        d, names = _all_three(orc32, B, cfg, seed=sum(map(ord, name)))
+    finally:
+        cg.cg_debug_patch_min_tiles(512)
+    if name.startswith("strided_patch"):
+        assert len([n for n in names if n.startswith("igemm_patch")]) >= 1, names
+    else:
+        assert all(n.startswith("igemm_kernel") for n in names), names
     if name.startswith("splitk"):
         # the reduction over pixels was cut: partial planes in the workspace, added by a second kernel
         bias_bytes = 4 * d.M * min(d.N, -(-2048 // d.M))
@@ -125,6 +141,8 @@ def test_patch_kernel_six_chunks_exact(orc32, patch_path, B, C, M, W):
     cfg = dict(C=C, H=56, W=W, M=M, k=3, stride=1, pad=1, groups=1)
     d, names = _all_three(orc32, B, cfg, seed=B * 100 + M, bwd_weight=False)
     assert len([n for n in names if n.startswith("igemm_patch_kernel") and n.endswith(",6>")]) == (2 if C > 48 else 1), names
+    if C <= 48:       # backward-data with at most 48 rows: the 16-row-tile kernel, six chunks as well
+        assert any(n.startswith("igemm_patch16_kernel") and n.endswith(",6>") for n in names), names
 
 
 @pytest.mark.parametrize("name", list(BAND_SHAPES))

@@ -80,7 +80,10 @@ def test_workspace_sizes():
     small = cg.conv_desc(2, 64, 13, 13, 64, 3, pad=1)
     assert cg.cg_conv_workspace_bytes(small, cg.CG_PASS_FWD) > 0                    # few tiles: K is sliced
     d1 = cg.conv_desc(256, 3, 227, 227, 96, 11, stride=4)
-    assert cg.cg_conv_workspace_bytes(d1, cg.CG_PASS_BWD_DATA) == 0      # strided path needs none
+    # strided backward-data: the filters rearranged by stride phase, 48 rows x (96 channels x 3 x 3 taps)
+    assert cg.cg_conv_workspace_bytes(d1, cg.CG_PASS_BWD_DATA) == 48 * 96 * 9 * 4
+    # a single input channel at stride 2: four (channel, phase) rows, the kernel by stride phase, no workspace
+    assert cg.cg_conv_workspace_bytes(cg.conv_desc(4, 1, 17, 17, 12, 3, stride=2, pad=1), cg.CG_PASS_BWD_DATA) == 0
 
 
 CASES = [
