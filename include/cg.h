@@ -61,6 +61,17 @@ typedef struct { float lr, mu, wd, grad_scale; } cg_sgd;
 
 enum { CG_PASS_FWD = 0, CG_PASS_BWD_DATA = 1, CG_PASS_BWD_WEIGHT = 2 };
 
+/* What the matrix instructions of a contraction multiply in.  Tensors are fp32 in
+ * memory and sums are accumulated in fp32 in every mode; the mode is always the
+ * caller's explicit choice, nothing selects a reduced one by itself.
+ *  CG_MATH_FP32   : fp32 products (the default of every entry point without a math argument).
+ *  CG_MATH_BF16   : both operands rounded to bf16 (nearest even) on their way into the
+ *                   matrix cores; parity bound 2e-2 (max-abs-relative).
+ *  CG_MATH_BF16X3 : every operand split into two bf16 numbers, a = ah + al, three
+ *                   products al*bh + ah*bl + ah*bh; the dropped al*bl is about 2^-16
+ *                   of a product, so results stay inside the fp32 parity bound. */
+enum { CG_MATH_FP32 = 0, CG_MATH_BF16 = 1, CG_MATH_BF16X3 = 2 };
+
 /* Output spatial size of a convolution.  Returns CG_EINVAL for an invalid descriptor. */
 int cg_conv_out_shape(const cg_conv_desc *d, int *OH, int *OW);
 
@@ -87,6 +98,20 @@ int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w,
  * fixed order, so results are reproducible run to run. */
 int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const float *dy,
                        float *dw, float *dbias, void *ws, size_t ws_bytes, void *stream);
+
+/* The three passes above with the arithmetic of the matrix instructions chosen by
+ * the caller (math = CG_MATH_*): the optional reduced-precision path for the
+ * "basic linear algebra operations" of section 2.1.  Same arguments, layouts,
+ * workspaces and errors; CG_MATH_FP32 is the call without the suffix.  The bias
+ * sum of backward-weight is always fp32.  CG_EUNSUPPORTED: backward-data of a
+ * strided convolution with fewer than 8 (channel, stride phase) pairs per group
+ * exists in fp32 only. */
+int cg_conv_fwd_math(const cg_conv_desc *d, const float *x, const float *w, const float *bias,
+                     float *y, void *ws, size_t ws_bytes, int math, void *stream);
+int cg_conv_bwd_data_math(const cg_conv_desc *d, const float *dy, const float *w,
+                          float *dx, void *ws, size_t ws_bytes, int math, void *stream);
+int cg_conv_bwd_weight_math(const cg_conv_desc *d, const float *x, const float *dy,
+                            float *dw, float *dbias, void *ws, size_t ws_bytes, int math, void *stream);
 
 /* cg_conv_bwd_weight for callers that can hand over no workspace and may not
  * allocate one: code under HIP graph capture, tight serving loops, harnesses
@@ -211,7 +236,8 @@ int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local,
 /* Device workspace (activations, gradients of activations, kernel scratch). */
 size_t cg_net_workspace_bytes(const cg_net *net);
 
-enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2, CG_STEP_TREE_SUM = 4 };
+enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2, CG_STEP_TREE_SUM = 4,
+       CG_STEP_BF16 = 8, CG_STEP_BF16X3 = 16 };
 
 /* One SGD iteration of this worker (Fig. 1 with the turn-based schedule of
  * Fig. 3): forward through layers 1..L, loss, then for l = L..1 the local
@@ -231,6 +257,9 @@ enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2, CG_STEP_TREE_S
  *  CG_STEP_TREE_SUM: the K+1 gradients of every layer are added in the
  *  association of the binomial reduction tree (cg_grad_reduce_sgd_tree) instead
  *  of left to right.
+ *  CG_STEP_BF16 / CG_STEP_BF16X3 (at most one of them): every convolution and
+ *  fully-connected pass of the step multiplies in CG_MATH_BF16 / CG_MATH_BF16X3
+ *  (see cg_conv_fwd_math); everything else, the update included, is unchanged.
  *  CG_STEP_JOIN (with the overlapped schedule): at the end of the call
  *  compute_stream also waits for the last update, so that every stream the call
  *  used has joined compute_stream and the next call depends on no event of this

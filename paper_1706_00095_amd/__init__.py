@@ -15,7 +15,8 @@ LIB_PATH = os.environ.get("CG_LIB_PATH", os.path.join(_HERE, "libcg.so"))
 
 CG_OK, CG_EINVAL, CG_ENOSPC, CG_EUNSUPPORTED, CG_EHIP = 0, -1, -2, -3, -4
 CG_PASS_FWD, CG_PASS_BWD_DATA, CG_PASS_BWD_WEIGHT = 0, 1, 2
-CG_STEP_OVERLAP, CG_STEP_SERIAL, CG_STEP_JOIN, CG_STEP_TREE_SUM = 0, 1, 2, 4
+CG_STEP_OVERLAP, CG_STEP_SERIAL, CG_STEP_JOIN, CG_STEP_TREE_SUM, CG_STEP_BF16, CG_STEP_BF16X3 = 0, 1, 2, 4, 8, 16
+CG_MATH_FP32, CG_MATH_BF16, CG_MATH_BF16X3 = 0, 1, 2
 CG_MAX_PEERS = 64
 CG_NOALLOC_SCRATCH_BYTES = 64 << 20
 LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc": 5, "dropout": 6,
@@ -23,6 +24,7 @@ LAYER_KINDS = {"conv": 0, "relu": 1, "lrn": 2, "maxpool": 3, "avgpool": 4, "fc":
 
 EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight", "cg_conv_bwd_weight_noalloc",
+    "cg_conv_fwd_math", "cg_conv_bwd_data_math", "cg_conv_bwd_weight_math",
     "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_grad_reduce_sgd_tree", "cg_grad_reduce_sgd_tree_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
     "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_net_tensor_image_stride", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_stream", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
@@ -75,6 +77,9 @@ def lib():
         L.cg_conv_bwd_data.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.cg_conv_bwd_weight.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.cg_conv_bwd_weight_noalloc.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.cg_conv_fwd_math.argtypes = [dp, vp, vp, vp, vp, vp, sz, C.c_int, vp]
+        L.cg_conv_bwd_data_math.argtypes = [dp, vp, vp, vp, vp, sz, C.c_int, vp]
+        L.cg_conv_bwd_weight_math.argtypes = [dp, vp, vp, vp, vp, vp, sz, C.c_int, vp]
         L.cg_grad_reduce_sgd.argtypes = [vp, vp, vp, C.POINTER(vp), C.c_int, sz, C.POINTER(cg_sgd), vp]
         L.cg_grad_reduce_sgd_multi.argtypes = [C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                                C.POINTER(C.POINTER(vp)), C.c_int, C.POINTER(sz), C.POINTER(cg_sgd), vp]
@@ -173,6 +178,21 @@ def cg_conv_bwd_data(d, dy, w, dx, ws=None, stream=None):
 def cg_conv_bwd_weight(d, x, dy, dw, dbias, ws=None, stream=None):
     _check(lib().cg_conv_bwd_weight(C.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(dbias), *_ws_args(ws),
                                     _stream(stream)), "cg_conv_bwd_weight")
+
+
+def cg_conv_fwd_math(d, x, w, bias, y, ws, math, stream=None):
+    _check(lib().cg_conv_fwd_math(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), *_ws_args(ws), math, _stream(stream)),
+           "cg_conv_fwd_math")
+
+
+def cg_conv_bwd_data_math(d, dy, w, dx, ws, math, stream=None):
+    _check(lib().cg_conv_bwd_data_math(C.byref(d), _ptr(dy), _ptr(w), _ptr(dx), *_ws_args(ws), math, _stream(stream)),
+           "cg_conv_bwd_data_math")
+
+
+def cg_conv_bwd_weight_math(d, x, dy, dw, dbias, ws, math, stream=None):
+    _check(lib().cg_conv_bwd_weight_math(C.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(dbias), *_ws_args(ws), math,
+                                         _stream(stream)), "cg_conv_bwd_weight_math")
 
 
 def cg_conv_bwd_weight_noalloc(d, x, dy, dw, dbias, stream=None):

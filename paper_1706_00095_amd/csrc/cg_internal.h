@@ -168,6 +168,7 @@ struct IgemmProblem {
     int relu;                 // C = max(result, 0) after bias (forward passes followed by a rectifier)
     const float *gate;        // same layout as C, or NULL: result = 0 where gate <= 0 (backward-data into a
                               // rectifier: the gradient with respect to the rectifier's input), before accumulate
+    int math;                 // CG_MATH_FP32, CG_MATH_BF16 or CG_MATH_BF16X3: what the matrix instructions multiply in
     int use_patch;            // B is described by `patch` (and A is the matching tap-major matrix); B unused
     PatchGeom patch;
     int use_wgrad;            // backward-weight from image bands (`wgrad`): A = dy rows, B unused, K counted in pixels
@@ -187,6 +188,9 @@ void patch_set_min_tiles(uint32_t t);
 
 // Validates the problem against what the kernels assume and launches it.
 int igemm_launch(const IgemmProblem &p, hipStream_t stream);
+// The same for the bf16 matrix instructions (igemm_launch dispatches on p.math)
+int igemm_launch_bf16(const IgemmProblem &p, hipStream_t stream);
+int igemm_launch_bf16x3(const IgemmProblem &p, hipStream_t stream);
 // Host-side evaluation of one operand element: offset and validity (for tests of the maps).
 void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, int64_t *off, int *valid);
 
@@ -208,18 +212,19 @@ int conv_check(const cg_conv_desc *d, int *OH, int *OW);
 size_t conv_ws_bytes(const cg_conv_desc &d, int pass);
 size_t fc_ws_bytes(int B, int IN, int OUT, int pass);
 // relu != 0: y = max(conv + bias, 0), the rectifier that follows folded into the store
+// math: CG_MATH_* (what the matrix instructions multiply in; workspace sizes do not depend on it)
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0);
+                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0, int math = 0);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
-                       size_t ws_bytes, int accumulate, hipStream_t stream);
+                       size_t ws_bytes, int accumulate, hipStream_t stream, int math = 0);
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
-                         void *ws, size_t ws_bytes, hipStream_t stream);
+                         void *ws, size_t ws_bytes, hipStream_t stream, int math = 0);
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
-                size_t ws_bytes, int relu, hipStream_t stream);
+                size_t ws_bytes, int relu, hipStream_t stream, int math = 0);
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, const float *gate,
-                     int accumulate, void *ws, size_t ws_bytes, hipStream_t stream);
+                     int accumulate, void *ws, size_t ws_bytes, hipStream_t stream, int math = 0);
 int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
-                       size_t ws_bytes, hipStream_t stream);
+                       size_t ws_bytes, hipStream_t stream, int math = 0);
 
 // ---- gradient aggregation + update (sgd.hip) --------------------------------------------------
 int grad_reduce_sgd_impl(float *w, float *v, const float *g_local, const float *const *g_peers, int K,

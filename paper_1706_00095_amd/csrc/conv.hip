@@ -338,9 +338,12 @@ static void tap_major_filters(IgemmProblem &p, const float *m, int rows, int K, 
     p.A.lanes_k = 1;
 }
 
+static bool math_ok(int math) { return math == CG_MATH_FP32 || math == CG_MATH_BF16 || math == CG_MATH_BF16X3; }
+
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride)
+                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride, int math)
 {
+    if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_fwd", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
@@ -351,6 +354,7 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
                                               y_img_stride * (int64_t)d.N >= (1ll << 31)))) return CG_EINVAL;
     IgemmProblem p = fwd_problem(d, OH, OW, x, w, bias, y, y_img_stride);
     p.relu = relu;
+    p.math = math;
     if (fwd_patch(d, OH, OW, x, p)) {
         const int G = d.groups, Cg = d.C / G, Mg = d.M / G, KK = d.KH * d.KW;
         const size_t wt_bytes = round256((size_t)d.M * Cg * KK * sizeof(float));
@@ -532,8 +536,9 @@ static int strided_filters(const float *w, float *dst, const cg_conv_desc &d, co
 }
 
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
-                       size_t ws_bytes, int accumulate, hipStream_t stream)
+                       size_t ws_bytes, int accumulate, hipStream_t stream, int math)
 {
+    if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_bwd_data", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
@@ -546,11 +551,13 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         float *wt = static_cast<float *>(ws);
         IgemmProblem p = bwd_data_strided_problem(d, sg, OH, OW, dy, wt, dx, accumulate);
         p.gate = gate;
+        p.math = math;
         const bool patch = bwd_data_strided_patch(d, sg, OH, OW, dy, p);
         const int rc2 = strided_filters(w, wt, d, sg, patch ? 1 : 0, stream);
         if (rc2) return rc2;
         return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
     }
+    if ((d.stride_h != 1 || d.stride_w != 1) && math != CG_MATH_FP32) return CG_EUNSUPPORTED;   // plain vector arithmetic below
     if (d.stride_h != 1 || d.stride_w != 1) {
         // few rows (channels x phases): by stride phase, for at most four taps per dimension and phase
         const int Cg = d.C / d.groups;
@@ -597,6 +604,7 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     {
         IgemmProblem pp = bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate);
         pp.gate = gate;
+        pp.math = math;
         if (bwd_data_patch(d, OH, OW, dy, pp)) {
             const int rc2 = permute_filters(w, wt, G, Mg, Cg, KK, 1, stream);
             if (rc2) return rc2;
@@ -613,6 +621,7 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     }
     IgemmProblem p = bwd_data_problem(d, OH, OW, dy, in_place ? w : wt, dx, accumulate);
     p.gate = gate;
+    p.math = math;
     return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
 }
 
@@ -667,14 +676,17 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
 }
 
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
-                         void *ws, size_t ws_bytes, hipStream_t stream)
+                         void *ws, size_t ws_bytes, hipStream_t stream, int math)
 {
+    if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_bwd_weight", -1);
     int OH, OW;
     const int rc = conv_check(&d, &OH, &OW);
     if (rc) return rc;
-    const IgemmProblem p = bwd_weight_problem(d, OH, OW, x, dy, dw);
-    const size_t split_bytes = round256(igemm_ws_bytes(p));
+    IgemmProblem p = bwd_weight_problem(d, OH, OW, x, dy, dw);
+    const size_t split_bytes = round256(igemm_ws_bytes(p));       // sized for the kernel the fp32 mode picks
+    p.math = math;
+    if (math != CG_MATH_FP32 && p.use_wgrad) { p.use_wgrad = 0; p.splits = 1; }    // the band kernel is fp32 only
     const size_t bias_bytes = db ? bias_grad_ws_bytes(d.N, d.M) : 0;
     if (split_bytes + bias_bytes > 0) {
         if (!ws || ws_bytes < split_bytes + bias_bytes) return CG_ENOSPC;
@@ -764,31 +776,35 @@ static IgemmProblem fc_bwd_weight_problem(int B, int IN, int OUT, const float *x
 }
 
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
-                size_t ws_bytes, int relu, hipStream_t stream)
+                size_t ws_bytes, int relu, hipStream_t stream, int math)
 {
     ProfTag tag("fc_fwd", -1);
-    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    if (B <= 0 || IN <= 0 || OUT <= 0 || !math_ok(math)) return CG_EINVAL;
     IgemmProblem p = fc_fwd_problem(B, IN, OUT, x, W, bias, y);
     p.relu = relu;
+    p.math = math;
     return igemm_run(p, ws, ws_bytes, stream);
 }
 
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, const float *gate,
-                     int accumulate, void *ws, size_t ws_bytes, hipStream_t stream)
+                     int accumulate, void *ws, size_t ws_bytes, hipStream_t stream, int math)
 {
     ProfTag tag("fc_bwd_data", -1);
-    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
+    if (B <= 0 || IN <= 0 || OUT <= 0 || !math_ok(math)) return CG_EINVAL;
     IgemmProblem p = fc_bwd_data_problem(B, IN, OUT, dy, W, dx, accumulate);
     p.gate = gate;
+    p.math = math;
     return igemm_run(p, ws, ws_bytes, stream);
 }
 
 int fc_bwd_weight_impl(int B, int IN, int OUT, const float *x, const float *dy, float *dW, float *db, void *ws,
-                       size_t ws_bytes, hipStream_t stream)
+                       size_t ws_bytes, hipStream_t stream, int math)
 {
     ProfTag tag("fc_bwd_weight", -1);
-    if (B <= 0 || IN <= 0 || OUT <= 0) return CG_EINVAL;
-    const int r = igemm_run(fc_bwd_weight_problem(B, IN, OUT, x, dy, dW), ws, ws_bytes, stream);
+    if (B <= 0 || IN <= 0 || OUT <= 0 || !math_ok(math)) return CG_EINVAL;
+    IgemmProblem pw = fc_bwd_weight_problem(B, IN, OUT, x, dy, dW);
+    pw.math = math;
+    const int r = igemm_run(pw, ws, ws_bytes, stream);
     if (r) return r;
     if (db) return fc_bias_grad_launch(dy, B, OUT, db, stream);
     return CG_OK;
@@ -883,6 +899,32 @@ extern "C" int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const f
     if (!d || !x || !dy || !dw) return CG_EINVAL;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CG_EINVAL;
     return conv_bwd_weight_impl(*d, x, dy, dw, dbias, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---- the three passes with the arithmetic of the matrix instructions chosen by the caller -----------
+
+extern "C" int cg_conv_fwd_math(const cg_conv_desc *d, const float *x, const float *w, const float *bias, float *y,
+                                void *ws, size_t ws_bytes, int math, void *stream)
+{
+    if (!d || !x || !w || !y) return CG_EINVAL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return CG_EINVAL;
+    return conv_fwd_impl(*d, x, w, bias, y, ws, ws_bytes, 0, static_cast<hipStream_t>(stream), 0, math);
+}
+
+extern "C" int cg_conv_bwd_data_math(const cg_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,
+                                     size_t ws_bytes, int math, void *stream)
+{
+    if (!d || !dy || !w || !dx) return CG_EINVAL;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return CG_EINVAL;
+    return conv_bwd_data_impl(*d, dy, w, dx, nullptr, ws, ws_bytes, 0, static_cast<hipStream_t>(stream), math);
+}
+
+extern "C" int cg_conv_bwd_weight_math(const cg_conv_desc *d, const float *x, const float *dy, float *dw, float *dbias,
+                                       void *ws, size_t ws_bytes, int math, void *stream)
+{
+    if (!d || !x || !dy || !dw) return CG_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dw)) return CG_EINVAL;
+    return conv_bwd_weight_impl(*d, x, dy, dw, dbias, ws, ws_bytes, static_cast<hipStream_t>(stream), math);
 }
 
 // ---- backward-weight without a caller's workspace ------------------------------------------------

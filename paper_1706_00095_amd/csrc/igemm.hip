@@ -20,9 +20,29 @@
 #include <utility>
 #include "cg_internal.h"
 
+// This file is compiled three times.  CG_MATH = 0 (the default) multiplies in fp32 and holds
+// everything: kernels, planning, K slices, bias gradient.  CG_MATH = 1 and 2 build only the two
+// main kernels and their launchers once more, for the bf16 matrix instructions: the tiles travel
+// and lie in LDS as fp32 exactly as before, a lane rounds its fragments to bf16 (nearest even)
+// and one v_mfma_f32_32x32x16_bf16 per accumulator multiplies a whole K-tile of 16.
+//   1 (CG_MATH_BF16):   a*b with a, b rounded to bf16, accumulated in fp32.
+//   2 (CG_MATH_BF16X3): a = ah + al, b = bh + bl (ah = bf16(a), al = bf16(a - ah)), three products
+//                       al*bh + ah*bl + ah*bh: what is dropped is al*bl, about 2^-16 of a product.
+#ifndef CG_MATH
+#define CG_MATH 0
+#endif
+#if CG_MATH == 0
+#define CG_IGEMM_LAUNCH igemm_launch
+#elif CG_MATH == 1
+#define CG_IGEMM_LAUNCH igemm_launch_bf16
+#else
+#define CG_IGEMM_LAUNCH igemm_launch_bf16x3
+#endif
+
 namespace cg {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) float lds_float;
 typedef uint32_t BufferRsrc __attribute__((ext_vector_type(4)));   // the four descriptor words of a raw buffer
 
@@ -72,6 +92,23 @@ __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int
 template <int B, int E, class F> __device__ __forceinline__ void static_for(F &&f)
 {
     static_for_impl<B>(f, std::make_integer_sequence<int, (E > B ? E - B : 0)>{});
+}
+
+// The eight fp32 fragment values a lane holds of a K-tile (k = 8*ks + 4*h + t, ks = 0..1, t = 0..3)
+// as the bf16 operand vector of v_mfma_f32_32x32x16_bf16, whose lane half h supplies k slots
+// 8h..8h+7: slot 4*ks + t.  Which k sits in which slot is immaterial as long as A and B agree.
+template <bool SPLIT>
+__device__ __forceinline__ void to_bf16(const float (&f)[KT / 8][4], bf16x8 &hi, bf16x8 &lo)
+{
+#pragma unroll
+    for (int ks = 0; ks < KT / 8; ++ks)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float x = f[ks][t];
+            const __bf16 xh = (__bf16)x;
+            hi[4 * ks + t] = xh;
+            if (SPLIT) lo[4 * ks + t] = (__bf16)(x - (float)xh);
+        }
 }
 
 // 64 lanes x 4 bytes, global memory -> LDS: lane l's element lands at lds + 4*l.  `lds` and `soff`
@@ -410,7 +447,7 @@ __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&a
 
 }  // namespace
 
-template <int WM, int WN, int TM, int TN, int NST, class LA, class LB>
+template <int WM, int WN, int TM, int TN, int NST, class LA, class LB, int MATH>
 __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
 {
     static_assert(WM * WN == 4, "four waves");
@@ -465,6 +502,35 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmProblem p)
         // whose stage the loads issued below overwrite.
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NST - 2) * LPT) : "memory");
         const float *a_s = smem + (it % NST) * STAGE, *b_s = a_s + LA::SZ;
+        if constexpr (MATH != 0) {
+            // bf16 matrix instructions: all fragments of the tile, rounded (and split), one MFMA per
+            // accumulator and product, then the next tile's loads
+            float af[TM][KT / 8][4], bf[TN][KT / 8][4];
+#pragma unroll
+            for (int ks = 0; ks < KT / 8; ++ks) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[i][ks]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) LB::frag(b_s, (wn * TN + j) * 32 + li, ks, h, bf[j][ks]);
+            }
+            bf16x8 ah[TM], al[TM], bh[TN], bl[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) to_bf16<MATH == 2>(af[i], ah[i], al[i]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) to_bf16<MATH == 2>(bf[j], bh[j], bl[j]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (MATH == 2) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+                    }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+                }
+            static_for<0, NPART>([&](auto PC) { issue_part(PC, it + NST - 1); });
+            continue;
+        }
         float af[KT / 8][TM][4], bf[KT / 8][TN][4];
         // the fragments of the tile's first eight k now, those of the second eight behind the first
         // MFMA step: half the reads are waited for at the start of a tile
@@ -527,7 +593,7 @@ template <int NSL, int PAD = 8> struct PatchB {
     static constexpr int NB = 4 * NSL;               // load instructions per wave and channel block
 };
 
-template <int WM, int WN, int TM, int TN, int NSTA, int NSL>
+template <int WM, int WN, int TM, int TN, int NSTA, int NSL, int MATH>
 __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem p)
 {
     static_assert(WM * WN == 4 && WN * TN == 4, "four waves, 128 pixels per block");
@@ -653,6 +719,42 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
         const float *a_s = smem + (it % NSTA) * LA::SZ;
         const int py = pg.flip ? pg.KH - 1 - cky : cky, px = pg.flip ? pg.KW - 1 - ckx : ckx;
         const float *b_s = sB + (ccb & 1) * PB::BUF + (py * pg.Wp + px);
+        if constexpr (MATH != 0) {
+            float af[TM][KT / 8][4], bf[TN][KT / 8][4];
+#pragma unroll
+            for (int ks = 0; ks < KT / 8; ++ks) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) LA::frag(a_s, (wm * TM + i) * 32 + li, ks, h, af[i][ks]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) bf[j][ks][t] = b_s[sig[j] + (8 * ks + t) * PB::CS];
+            }
+            bf16x8 ah[TM], al[TM], bh[TN], bl[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) to_bf16<MATH == 2>(af[i], ah[i], al[i]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) to_bf16<MATH == 2>(bf[j], bh[j], bl[j]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (MATH == 2) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+                    }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+                }
+            const bool do_patch_b = burst && ct == 0;
+            static_for<0, NPART>([&](auto PC) {
+                issue_a_part(PC, it + NSTA - 1, icb, it_);
+                if (do_patch_b) issue_patch_part(PC, ccb + 1);
+            });
+            advance_issue();
+            if (++ckx == pg.KW) { ckx = 0; ++cky; }
+            if (++ct == KK) { ct = 0; cky = 0; ++ccb; }
+            continue;
+        }
         float af[KT / 8][TM][4], bf[KT / 8][TN][4];
         // Fragments are read one MFMA step ahead (A once per eight k, B per step): only the first step's
         // reads are waited for at the start of a tile, the others arrive while the matrix pipeline works.
@@ -693,6 +795,7 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_kernel(const IgemmProblem 
                        smem + wave * EpiLds<TN>::FLOATS);
 }
 
+#if CG_MATH == 0
 // ---- patch kernel for at most 48 rows ------------------------------------------------------------
 //
 // The same data movement as igemm_patch_kernel, multiplied with v_mfma_f32_16x16x4_f32: a block
@@ -1083,6 +1186,8 @@ __global__ __launch_bounds__(256, 2) void igemm_wgrad_kernel(const IgemmProblem 
                        smem + wave * EpiLds<TN>::FLOATS);
 }
 
+#endif  // CG_MATH == 0
+
 namespace {
 
 template <int WM, int WN, int TM, int TN, int NST, class LA, class LB>
@@ -1094,7 +1199,7 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
     int rec = -1;
     if (prof_on()) {
         char name[64];
-        snprintf(name, sizeof name, "igemm_kernel<%dx%d,%s>", MT, NT, modes);
+        snprintf(name, sizeof name, CG_MATH == 0 ? "igemm_kernel<%dx%d,%s>" : CG_MATH == 1 ? "igemm_kernel<%dx%d,%s,bf16>" : "igemm_kernel<%dx%d,%s,bf16x3>", MT, NT, modes);
         rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = (size_t)NST * (LA::SZ + LB::SZ) * sizeof(float);
@@ -1102,11 +1207,11 @@ int launch_cfg(const IgemmProblem &p, const char *modes, hipStream_t stream)
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
     static std::atomic<bool> attr_set{false};      // raising the dynamic-LDS limit: once per kernel (repeating it is harmless)
     if (!attr_set.load(std::memory_order_acquire)) {
-        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_kernel<WM, WN, TM, TN, NST, LA, LB>),
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_kernel<WM, WN, TM, TN, NST, LA, LB, CG_MATH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, NST, LA, LB>), grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL((igemm_kernel<WM, WN, TM, TN, NST, LA, LB, CG_MATH>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
@@ -1237,7 +1342,7 @@ int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
     int rec = -1;
     if (prof_on()) {
         char name[64];
-        snprintf(name, sizeof name, "igemm_patch_kernel<%dx128,%d>", MT, NSL);
+        snprintf(name, sizeof name, CG_MATH == 0 ? "igemm_patch_kernel<%dx128,%d>" : CG_MATH == 1 ? "igemm_patch_kernel<%dx128,%d,bf16>" : "igemm_patch_kernel<%dx128,%d,bf16x3>", MT, NSL);
         rec = prof_begin(name, p.flops > 0 ? p.flops : 2.0 * p.M * (double)p.N * p.K * p.groups, 0.0, stream);
     }
     constexpr size_t lds = ((size_t)NSTA * LA::SZ + 2 * PatchB<NSL>::BUF) * sizeof(float);
@@ -1245,16 +1350,17 @@ int launch_patch_cfg(const IgemmProblem &p, hipStream_t stream)
     static_assert(2 * lds <= 160 * 1024, "two blocks of this tile do not fit the LDS of a compute unit");
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL>),
+        CG_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL, CG_MATH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL>), grid, dim3(256), lds, stream, p);
+    hipLaunchKernelGGL((igemm_patch_kernel<2, 2, TM, 2, NSTA, NSL, CG_MATH>), grid, dim3(256), lds, stream, p);
     prof_end(rec, stream);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }
 
+#if CG_MATH == 0
 template <int TM, int NSTA, int NSL>
 int launch_patch16_cfg(const IgemmProblem &p, hipStream_t stream)
 {
@@ -1282,6 +1388,8 @@ int launch_patch16_cfg(const IgemmProblem &p, hipStream_t stream)
     return CG_OK;
 }
 
+#endif
+
 // row-tile height of the patch kernel: 64, 128 or 192 rows
 int patch_mt(uint32_t M, uint32_t N, uint32_t groups)
 {
@@ -1307,6 +1415,7 @@ int patch_launch_tiles(const IgemmProblem &p, int mt, hipStream_t stream)
 
 int patch_launch(const IgemmProblem &p, hipStream_t stream)
 {
+#if CG_MATH == 0
     if (p.M <= 48) {             // the 16-row tiles waste less of a small row count than a 64-row tile
         const int tm = (int)(p.M + 15) / 16;
         if (p.patch.nsl == 4)
@@ -1318,6 +1427,7 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
         return tm == 3 ? launch_patch16_cfg<3, 4, 5>(p, stream) : tm == 2 ? launch_patch16_cfg<2, 4, 5>(p, stream)
                                                                           : launch_patch16_cfg<1, 4, 5>(p, stream);
     }
+#endif
     int mt = patch_mt(p.M, p.N, p.groups);
     // six chunks: no 192-row instance; 128-row tiles unless they would pad the rows by half a tile or more
     if (p.patch.nsl == 6 && mt > 64) mt = (p.M + 127) / 128 * 128 - p.M >= 64 ? 64 : 128;
@@ -1355,6 +1465,7 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
 
 }  // namespace
 
+#if CG_MATH == 0
 namespace {
 
 template <int TM, int NSTA, int CPB, int NSL>
@@ -1539,13 +1650,23 @@ void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, int64_t *of
     *off = (int64_t)r.off + q.off + op.shift;
 }
 
-int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
+#endif  // CG_MATH == 0
+
+int CG_IGEMM_LAUNCH(const IgemmProblem &p0, hipStream_t stream)
 {
+#if CG_MATH == 0
+    if (p0.math == CG_MATH_BF16) return igemm_launch_bf16(p0, stream);
+    if (p0.math == CG_MATH_BF16X3) return igemm_launch_bf16x3(p0, stream);
+    if (p0.math != CG_MATH_FP32) return CG_EINVAL;
+#endif
     IgemmProblem p = p0;
     if (!p.c_ptr || !aligned16(p.c_ptr)) return CG_EINVAL;
     if (p.M == 0 || p.N == 0 || p.K == 0 || p.groups == 0 || p.splits == 0) return CG_EINVAL;
     if (p.M >= (1u << 30) || p.N >= (1u << 30) || p.K >= (1u << 30)) return CG_EUNSUPPORTED;
     if (p.bias_mode && !p.bias) return CG_EINVAL;
+#if CG_MATH != 0
+    if (p.use_wgrad) return CG_EUNSUPPORTED;      // the band kernel multiplies in fp32 only
+#else
     if (p.use_wgrad) {         // K slices are whole units here, not k ranges
         if (!p.wgrad.x || !aligned16(p.wgrad.x) || p.wgrad.cpb == 0 || p.A.check) return CG_EINVAL;
         p.A.shift = 0;
@@ -1553,6 +1674,7 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
         if (rcw) return rcw;
         return wgrad_launch(p, stream);
     }
+#endif
     if (p.splits > 1 && (p.k_per_split % KT != 0)) return CG_EINVAL;
     if ((uint64_t)p.k_per_split * p.splits < p.K || (uint64_t)p.k_per_split * (p.splits - 1) >= p.K) return CG_EINVAL;
     if (p.bias_mode && !p.bias) return CG_EINVAL;
@@ -1590,6 +1712,7 @@ int igemm_launch(const IgemmProblem &p0, hipStream_t stream)
     return CG_EUNSUPPORTED;
 }
 
+#if CG_MATH == 0
 // ---- split-K: more blocks for problems whose C has few tiles ---------------------------------
 
 namespace {
@@ -1837,5 +1960,7 @@ int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, 
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
 }
+
+#endif  // CG_MATH == 0
 
 }  // namespace cg

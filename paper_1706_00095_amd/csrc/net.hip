@@ -338,6 +338,8 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
     if (ws_bytes < net->ws_floats * sizeof(float)) return CG_ENOSPC;
     if (!aligned16(ws) || !aligned16(x)) return CG_EINVAL;
     const bool serial = (flags & CG_STEP_SERIAL) != 0;
+    if ((flags & CG_STEP_BF16) && (flags & CG_STEP_BF16X3)) return CG_EINVAL;
+    const int math = (flags & CG_STEP_BF16) ? CG_MATH_BF16 : (flags & CG_STEP_BF16X3) ? CG_MATH_BF16X3 : CG_MATH_FP32;
     hipStream_t S0 = static_cast<hipStream_t>(compute_stream);
     hipStream_t S1 = serial ? S0 : static_cast<hipStream_t>(update_stream);
     if (!serial && S0 == S1) return CG_EINVAL;
@@ -380,11 +382,11 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         switch (d.kind) {
         case CG_LAYER_CONV:
             rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, ly.fused_relu, S0,
-                               ly.out_img_stride);
+                               ly.out_img_stride, math);
             break;
         case CG_LAYER_FC:
             rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, scratch,
-                             scratch_bytes, ly.fused_relu, S0);
+                             scratch_bytes, ly.fused_relu, S0, math);
             break;
         case CG_LAYER_RELU:
             if (ly.alias_of < 0) rc = relu_fwd_launch(in, out, in_elems, S0);
@@ -495,14 +497,14 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             }
             const int IN = ly.inC * ly.inH * ly.inW;
             if (d.kind == CG_LAYER_CONV)
-                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2);
+                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
             else
-                rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2);
+                rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
             if (rc == CG_OK && want_dx) {
                 if (d.kind == CG_LAYER_CONV)
-                    rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0);
+                    rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0, math);
                 else
-                    rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0);
+                    rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0, math);
             }
             break;
         }

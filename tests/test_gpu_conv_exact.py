@@ -66,20 +66,20 @@ def _logged(fn):
     return out, names
 
 
-def _all_three(orc32, B, cfg, seed, fwd=True, bwd_data=True, bwd_weight=True):
+def _all_three(orc32, B, cfg, seed, fwd=True, bwd_data=True, bwd_weight=True, math=None):
     c, x, w, b, dy = cg_synth.conv_layer_int_tensors(cfg, B, seed)
     d, od = _descs(B, c)
     names = []
     if fwd:
-        y, n = _logged(lambda: host(conv_fwd(d, dev(x), dev(w), dev(b))))
+        y, n = _logged(lambda: host(conv_fwd(d, dev(x), dev(w), dev(b), math)))
         names += n
         _same(y, orc32.conv_fwd(od, x, w, b), "forward")
     if bwd_data:
-        dx, n = _logged(lambda: host(conv_bwd_data(d, dev(dy), dev(w))))
+        dx, n = _logged(lambda: host(conv_bwd_data(d, dev(dy), dev(w), math)))
         names += n
         _same(dx, orc32.conv_bwd_data(od, dy, w), "backward-data")
     if bwd_weight:
-        (dw, db), n = _logged(lambda: tuple(host(t) for t in conv_bwd_weight(d, dev(x), dev(dy))))
+        (dw, db), n = _logged(lambda: tuple(host(t) for t in conv_bwd_weight(d, dev(x), dev(dy), math)))
         names += n
         rdw, rdb = orc32.conv_bwd_weight(od, x, dy)
         _same(dw, rdw, "backward-weight")

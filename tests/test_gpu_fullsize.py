@@ -1,10 +1,11 @@
 """Parity at the benchmark's real sizes, in the launch configuration bench.py times.
 
-The oracle cannot run a whole AlexNet-shaped iteration at B=256 in test time, so:
- - the three fully-connected layers run at B=256 as their own net (oracle: seconds);
- - the whole AlexNet-shaped net runs at B=16 against the oracle element by element;
- - each AlexNet convolution layer at B=256 is checked on sampled outputs the oracle's
-   definition gives one by one, and through the adjoint identities, which hold at any size.
+ - the whole AlexNet-shaped net at B = 16, 64 and 256 (the benchmark's workload; the oracle needs
+   about half a minute for it) against the oracle element by element;
+ - the three fully-connected layers at B=256 as their own net;
+ - each AlexNet convolution layer at B=256 on sampled outputs the oracle's definition gives one by
+   one, and through the adjoint identities, which hold at any size (every element of these layers is
+   compared in test_gpu_conv_exact.py, on integer inputs).
 """
 import numpy as np
 import pytest
@@ -50,9 +51,9 @@ def _backward_state_from_gpu_forward(orc32, gn, layers, t, acts):
     return acts_g, aux_g
 
 
-def _check_step(orc32, layers, in_shape, B, t):
+def _check_step(orc32, layers, in_shape, B, t, flags=0):
     gn = GpuNet(layers, in_shape, B, t)
-    gn.step(SGD)
+    gn.step(SGD, flags)
     gn.sync()
     buckets = {k: v.copy() for k, v in t["buckets"].items()}
     loss, acts, aux = onet.forward(orc32, layers, t["x"], buckets, t["labels"], t["masks"])
