@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 # context only (other hardware, full AlexNet on ImageNet, paper Table 1): seconds per iteration, B=256
 PAPER_ALEXNET_S_PER_ITER = {"P100": 0.1, "K80": 0.9, "KNL": 0.6, "CPU": 2.0}
@@ -124,7 +125,7 @@ def hbm_achievable(cg, torch, reps=20):
     return out
 
 
-def conv_layers_standalone(cg, torch, B, reps=10):
+def conv_layers_standalone(cg, torch, B, reps=10, math=0):
     """Configuration 2: every AlexNet-shaped convolution layer alone, forward / backward-data /
     backward-weight through the C ABI (the first layer's backward-data included, which a net skips),
     TFLOP/s of useful work 2*M*N*K*groups over the mean of `reps` back-to-back calls."""
@@ -143,9 +144,12 @@ def conv_layers_standalone(cg, torch, B, reps=10):
         y, dx, dw, db = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w), torch.empty_like(b)
         ws = [torch.empty(max(cg.cg_conv_workspace_bytes(d, p), 16), dtype=torch.uint8, device="cuda") for p in range(3)]
         flop = 2.0 * c["M"] * Cg * c["k"] ** 2 * B * OH * OW
-        calls = {"fwd": lambda: cg.cg_conv_fwd(d, x, w, b, y, ws[0]),
-                 "bwd_data": lambda: cg.cg_conv_bwd_data(d, dy, w, dx, ws[1]),
-                 "bwd_weight": lambda: cg.cg_conv_bwd_weight(d, x, dy, dw, db, ws[2])}
+        calls = {"fwd": lambda: cg.cg_conv_fwd_math(d, x, w, b, y, ws[0], math),
+                 "bwd_data": lambda: cg.cg_conv_bwd_data_math(d, dy, w, dx, ws[1], math),
+                 "bwd_weight": lambda: cg.cg_conv_bwd_weight_math(d, x, dy, dw, db, ws[2], math)}
+        # the least a pass must move through HBM: its two operand tensors read once, its result written once
+        nbytes = {"fwd": 4.0 * (x.numel() + w.numel() + dy.numel()), "bwd_data": 4.0 * (x.numel() + w.numel() + dy.numel()),
+                  "bwd_weight": 4.0 * (x.numel() + w.numel() + dy.numel())}
         res = {}
         for ps, fn in calls.items():
             fn(); fn()
@@ -157,10 +161,50 @@ def conv_layers_standalone(cg, torch, B, reps=10):
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / reps
-            res[ps] = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1)}
+            res[ps] = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1),
+                       "hbm_floor_ms": round(nbytes[ps] / PEAK_HBM_GBS / 1e6, 4)}
         out[name] = res
     out["what"] = (f"B={B}, each pass alone on the GPU through cg_conv_fwd / cg_conv_bwd_data / cg_conv_bwd_weight (filter "
                    "permutation, K-slice sums and bias gradient included in the time), useful FLOP = 2*M*N*K*groups")
+    return out
+
+
+def reduced_precision(cg, torch, B, K, sgd, steps=30):
+    """The optional bf16 matrix-core modes, chosen explicitly (CG_STEP_BF16: operands rounded to bf16,
+    parity bound 2e-2; CG_STEP_BF16X3: operands split into two bf16 numbers, three products, inside the
+    fp32 parity bound): the same AlexNet-shaped step and the same stand-alone layers.  Separate lines:
+    the headline stays fp32.  Rooflines: the dense bf16 matrix peak (a third of it per useful product
+    in the three-product mode), or the HBM floor of the pass where that is the longer time."""
+    out = {}
+    for tag, flag, math, peak in (("bf16", cg.CG_STEP_BF16, cg.CG_MATH_BF16, PEAK_BF16_MFMA_TFLOPS),
+                                  ("bf16x3", cg.CG_STEP_BF16X3, cg.CG_MATH_BF16X3, PEAK_BF16_MFMA_TFLOPS / 3)):
+        st = build_net(cg, torch, B, K, seed=4, n_batches=min(32, steps + 5))
+        torch.cuda.synchronize()
+        run_steps(cg, torch, st, sgd, 5, flag)
+        sync(torch, st)
+        t0 = time.perf_counter()
+        run_steps(cg, torch, st, sgd, steps, flag)
+        sync(torch, st)
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        loss = float(st["loss"].cpu()[0])
+        del st
+        torch.cuda.empty_cache()
+        layers = conv_layers_standalone(cg, torch, B, math=math)
+        best = None
+        for name, v in layers.items():
+            if name == "what":
+                continue
+            for ps, r in v.items():
+                flop = r["tflops"] * r["ms"] * 1e9
+                mfma_ms = flop / peak / 1e9
+                r["bound"] = "hbm" if r["hbm_floor_ms"] > mfma_ms else "mfma"
+                r["frac"] = round(max(mfma_ms, r["hbm_floor_ms"]) / r["ms"], 3)
+                if best is None or r["tflops"] > best[1]["tflops"]:
+                    best = (f"{name}.{ps}", r)
+        out[tag] = {"workload": f"alexnet_shaped_train_step_B{B}_K{K}", "dtype": tag, "ms_per_step": ms,
+                    "images_per_s": B / (ms * 1e-3), "steps": steps, "loss": loss,
+                    "matrix_peak_tflops": round(peak, 1), "conv_layers_standalone": layers,
+                    "fastest_pass": {"pass": best[0], **best[1]}}
     return out
 
 
@@ -472,9 +516,10 @@ def main():
 
     # ---- configuration 2 stand-alone (every layer's three passes, the first layer's backward-data included)
     # and the other per-worker batch configuration 4 names (B = 64), as context beside the headline
-    layer_bench = b64 = None
+    layer_bench = b64 = reduced = None
     if not args.skip_layer_bench and not args.serial:
         layer_bench = conv_layers_standalone(cg, torch, B)
+        reduced = reduced_precision(cg, torch, B, K, sgd)
         if B != 64:
             st64 = build_net(cg, torch, 64, K, seed=4, n_batches=16)
             torch.cuda.synchronize()
@@ -516,6 +561,7 @@ def main():
         "hbm_achievable": achievable,
         "conv_layers_standalone": layer_bench,
         "alexnet_b64_step": b64,
+        "reduced_precision": reduced,
         "inception_step": inception,
         "googlenet_step": googlenet,
         "cpu_baseline": cpu,

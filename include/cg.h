@@ -224,7 +224,9 @@ long long cg_net_param_count(const cg_net *net, int layer);
  *  2: the gradient with respect to the layer's output.  The backward of a
  *     rectifier whose only consumer is a convolution, fully-connected, LRN,
  *     max-pool or dropout layer is folded into that consumer's backward kernel,
- *     which writes the gradient of the rectifier's input directly. */
+ *     which writes the gradient of the rectifier's input directly.
+ * An LRN layer whose only consumer is a max-pool runs fused with it in forward
+ * and reports bit 1: its output is never written. */
 int cg_net_layer_fused(const cg_net *net, int layer);
 
 /* Attach the caller-owned buffers of a parameter layer: model w, history v,

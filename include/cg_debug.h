@@ -66,6 +66,15 @@ int cg_profile_enable(int on);
 int cg_profile_count(void);
 int cg_profile_get(int i, cg_profile_record *out);
 
+/* How nets created from now on run an LRN layer whose only consumer is a
+ * max-pool.  mode 0: two kernels per direction.  mode 1 (the default): forward
+ * as one kernel, the LRN's output is not materialised (cg_net_layer_fused
+ * reports 1 for that LRN layer).  mode 3: backward as one kernel as well,
+ * neither the LRN's output nor the gradient with respect to it exists
+ * (reports 3); built and tested, slower than the two kernels it replaces.
+ * Process-wide. */
+int cg_debug_fuse_lrn_pool(int mode);
+
 /* Measurement aid: the streaming rates the memory system reaches with the
  * simplest possible kernels, to quote beside the published peak.  mode 0:
  * dst[i] = src[i]; mode 1: read src only (dst receives one float4 if the sum

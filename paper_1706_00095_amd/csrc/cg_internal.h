@@ -250,6 +250,14 @@ int lrn_fwd_launch(const float *x, float *y, int N, int C, int HW, int size, flo
 // recomputes the scales from x; nothing saved by forward is read
 int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int HW, int size, float alpha, float beta,
                    float kappa, int accumulate, int gate, hipStream_t st);
+// LRN followed by max-pooling in one pass (neither the normalised tensor nor its gradient is
+// materialised); lrn_pool_fusable says whether the fused kernels take a layer pair
+bool lrn_pool_fusable(int C, int H, int W, int size, int k, int s, int p);
+int lrn_pool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, int H, int W, int size, float alpha,
+                        float beta, float kappa, int k, int s, int p, hipStream_t st);
+int lrn_pool_bwd_launch(const float *x, const float *dpool, const int32_t *argmax, float *dx, int N, int C, int H, int W,
+                        int size, float alpha, float beta, float kappa, int k, int s, int p, int accumulate, int gate,
+                        hipStream_t st);
 int avgpool_fwd_launch(const float *x, float *y, int NC, int HW, hipStream_t st);
 int avgpool_bwd_launch(const float *dy, float *dx, int NC, int HW, int accumulate, hipStream_t st);
 int dropout_launch(const float *x, const uint8_t *mask, float *y, const float *gate, size_t n, float p, int accumulate,

@@ -552,6 +552,248 @@ __global__ __launch_bounds__(TB) void lrn_bwd_stream_kernel(const float *__restr
     }
 }
 
+// ---- LRN followed by max-pooling, in one pass -----------------------------------------------------
+// The normalised tensor is the largest of an AlexNet-shaped net (the first layer's 96 x 55 x 55 per
+// image) and exists only to be pooled: written once by the LRN, read once by the pool, and in
+// backward its gradient is written by the pool and read by the LRN.  Fused, neither it nor its
+// gradient touches memory.  A block owns one image, LP_CH channels (plus the window's halo) and a
+// band of rows of at most 4 x 256 pixels, and walks along the channels like the stream kernels
+// above, a thread holding four consecutive pixels, so that the band of the current channel is in
+// the block:
+//   forward:  a band is the input rows that `prb` pooled rows need (neighbouring bands share the
+//             k - s rows their windows overlap in); the band of y = x * scale^-beta goes to LDS (two
+//             buffers, one barrier per channel) and is pooled from there: only the pooled values
+//             and the winners are written;
+//   backward: a band is `hrb` input rows; the pooled rows of dy and of the winners that cover it
+//             are staged in LDS, a pixel collects the dy of the windows that elected it (ascending
+//             window order, as maxpool_bwd_kernel does) and feeds it to the LRN backward recurrence
+//             of lrn_bwd_stream_kernel.
+// The arithmetic is that of the separate kernels, operation for operation: same y, same winners.
+constexpr int LP_CH = 32;
+constexpr int LP_NP = 4;          // staged pooled elements per thread (at most LP_NP * TB a band)
+
+// LDS writes of this wave have landed, then the block's barrier.  Unlike __syncthreads() this does
+// not wait for the global loads in flight: the next channel's loads are issued before the barrier
+// and must stay in flight across it, or every step would run at the latency of HBM.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// KT, ST: window and stride when known at compile time (0 = run-time values); INSIDE: no window
+// reaches beyond the plane (no padding, the last window ends inside), so no tap needs a range test
+template <int SIZE, int KT, int ST, bool INSIDE>
+__global__ __launch_bounds__(TB) void lrn_pool_fwd_kernel(const float *__restrict__ x, float *__restrict__ yp,
+                                                          int32_t *__restrict__ argmax, int C, int H, int W, int OH, int OW,
+                                                          int k_rt, int s_rt, int p, int nchunk, int nbands, int prb, float aos,
+                                                          float beta, float kappa, FastDiv divOW)
+{
+    const int k = KT ? KT : k_rt, s = ST ? ST : s_rt;
+    extern __shared__ __align__(16) float lp_lds[];          // [2][4 * TB]
+    constexpr int half = (SIZE - 1) / 2, LB = LRN_V * TB;
+    const int HW = H * W, P = OH * OW;
+    int bi = blockIdx.x;
+    const int band = bi % nbands; bi /= nbands;
+    const int n = bi / nchunk, c0 = (bi % nchunk) * LP_CH, c1 = min(C, c0 + LP_CH);
+    const int pr0 = band * prb, pr1 = min(OH, pr0 + prb);
+    const int ih0 = max(0, pr0 * s - p), ih1 = min(H, (pr1 - 1) * s - p + k);
+    const int base = ih0 * W, lim = ih1 * W;                 // the band's pixels in the plane
+    const float *xn = x + (size_t)n * C * HW;
+    const int loc = (int)threadIdx.x * LRN_V, pix = base + loc, rem = lim - pix;
+    auto load_x = [&](int cc) {
+        return (rem > 0 && cc >= 0 && cc < C) ? px_load(xn + (size_t)cc * HW + pix, rem) : px_zero();
+    };
+    Px4 win[SIZE], nxt;             // nxt: the channel that enters the window in the coming step, loaded a step ahead
+#pragma unroll
+    for (int d = 0; d < SIZE - 1; ++d) win[d + 1] = load_x(c0 - half + d);
+    nxt = load_x(c0 - half + SIZE - 1);
+    int buf = 0;
+    for (int c = c0; c < c1; ++c) {
+        float *ys = lp_lds + buf * LB;
+        const int e = c - half + SIZE - 1;
+#pragma unroll
+        for (int d = 0; d < SIZE - 1; ++d) win[d] = win[d + 1];
+        win[SIZE - 1] = nxt;
+        nxt = c + 1 < c1 ? load_x(e + 1) : px_zero();
+        if (rem > 0) {
+            float out[LRN_V];
+#pragma unroll
+            for (int v = 0; v < LRN_V; ++v) {
+                float ss = 0.f;
+#pragma unroll
+                for (int d = 0; d < SIZE; ++d) ss += win[d].v[v] * win[d].v[v];
+                out[v] = win[half].v[v] * pow_neg(kappa + aos * ss, beta);
+            }
+            *reinterpret_cast<float4 *>(ys + loc) = make_float4(out[0], out[1], out[2], out[3]);   // beyond rem: never read
+        }
+        lds_barrier();          // the band is complete; the other buffer's readers of two channels ago are done too
+        const size_t obase = ((size_t)n * C + c) * P;
+        for (int o = pr0 * OW + (int)threadIdx.x; o < pr1 * OW; o += TB) {
+            const int oh = (int)fdiv((uint32_t)o, divOW), ow = o - oh * OW;
+            int best = -1;
+            float bv = 0.f;
+            if constexpr (INSIDE && KT > 0) {
+                const int org = oh * s * W + ow * s;          // p = 0: the window's first element
+                const float *yw = ys + org - base;
+                best = org; bv = yw[0];
+#pragma unroll
+                for (int kh = 0; kh < KT; ++kh)
+#pragma unroll
+                    for (int kw = 0; kw < KT; ++kw) {
+                        if (kh == 0 && kw == 0) continue;
+                        const float val = yw[kh * W + kw];
+                        if (val > bv) { best = org + kh * W + kw; bv = val; }
+                    }
+            } else {
+                for (int kh = 0; kh < k; ++kh) {
+                    const int ih = oh * s - p + kh;
+                    if (ih < 0 || ih >= H) continue;
+                    for (int kw = 0; kw < k; ++kw) {
+                        const int iw = ow * s - p + kw;
+                        if (iw < 0 || iw >= W) continue;
+                        const float val = ys[ih * W + iw - base];
+                        if (best < 0 || val > bv) { best = ih * W + iw; bv = val; }
+                    }
+                }
+            }
+            yp[obase + o] = bv;
+            argmax[obase + o] = best;
+        }
+        buf ^= 1;
+    }
+}
+
+template <int SIZE, int ACC, int GATE>
+__global__ __launch_bounds__(TB) void lrn_pool_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dpool,
+                                                          const int32_t *__restrict__ argmax, float *__restrict__ dx, int C,
+                                                          int H, int W, int OH, int OW, int k, int s, int p, int nchunk,
+                                                          int nbands, int hrb, float aos, float coef, float beta,
+                                                          float kappa, FastDiv divW, FastDiv divS)
+{
+    extern __shared__ __align__(16) float lp_lds[];          // [2][LP_NP * TB] pooled dy, then the same of winners
+    constexpr int half = (SIZE - 1) / 2, LS = LP_NP * TB;
+    const int HW = H * W, P = OH * OW;
+    float *dps = lp_lds;
+    int32_t *ams = reinterpret_cast<int32_t *>(lp_lds + 2 * LS);
+    int bi = blockIdx.x;
+    const int band = bi % nbands; bi /= nbands;
+    const int n = bi / nchunk, c0 = (bi % nchunk) * LP_CH, c1 = min(C, c0 + LP_CH);
+    const int h0 = band * hrb, h1 = min(H, h0 + hrb);
+    // pooled rows with a window on the band's rows
+    const int a_lo = h0 + p - k + 1;
+    const int oh_lo = a_lo > 0 ? (int)fdiv((uint32_t)(a_lo + s - 1), divS) : 0;
+    const int oh_hi = min(OH - 1, (int)fdiv((uint32_t)(h1 - 1 + p), divS));
+    const int sbase = oh_lo * OW, scount = max(0, (oh_hi - oh_lo + 1) * OW);
+    const size_t img = (size_t)n * C * HW;
+    const float *xn = x + img;
+    float *dn = dx + img;
+    const int pix = h0 * W + (int)threadIdx.x * LRN_V, rem = h1 * W - pix;
+    // the windows that cover each of the thread's pixels: first window row / column and how many
+    // (at most ceil(k/s) a dimension), packed: oh0 | noh << 12 | ow0 << 16 | now << 28
+    uint32_t cover[LRN_V];
+#pragma unroll
+    for (int v = 0; v < LRN_V; ++v) {
+        const int q = min(pix + v, HW - 1);
+        const int h = (int)fdiv((uint32_t)q, divW), w = q - h * W;
+        const int a_h = h + p - k + 1, a_w = w + p - k + 1;
+        const int oh0 = a_h > 0 ? (int)fdiv((uint32_t)(a_h + s - 1), divS) : 0, oh1 = min(OH - 1, (int)fdiv((uint32_t)(h + p), divS));
+        const int ow0 = a_w > 0 ? (int)fdiv((uint32_t)(a_w + s - 1), divS) : 0, ow1 = min(OW - 1, (int)fdiv((uint32_t)(w + p), divS));
+        const int noh = max(0, oh1 - oh0 + 1), now = max(0, ow1 - ow0 + 1);
+        cover[v] = (uint32_t)oh0 | ((uint32_t)noh << 12) | ((uint32_t)ow0 << 16) | ((uint32_t)now << 28);
+    }
+    auto load_x = [&](int cc) {
+        return (rem > 0 && cc >= 0 && cc < C) ? px_load(xn + (size_t)cc * HW + pix, rem) : px_zero();
+    };
+    // the staged part of channel jj's pooled plane (dy and winners), this thread's elements, into registers
+    float pd[LP_NP];
+    int32_t pa[LP_NP];
+    auto load_plane = [&](int jj) {
+        const size_t pb = ((size_t)n * C + jj) * P + sbase;
+#pragma unroll
+        for (int u = 0; u < LP_NP; ++u) {
+            const int o = u * TB + (int)threadIdx.x;
+            if (o < scount) { pd[u] = dpool[pb + o]; pa[u] = argmax[pb + o]; }
+        }
+    };
+    Px4 win[SIZE], tr[SIZE], q[half + 1], nxt;
+#pragma unroll
+    for (int d = 0; d < SIZE; ++d) tr[d] = px_zero();
+#pragma unroll
+    for (int d = 0; d <= half; ++d) q[d] = px_zero();
+    const int cs = c0 - (SIZE - 1);
+#pragma unroll
+    for (int d = 0; d < SIZE - 1; ++d) win[d + 1] = load_x(cs + d);
+    nxt = load_x(cs + SIZE - 1);
+    if (cs + half >= 0 && cs + half < C) load_plane(cs + half);
+    int buf = 0;
+    for (int c = cs; c < c1; ++c) {
+        const int e = c + SIZE - 1, j = c + half;
+        const bool have_j = j >= 0 && j < C;                   // uniform over the block
+        if (have_j) {
+            // channel j's pooled rows, loaded during the previous step, go to LDS
+#pragma unroll
+            for (int u = 0; u < LP_NP; ++u) {
+                const int o = u * TB + (int)threadIdx.x;
+                if (o < scount) { dps[buf * LS + o] = pd[u]; ams[buf * LS + o] = pa[u]; }
+            }
+            lds_barrier();      // staged; the other buffer's readers of the step before are done too
+        }
+        // what the next step needs from memory, a step ahead
+        if (c + 1 < c1 && j + 1 >= 0 && j + 1 < C) load_plane(j + 1);
+#pragma unroll
+        for (int d = 0; d < SIZE - 1; ++d) { win[d] = win[d + 1]; tr[d] = tr[d + 1]; }
+#pragma unroll
+        for (int d = 0; d < half; ++d) q[d] = q[d + 1];
+        win[SIZE - 1] = nxt;
+        nxt = c + 1 < c1 ? load_x(e + 1) : px_zero();
+        if (rem > 0) {
+            Px4 t = px_zero(), qq = px_zero();
+            if (have_j) {
+                const float *dp = dps + buf * LS - sbase;
+                const int32_t *am = ams + buf * LS - sbase;
+#pragma unroll
+                for (int v = 0; v < LRN_V; ++v) {
+                    // the gradient of the LRN output at this pixel: dy of the windows that elected it
+                    float gsum = 0.f;
+                    if (v < rem) {
+                        const uint32_t cv = cover[v];
+                        const int oh0 = (int)(cv & 0xfffu), noh = (int)((cv >> 12) & 0xfu);
+                        const int ow0 = (int)((cv >> 16) & 0xfffu), now = (int)(cv >> 28);
+                        const int me = pix + v;
+                        for (int a = 0; a < noh; ++a)
+                            for (int b = 0; b < now; ++b) {
+                                const int o = (oh0 + a) * OW + ow0 + b;
+                                if (am[o] == me) gsum += dp[o];
+                            }
+                    }
+                    float ss = 0.f;
+#pragma unroll
+                    for (int d = 0; d < SIZE; ++d) ss += win[d].v[v] * win[d].v[v];
+                    const float sc = kappa + aos * ss, pw = pow_neg(sc, beta);
+                    qq.v[v] = gsum * pw;
+                    t.v[v] = qq.v[v] * win[half].v[v] / sc;
+                }
+            }
+            tr[SIZE - 1] = t;
+            q[half] = qq;
+            if (c >= c0) {
+                Px4 out;
+#pragma unroll
+                for (int v = 0; v < LRN_V; ++v) {
+                    float cross = 0.f;
+#pragma unroll
+                    for (int d = 0; d < SIZE; ++d) cross += tr[d].v[v];
+                    float gval = q[0].v[v] - coef * win[0].v[v] * cross;
+                    if (GATE && !(win[0].v[v] > 0.f)) gval = 0.f;
+                    out.v[v] = gval;
+                }
+                px_store<ACC>(dn + (size_t)c * HW + pix, rem, out);
+            }
+        }
+        if (have_j) buf ^= 1;
+    }
+}
+
 // any window size: the definition, term by term (scales recomputed per term)
 __global__ __launch_bounds__(TB) void lrn_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, size_t total,
                                                      int C, int HW, int size, float alpha_over_size, float beta,
@@ -944,6 +1186,80 @@ int lrn_bwd_launch(const float *x, const float *dy, float *dx, int N, int C, int
     }
     }
 #undef CG_LRN_BWD
+    CG_LAUNCH_CHECK();
+}
+
+// LRN + max-pool in one pass: which layer pairs the fused kernels take (window sizes of the stream
+// kernels; the rows of one pool window within a block's 1024 pixels; windows packed into 12 / 4 bits)
+static int lrn_pool_fwd_rows(int W, int k, int s) { return ((LRN_V * TB) / W - k) / s + 1; }     // pooled rows per band
+bool lrn_pool_fusable(int C, int H, int W, int size, int k, int s, int p)
+{
+    if (!(size == 3 || size == 5)) return false;
+    if (H >= 4096 || W >= 4096 || k <= 0 || s <= 0 || p < 0 || p >= k || C <= 0) return false;
+    if ((k + s - 1) / s > 15 || k * W > LRN_V * TB) return false;
+    const int OH = pool_out_size(H, k, s, p), OW = pool_out_size(W, k, s, p);
+    if (OH <= 0 || OW <= 0) return false;
+    // backward: the pooled rows that cover a band of (1024 / W) input rows fit the staging
+    const int hrb = (LRN_V * TB) / W < H ? (LRN_V * TB) / W : H;
+    return ((hrb + k - 2) / s + 2) * OW <= LP_NP * TB;
+}
+
+int lrn_pool_fwd_launch(const float *x, float *y, int32_t *argmax, int N, int C, int H, int W, int size, float alpha,
+                        float beta, float kappa, int k, int s, int p, hipStream_t st)
+{
+    if (!lrn_pool_fusable(C, H, W, size, k, s, p) || N <= 0) return CG_EUNSUPPORTED;
+    const int OH = pool_out_size(H, k, s, p), OW = pool_out_size(W, k, s, p);
+    const int nchunk = (C + LP_CH - 1) / LP_CH;
+    // bands of equal height, as few as fit
+    int prb = lrn_pool_fwd_rows(W, k, s);
+    const int nbands = (OH + prb - 1) / prb;
+    prb = (OH + nbands - 1) / nbands;
+    if ((uint64_t)N * nchunk * nbands >= (1ull << 31)) return CG_EUNSUPPORTED;
+    const dim3 grid((unsigned)(N * nchunk * nbands));
+    const size_t lds = 2 * (size_t)LRN_V * TB * sizeof(float);
+    const float aos = alpha / (float)size;
+    const FastDiv divOW = make_fastdiv((uint32_t)OW);
+    const bool inside = p == 0 && (OH - 1) * s + k <= H && (OW - 1) * s + k <= W;
+#define CG_LP_FWD(SZ, K_, S_, IN_)                                                                                    \
+    hipLaunchKernelGGL((lrn_pool_fwd_kernel<SZ, K_, S_, IN_>), grid, dim3(TB), lds, st, x, y, argmax, C, H, W, OH, OW, k, \
+                       s, p, nchunk, nbands, prb, aos, beta, kappa, divOW)
+    if (size == 5 && k == 3 && s == 2 && inside) CG_LP_FWD(5, 3, 2, true);
+    else if (size == 5) CG_LP_FWD(5, 0, 0, false);
+    else if (k == 3 && s == 2 && inside) CG_LP_FWD(3, 3, 2, true);
+    else CG_LP_FWD(3, 0, 0, false);
+#undef CG_LP_FWD
+    CG_LAUNCH_CHECK();
+}
+
+int lrn_pool_bwd_launch(const float *x, const float *dpool, const int32_t *argmax, float *dx, int N, int C, int H, int W,
+                        int size, float alpha, float beta, float kappa, int k, int s, int p, int accumulate, int gate,
+                        hipStream_t st)
+{
+    if (!lrn_pool_fusable(C, H, W, size, k, s, p) || N <= 0) return CG_EUNSUPPORTED;
+    const int OH = pool_out_size(H, k, s, p), OW = pool_out_size(W, k, s, p);
+    const int nchunk = (C + LP_CH - 1) / LP_CH;
+    int hrb = (LRN_V * TB) / W;
+    const int nbands = (H + hrb - 1) / hrb;
+    hrb = (H + nbands - 1) / nbands;
+    if ((uint64_t)N * nchunk * nbands >= (1ull << 31)) return CG_EUNSUPPORTED;
+    const dim3 grid((unsigned)(N * nchunk * nbands));
+    const size_t lds = 4 * (size_t)LP_NP * TB * sizeof(float);
+    const float aos = alpha / (float)size, coef = 2.f * alpha * beta / (float)size;
+    const FastDiv divW = make_fastdiv((uint32_t)W), divS = make_fastdiv((uint32_t)s);
+#define CG_LP_BWD(SZ, A_, GT_)                                                                                        \
+    hipLaunchKernelGGL((lrn_pool_bwd_kernel<SZ, A_, GT_>), grid, dim3(TB), lds, st, x, dpool, argmax, dx, C, H, W, OH,  \
+                       OW, k, s, p, nchunk, nbands, hrb, aos, coef, beta, kappa, divW, divS)
+#define CG_LP_BWD_AG(SZ)                                                                                              \
+    do {                                                                                                              \
+        if (accumulate && gate) CG_LP_BWD(SZ, 1, 1);                                                                  \
+        else if (accumulate) CG_LP_BWD(SZ, 1, 0);                                                                     \
+        else if (gate) CG_LP_BWD(SZ, 0, 1);                                                                           \
+        else CG_LP_BWD(SZ, 0, 0);                                                                                     \
+    } while (0)
+    if (size == 3) CG_LP_BWD_AG(3);
+    else CG_LP_BWD_AG(5);
+#undef CG_LP_BWD_AG
+#undef CG_LP_BWD
     CG_LAUNCH_CHECK();
 }
 

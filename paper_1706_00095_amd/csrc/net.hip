@@ -12,9 +12,22 @@
 // Within a layer's turn backward-data and backward-weight are independent and run side by side
 // (backward-weight on a third stream owned by the net); the update waits for both, because it
 // overwrites the model that backward-data still reads.
+#include <atomic>
 #include <new>
 #include <vector>
 #include "cg_internal.h"
+
+// How nets created from now on run an LRN layer followed by a max-pool: bit 0 = forward as one
+// kernel, bit 1 = backward as one kernel.  Forward fused is the default; the fused backward is
+// built and tested but bound by its instruction count, not by memory, and slower than the two
+// separate kernels (measured), so it runs only when asked for.
+static std::atomic<int> g_fuse_lrn_pool{1};
+extern "C" int cg_debug_fuse_lrn_pool(int mode)
+{
+    if (mode < 0 || mode > 3 || mode == 2) return CG_EINVAL;     // backward fused needs forward fused
+    g_fuse_lrn_pool.store(mode, std::memory_order_relaxed);
+    return CG_OK;
+}
 
 struct cg_net {
     struct Layer {
@@ -55,6 +68,13 @@ struct cg_net {
         // bwd_folded with in_concat = the concat layer).
         long long out_img_stride = 0;
         int in_concat = -1;
+        // An LRN layer whose only consumer is a max-pool runs fused with it (fused_pool = the pool,
+        // the pool's fused_lrn = the LRN): forward at the pool's place, from the LRN's input straight
+        // to the pooled output and the winners; backward at the LRN's place, from the pool's gradient
+        // and winners straight to the gradient of the LRN's input.  The LRN's output and the gradient
+        // with respect to it are never written.
+        int fused_pool = -1, fused_lrn = -1;
+        bool fused_pool_bwd = false;          // (LRN layer) backward fused as well
     };
 
     int B = 0, C = 0, H = 0, W = 0;
@@ -233,6 +253,22 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
             }
         }
     }
+    if (rc == CG_OK && g_fuse_lrn_pool.load(std::memory_order_relaxed)) {
+        for (int r = 0; r < L; ++r) {
+            Layer &ln = net->layers[r];
+            if (ln.d.kind != CG_LAYER_LRN) continue;
+            int consumers = 0, who = -1;
+            for (int j = r + 1; j < L; ++j)
+                for (int k = 0; k < net->layers[j].d.n_inputs; ++k)
+                    if (net->layers[j].d.inputs[k] == r) { ++consumers; who = j; }
+            if (consumers != 1 || net->layers[who].d.kind != CG_LAYER_MAXPOOL) continue;
+            const cg_layer_desc &pd = net->layers[who].d;
+            if (!lrn_pool_fusable(ln.C, ln.H, ln.W, ln.d.lrn_size, pd.k, pd.stride, pd.pad)) continue;
+            ln.fused_pool = who;
+            ln.fused_pool_bwd = (g_fuse_lrn_pool.load(std::memory_order_relaxed) & 2) != 0;
+            net->layers[who].fused_lrn = r;
+        }
+    }
     if (rc == CG_OK && net->layers[L - 1].d.kind != CG_LAYER_SOFTMAX_CE) rc = CG_EINVAL;
     if (rc == CG_OK) {
         // the logits feed the loss only: its gradient is written by the loss kernel
@@ -285,7 +321,8 @@ extern "C" long long cg_net_param_count(const cg_net *net, int layer)
 extern "C" int cg_net_layer_fused(const cg_net *net, int layer)
 {
     if (!net || layer < 0 || layer >= (int)net->layers.size()) return CG_EINVAL;
-    return (net->layers[layer].fused_relu ? 1 : 0) | (net->layers[layer].bwd_folded ? 2 : 0);
+    const cg_net::Layer &ly = net->layers[layer];
+    return ((ly.fused_relu || ly.fused_pool >= 0) ? 1 : 0) | ((ly.bwd_folded || ly.fused_pool_bwd) ? 2 : 0);
 }
 
 extern "C" int cg_net_bind(cg_net *net, int layer, float *w, float *v, float *g_local, const float *const *g_peers,
@@ -392,9 +429,17 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             if (ly.alias_of < 0) rc = relu_fwd_launch(in, out, in_elems, S0);
             break;
         case CG_LAYER_LRN:
+            if (ly.fused_pool >= 0) break;           // runs at the pool's place, fused with it
             rc = lrn_fwd_launch(in, out, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha, d.lrn_beta, d.lrn_kappa, S0);
             break;
         case CG_LAYER_MAXPOOL:
+            if (ly.fused_lrn >= 0) {
+                const Layer &ln = net->layers[ly.fused_lrn];
+                rc = lrn_pool_fwd_launch(act(ln.d.inputs[0]), out, reinterpret_cast<int32_t *>(base + ly.aux_off), B, ln.C,
+                                         ln.H, ln.W, ln.d.lrn_size, ln.d.lrn_alpha, ln.d.lrn_beta, ln.d.lrn_kappa, d.k,
+                                         d.stride, d.pad, S0);
+                break;
+            }
             rc = maxpool_fwd_launch(in, out, reinterpret_cast<int32_t *>(base + ly.aux_off), B, ly.inC, ly.inH,
                                     ly.inW, d.k, d.stride, d.pad, S0);
             break;
@@ -512,11 +557,18 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             if (want_dx) rc = relu_bwd_launch(in, dy, dx, in_elems, accum, S0);
             break;
         case CG_LAYER_LRN:
-            if (want_dx)
+            if (want_dx && ly.fused_pool_bwd) {
+                const Layer &pl = net->layers[ly.fused_pool];
+                rc = lrn_pool_bwd_launch(in, base + pl.grad_off, reinterpret_cast<const int32_t *>(base + pl.aux_off), dx, B,
+                                         ly.C, ly.H, ly.W, d.lrn_size, d.lrn_alpha, d.lrn_beta, d.lrn_kappa, pl.d.k,
+                                         pl.d.stride, pl.d.pad, accum, gate != nullptr, S0);
+            } else if (want_dx)
                 rc = lrn_bwd_launch(in, dy, dx, B, ly.C, ly.H * ly.W, d.lrn_size, d.lrn_alpha, d.lrn_beta,
                                     d.lrn_kappa, accum, gate != nullptr, S0);
             break;
         case CG_LAYER_MAXPOOL:
+            if (ly.fused_lrn >= 0 && net->layers[ly.fused_lrn].fused_pool_bwd)
+                break;                                   // the LRN's turn goes from this layer's gradient to its own input's
             if (want_dx)
                 rc = maxpool_bwd_launch(dy, reinterpret_cast<const int32_t *>(base + ly.aux_off), dx, gate, B, ly.inC,
                                         ly.inH, ly.inW, d.k, d.stride, d.pad, accum, S0);

@@ -28,7 +28,17 @@ def _backward_state_from_gpu_forward(orc32, gn, layers, t, acts):
     backward passes then differ legitimately.  So the oracle's backward is run from the GPU's own
     forward activations: both sides take every decision in fp32 on the same numbers.  The
     max-pool winners the GPU stored must then be exactly the oracle's."""
-    acts_g = [host(gn.act(li)).reshape(acts[li].shape) for li in range(len(layers) - 1)] + [acts[-1]]
+    acts_g = []
+    for li, ly in enumerate(layers[:-1]):
+        if ly["kind"] == "lrn" and gn.fused(li):
+            # fused with the pool that follows: its output exists nowhere; the oracle's LRN of the GPU's input
+            # stands for it
+            src = ly["inputs"][0]
+            a = t["x"] if src < 0 else acts_g[src]
+            acts_g.append(orc32.lrn_fwd(a, ly["size"], ly["alpha"], ly["beta"], ly["kappa"])[0])
+        else:
+            acts_g.append(host(gn.act(li)).reshape(acts[li].shape))
+    acts_g.append(acts[-1])
     aux_g = []
     for li, ly in enumerate(layers):
         src = ly["inputs"][0]
@@ -42,7 +52,20 @@ def _backward_state_from_gpu_forward(orc32, gn, layers, t, acts):
         elif ly["kind"] == "maxpool":
             am = orc32.maxpool_fwd(a, ly["k"], ly["stride"], ly["pad"])[1]
             got = host(gn.act(li, 2)).view(np.int32).reshape(am.shape)
-            assert np.array_equal(got, am), ("max-pool winners", li)
+            if src >= 0 and layers[src]["kind"] == "lrn" and gn.fused(src):
+                # The pooled values come from the GPU's own LRN arithmetic (same definition, other rounding
+                # of scale^-beta), so where two values of a window agree to the last bits either may win.
+                # Such windows must be rare and their two candidates equal to rounding; the oracle's
+                # backward then routes through the GPU's winners, as it does through its rectifier signs.
+                diff = np.flatnonzero(got.ravel() != am.ravel())
+                assert diff.size <= max(2, got.size // 50000), ("max-pool winners", li, diff.size, got.size)
+                planes = a.reshape(-1, a.shape[2] * a.shape[3])
+                pl = diff // (am.shape[2] * am.shape[3])
+                va, vb = planes[pl, got.ravel()[diff]], planes[pl, am.ravel()[diff]]
+                assert np.all(np.abs(va - vb) <= 4e-6 * np.maximum(np.abs(vb), 1e-30)), ("max-pool winners", li)
+                am = got.copy()
+            else:
+                assert np.array_equal(got, am), ("max-pool winners", li)
             aux_g.append(am)
         elif ly["kind"] == "softmax_ce":
             aux_g.append(orc32.softmax_ce(a.reshape(a.shape[0], -1), t["labels"])[1].reshape(a.shape))

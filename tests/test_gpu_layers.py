@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 import cg_synth
+import paper_1706_00095_amd as cg
 from gpu_util import host, max_abs_rel
 from net_util import GpuNet
 from oracle import net as onet
@@ -40,11 +41,18 @@ def _net(lrn_size, pool, in_shape=(6, 14, 14)):
                                                     (7, (2, 2, 0), (6, 14, 14)), (4, (4, 3, 1), (6, 14, 14)),
                                                     (5, (3, 2, 0), (5, 9, 11)), (3, (3, 2, 1), (7, 10, 11)),
                                                     (5, (3, 1, 1), (3, 15, 15))])
-def test_layer_variants_match_oracle(orc32, lrn_size, pool, in_shape):
+@pytest.mark.parametrize("fuse", [0, 1, 3])
+def test_layer_variants_match_oracle(orc32, lrn_size, pool, in_shape, fuse):
+    """fuse: the LRN and the max-pool behind it (window sizes 3 and 5) as separate kernels (0), as one
+    kernel in forward (1, the default) or in both directions (3)."""
     layers, in_shape = _net(lrn_size, pool, in_shape)
     B = 5
     t = cg_synth.net_tensors(layers, in_shape, B, 2, seed=40 + lrn_size, num_classes=7, init="fan_in", peer_std=1e-3)
-    gn = GpuNet(layers, in_shape, B, t)
+    cg.cg_debug_fuse_lrn_pool(fuse)
+    try:
+        gn = GpuNet(layers, in_shape, B, t)
+    finally:
+        cg.cg_debug_fuse_lrn_pool(1)
     gn.step(SGD)
     gn.sync()
     buckets = {k: v.copy() for k, v in t["buckets"].items()}
@@ -64,7 +72,9 @@ def test_layer_variants_match_oracle(orc32, lrn_size, pool, in_shape):
             folded_bwd += 1
             continue
         assert max_abs_rel(host(gn.act(li, 1)), dref.ravel()) <= TOL, ("gradient", li, layers[li]["kind"])
-    assert folded_fwd == 3 and folded_bwd == 3        # the three rectifiers, both directions
+    fused = lrn_size in (3, 5)
+    # the three rectifiers, both directions, and the LRN where it runs fused with its pool
+    assert folded_fwd == 3 + (1 if fuse and fused else 0) and folded_bwd == 3 + (1 if fuse == 3 and fused else 0)
     for li in grads:
         assert max_abs_rel(host(gn.g[li]), grads[li]) <= TOL, ("g_local", li)
 
@@ -81,3 +91,20 @@ def test_pooling_planes_beyond_the_lds_staging(orc32, lrn_size, pool, in_shape):
     layers, in_shape = _net(lrn_size, pool, in_shape)
     t = cg_synth.net_tensors(layers, in_shape, 3, 2, seed=50 + lrn_size, num_classes=7, init="fan_in", peer_std=1e-3)
     _check_step(orc32, layers, in_shape, 3, t)
+
+
+@pytest.mark.parametrize("mode", [0, 3])
+def test_alexnet_shaped_iteration_lrn_pool_modes(orc32, mode):
+    """The AlexNet-shaped net (B = 16) with its two LRN + max-pool pairs as four separate kernels (0) and
+    with both directions fused (3); the default, forward fused only, is what every other whole-net
+    test runs.  Planes of 55 x 55 (four row bands a channel) and 27 x 27 (one)."""
+    from test_gpu_fullsize import _check_step
+    layers, in_shape = cg_synth.alexnet_layers()
+    t = cg_synth.net_tensors(layers, in_shape, 16, 1, seed=4, num_classes=1000)
+    cg.cg_debug_fuse_lrn_pool(mode)
+    try:
+        gn = _check_step(orc32, layers, in_shape, 16, t)
+    finally:
+        cg.cg_debug_fuse_lrn_pool(1)
+    lrn = [i for i, ly in enumerate(layers) if ly["kind"] == "lrn"]
+    assert [cg.cg_net_layer_fused(gn.net, i) for i in lrn] == [mode, mode]
