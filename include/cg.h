@@ -8,8 +8,8 @@
  * summed and the model of layer l is updated by
  *        w^{l,k+1} = w^{l,k} - eps * sum_{r=1..s} dw_r^{l,k}          (Eq. 1)
  * layer by layer, in inverse layer order, while the backward pass of the
- * remaining layers is still running (section 2.3, Fig. 3; "layer-wise model
- * update", section 3).  This library is ONE rank: the s-1 = K peer gradients
+ * remaining layers is still running (section 2.3, Fig. 3; the per-layer
+ * update of section 3).  This library is ONE rank: the s-1 = K peer gradients
  * are buffers already resident in this GPU's memory; the inter-node transport
  * (GPI-2, section 3.1-3.2) is outside it.
  *
@@ -54,7 +54,7 @@ typedef struct {
 } cg_conv_desc;
 
 /* Solver constants of the update: step size eps of Eq. 1 (lr), and the
- * "higher order terms" that depend on the model history (text after Eq. 1):
+ * terms that depend on the history of the model (text after Eq. 1):
  * momentum mu and L2 weight decay wd.  grad_scale multiplies the summed
  * gradient (1 = Eq. 1 literally; 1/(K+1) gives the mean over ranks). */
 typedef struct { float lr, mu, wd, grad_scale; } cg_sgd;
@@ -91,7 +91,7 @@ int cg_conv_fwd(const cg_conv_desc *d, const float *x, const float *w, const flo
 int cg_conv_bwd_data(const cg_conv_desc *d, const float *dy, const float *w,
                      float *dx, void *ws, size_t ws_bytes, void *stream);
 
-/* "compute local gradient dw_r^{(k,l)}" (Fig. 3, first line of the turn):
+/* The local gradient of a layer (Fig. 3, first step of a turn):
  *   dw[m,c,kh,kw] = sum_{n,oh,ow} dy[n,m,oh,ow] * x[n, g*C/G + c, oh*s-p+kh, ow*s-p+kw]
  *   dbias[m]      = sum_{n,oh,ow} dy[n,m,oh,ow]             (dbias may be NULL)
  * Both overwritten.  The sum over n,oh,ow is split into slices reduced in a
@@ -101,7 +101,7 @@ int cg_conv_bwd_weight(const cg_conv_desc *d, const float *x, const float *dy,
 
 /* The three passes above with the arithmetic of the matrix instructions chosen by
  * the caller (math = CG_MATH_*): the optional reduced-precision path for the
- * "basic linear algebra operations" of section 2.1.  Same arguments, layouts,
+ * dense linear algebra of section 2.1.  Same arguments, layouts,
  * workspaces and errors; CG_MATH_FP32 is the call without the suffix.  The bias
  * sum of backward-weight is always fp32.  CG_EUNSUPPORTED: backward-data of a
  * strided convolution with fewer than 8 (channel, stride phase) pairs per group
@@ -129,8 +129,8 @@ int cg_conv_bwd_weight_noalloc(const cg_conv_desc *d, const float *x, const floa
                                float *dw, float *dbias, void *stream);
 
 /* Gradient aggregation over s = K+1 ranks fused with the model update of one
- * layer (Eq. 1; "reduced (added to) with its own gradient data", section 3.2;
- * update on the reduced gradient, section 3.2 first paragraph).  Per element
+ * layer (Eq. 1; gradient reduction at the receiver and update on the reduced
+ * gradient, section 3.2).  Per element
  * i < n, every operation rounded to fp32 in this order, no fused multiply-add:
  *     s = g_local[i];  for k = 0..K-1:  s = s + g_peers[k][i];
  *     if (grad_scale != 1) s = s * grad_scale;
@@ -157,8 +157,8 @@ int cg_grad_reduce_sgd_multi(int nb, float *const *w, float *const *v,
                              const size_t *n, const cg_sgd *sgd, void *stream);
 
 /* cg_grad_reduce_sgd / cg_grad_reduce_sgd_multi with the K+1 gradients added in
- * the association of the binomial reduction tree of section 3.2 ("Reduction of
- * the Gradient": data travels from higher to lower rank numbers and ends on the
+ * the association of the binomial reduction tree of section 3.2 (gradient
+ * reduction: data travels from higher to lower rank numbers and ends on the
  * master, each rank adding what it receives to its own gradient before it
  * forwards the result).  Rank 0 is the local worker, rank k+1 is g_peers[k].
  * The receiver of rank r > 0 is r with its lowest set bit cleared; rank r
@@ -246,7 +246,7 @@ enum { CG_STEP_OVERLAP = 0, CG_STEP_SERIAL = 1, CG_STEP_JOIN = 2, CG_STEP_TREE_S
  * gradient of layer l followed, on update_stream, by its aggregation and model
  * update (cg_grad_reduce_sgd) while compute_stream continues with layer l-1.
  * Layer l's forward in the NEXT call waits only for layer l's own update
- * ("finalize", section 2.3): there is no device-wide barrier.
+ * (the per-layer completion step of section 2.3): there is no device-wide barrier.
  *  x [B,C,H,W], labels [B] (int32, device), dropout_masks: HOST array of L
  *  device pointers (uint8 keep-masks, one per DROPOUT layer, NULL elsewhere;
  *  the array may be NULL if the net has no dropout layer), loss_dev: 1 float.

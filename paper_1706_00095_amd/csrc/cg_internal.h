@@ -217,8 +217,10 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
                   size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0, int math = 0);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
                        size_t ws_bytes, int accumulate, hipStream_t stream, int math = 0);
+// bias_stream: if not null, the bias sums are enqueued there instead of on `stream` (dy must be complete
+// in that stream's order as well, and the caller joins both streams before db is used)
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
-                         void *ws, size_t ws_bytes, hipStream_t stream, int math = 0);
+                         void *ws, size_t ws_bytes, hipStream_t stream, int math = 0, hipStream_t bias_stream = nullptr);
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
                 size_t ws_bytes, int relu, hipStream_t stream, int math = 0);
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, const float *gate,

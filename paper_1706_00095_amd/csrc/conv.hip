@@ -4,7 +4,7 @@
 // Backward-data:    dX[c][(n,ih,iw)]  = sum_{(m,kh,kw)} Wt[c][(m,kh,kw)] * dY(n,m,(ih+p-kh)/s,(iw+p-kw)/s)
 // Backward-weight:  dW[m][(c,kh,kw)]  = sum_{(n,oh,ow)} dY[m][(n,oh,ow)] * X(n,c,oh*s-p+kh,ow*s-p+kw)
 // (section 2.1: forward propagation, backward propagation, gradient on the weights; the last
-// one is the "compute local gradient" step of every turn in Fig. 3).
+// one is the first step of every turn in Fig. 3).
 #include <mutex>
 #include "cg_internal.h"
 
@@ -676,7 +676,7 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
 }
 
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
-                         void *ws, size_t ws_bytes, hipStream_t stream, int math)
+                         void *ws, size_t ws_bytes, hipStream_t stream, int math, hipStream_t bias_stream)
 {
     if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_bwd_weight", -1);
@@ -695,8 +695,11 @@ int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy,
     // The bias sums go first: they need only dy and stream through HBM while another stream's matrix
     // kernel still runs; behind the weight gradient of a net's first layer they would sit, alone on
     // the GPU, between that kernel and the update the next iteration waits for.
+    // (bias_stream: a stream of the caller's that has nothing else to do meanwhile -- a net's first
+    // layer has no backward-data -- so that the sums run beside the matrix kernel, not in front of it)
     if (db) {
-        const int rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes, stream);
+        const int rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes,
+                                        bias_stream ? bias_stream : stream);
         if (rb) return rb;
     }
     return igemm_run(p, ws, split_bytes, stream);

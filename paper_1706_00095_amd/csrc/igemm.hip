@@ -115,9 +115,11 @@ __device__ __forceinline__ void to_bf16(const float (&f)[KT / 8][4], bf16x8 &hi,
 // are wave-uniform.  Written as assembly so that the waits stay under this file's control: the
 // kernel below waits for exactly the tile it is about to read (s_waitcnt vmcnt(n)), whereas the
 // compiler, told that a load writes LDS, drains every load in flight before each LDS read.
-// The hazard recognizer does not look inside assembly: a scalar register written by the preceding
-// instruction may not be read by a vector-memory instruction for five wait states (one for M0), so
-// the s_mov and the s_nop supply them.
+// The hazard recognizer does not look inside assembly: a scalar register written by a preceding
+// vector instruction (a readfirstlane, or a v_readlane that restores a spilled register, the buffer
+// descriptor included) may not be read by a vector-memory instruction for five wait states (one for
+// M0), so the s_mov and the s_nop 3 of this form supply them.  The short forms below (s_nop 0) are
+// for kernels that spill no scalar register, which the build checks (build.py).
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff, uint32_t soff)
@@ -133,11 +135,17 @@ __device__ __forceinline__ void load_to_lds(BufferRsrc rsrc, const float *lds, u
 __device__ __forceinline__ void load_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff)
 {
     const uint32_t lds_addr = (uint32_t)(size_t)(const lds_float *)lds;
+#if CG_MATH == 0
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                  ::"s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+#else   // the bf16 instances of the gathered kernel spill scalar registers: the long form throughout
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 ::"s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+#endif
 }
 // 64 lanes x 16 bytes: lane l's four elements land at lds + 16*l.
-template <int WS = 1>
+constexpr int kShortWS = CG_MATH == 0 ? 1 : 4;
+template <int WS = kShortWS>
 __device__ __forceinline__ void load4_to_lds(BufferRsrc rsrc, const float *lds, uint32_t voff)
 {
     const uint32_t lds_addr = (uint32_t)(size_t)(const lds_float *)lds;
@@ -273,7 +281,7 @@ template <int R, bool CHECK> struct KLoader {
 // only 4-byte alignment, and the range check is per float: a quad that reaches beyond K, a run or
 // the tensor delivers the floats that exist and zeros (or the neighbouring row's values) for the
 // rest, which meet zeros of operand B.
-template <int R, int WS = 1> struct KLoader4 {       // WS: wait states behind the M0 set-up of a load (1 or 4)
+template <int R, int WS = kShortWS> struct KLoader4 {       // WS: wait states behind the M0 set-up of a load (1 or 4)
     static constexpr int NJ = (R + 63) / 64;     // load instructions per tile and wave
     static constexpr int SZ = 4 * NJ * 256;      // rows beyond R are loaded as zeros
     static constexpr int LPT = NJ;
@@ -1006,7 +1014,7 @@ __global__ __launch_bounds__(256, 2) void igemm_wgrad_kernel(const IgemmProblem 
     static_assert(WM * WN == 4 && WN * TN == 4, "four waves, 128 columns per block");
     static_assert(CPB % 4 == 0, "whole channels per wave");
     constexpr int MT = WM * TM * 32, NT = 128;
-    using LA = KLoader4<MT>;
+    using LA = KLoader4<MT, 4>;
     constexpr int LAW = LA::LPT;
     constexpr int CS = NSL * 64 + 1;            // odd: the channels of one tap fall on different banks
     constexpr int BUF = CPB * CS;
@@ -1114,7 +1122,7 @@ __global__ __launch_bounds__(256, 2) void igemm_wgrad_kernel(const IgemmProblem 
         }
 #pragma unroll
         for (int j = Pn * LAW / NPART; j < (Pn + 1) * LAW / NPART; ++j)
-            load4_to_lds(rsrcA, smem + (tile % NSTA) * LA::SZ + (wave * LA::NJ + j) * 256, la.roff[j] + la.koff);
+            load4_to_lds<4>(rsrcA, smem + (tile % NSTA) * LA::SZ + (wave * LA::NJ + j) * 256, la.roff[j] + la.koff);
     };
     auto tiles_of = [&](int u) {
         int img, oy0, rows;
@@ -1472,7 +1480,7 @@ template <int TM, int NSTA, int CPB, int NSL>
 int launch_wgrad_cfg(const IgemmProblem &p, hipStream_t stream)
 {
     constexpr int MT = 2 * TM * 32;
-    using LA = KLoader4<MT>;
+    using LA = KLoader4<MT, 4>;
     dim3 grid((p.N + 127) / 128, (p.M + MT - 1) / MT, p.groups * p.splits);
     if (grid.y > 65535u || grid.z > 65535u) return CG_EUNSUPPORTED;
     int rec = -1;

@@ -542,7 +542,10 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             }
             const int IN = ly.inC * ly.inH * ly.inW;
             if (d.kind == CG_LAYER_CONV)
-                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
+                // without a backward-data pass of its own (a first layer) the compute stream is idle during this
+                // turn: the bias sums go there, beside the weight gradient; the update waits for both streams
+                rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math,
+                                          (!serial && !want_dx) ? S0 : nullptr);
             else
                 rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
             if (rc == CG_OK && want_dx) {
