@@ -275,13 +275,16 @@ def googlenet_workload(cg, torch, sgd, steps, flags, table=False):
     torch.cuda.synchronize()
     run_steps(cg, torch, gst, sgd, 5, flags)
     sync(torch, gst)
+    l0 = cg.cg_debug_launch_count()
     t0 = time.perf_counter()
     run_steps(cg, torch, gst, sgd, steps, flags)
     sync(torch, gst)
     gms = (time.perf_counter() - t0) / steps * 1e3
+    launches = (cg.cg_debug_launch_count() - l0) / steps
     gflop = 3 * 2 * 1.5827 * 32 - 2 * 0.118 * 32       # forward x 3, minus the first layer's backward-data
     out = {"workload": "googlenet_shaped_train_step_224_B32_K8", "ms_per_step": gms,
            "images_per_s": 32 / (gms * 1e-3), "steps": steps, "matrix_core_tflops": gflop / gms,
+           "kernel_launches_per_step": launches,
            "schedule": "serial" if flags == cg.CG_STEP_SERIAL else "overlap", "loss": float(gst["loss"][0].item())}
     if table:
         cg.cg_profile_enable(True)
@@ -434,10 +437,12 @@ def main():
 
     # ---- the timed region: K whole iterations, every matrix-core and update launch bracketed by events
     cg.cg_profile_enable(True)
+    launches0 = cg.cg_debug_launch_count()
     t0 = time.perf_counter()
     run_steps(cg, torch, st, sgd, args.steps, flags)
     sync(torch, st)
     wall = time.perf_counter() - t0
+    launches_per_step = (cg.cg_debug_launch_count() - launches0) / args.steps
     cg.cg_profile_enable(False)
     agg = collect_profile(cg)
     loss = float(st["loss"].cpu()[0])
@@ -557,6 +562,7 @@ def main():
                                            "(glue layers and updates included in the time)"},
         "matrix_core_kernels_exclusive": totals_excl,
         "serial_schedule_ms_per_step": serial_ms,
+        "kernel_launches_per_step": launches_per_step,
         "grad_update": grad_update,
         "hbm_achievable": achievable,
         "conv_layers_standalone": layer_bench,

@@ -75,6 +75,10 @@ int cg_profile_get(int i, cg_profile_record *out);
  * Process-wide. */
 int cg_debug_fuse_lrn_pool(int mode);
 
+/* Measurement aid: kernels launched by the library in this process so far
+ * (every entry point, every stream). */
+unsigned long long cg_debug_launch_count(void);
+
 /* Measurement aid: the streaming rates the memory system reaches with the
  * simplest possible kernels, to quote beside the published peak.  mode 0:
  * dst[i] = src[i]; mode 1: read src only (dst receives one float4 if the sum

@@ -9,6 +9,9 @@ namespace cg {
 
 static thread_local int g_last_hip_error = 0;
 
+static std::atomic<unsigned long long> g_launches{0};
+void note_launch() { g_launches.fetch_add(1, std::memory_order_relaxed); }
+
 int hip_fail(hipError_t e)
 {
     g_last_hip_error = (int)e;
@@ -160,6 +163,11 @@ extern "C" int cg_debug_stream(void *dst, const void *src, const void *src2, siz
     else hipLaunchKernelGGL(cg::debug_stream_kernel<3>, grid, dim3(256), 0, s, d, a, b, n4);
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
+}
+
+extern "C" unsigned long long cg_debug_launch_count(void)
+{
+    return cg::g_launches.load(std::memory_order_relaxed);
 }
 
 extern "C" const char *cg_strerror(int code)

@@ -8,6 +8,19 @@
 
 namespace cg {
 
+// Every kernel launch of the library is counted (cg_debug_launch_count): nets of many small layers
+// are bound by the number of launches, and benchmarks report it.
+void note_launch();
+}  // namespace cg
+#undef hipLaunchKernelGGL
+#define hipLaunchKernelGGL(kernelName, ...)                          \
+    do {                                                             \
+        ::cg::note_launch();                                         \
+        hipLaunchKernelGGLInternal((kernelName), __VA_ARGS__);       \
+    } while (0)
+
+namespace cg {
+
 // Records the failing hipError_t for cg_last_hip_error() and maps it to CG_EHIP.
 int hip_fail(hipError_t e);
 

@@ -28,10 +28,11 @@ COPY_BYTES = 256 << 20
 
 def label(name):
     name = name.replace("(anonymous namespace)::", "").replace("void ", "")
-    m = re.match(r"cg::igemm_patch_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+)>", name)
+    math = {"0": "", "1": ",bf16", "2": ",bf16x3"}      # last template argument of the two big kernels: the arithmetic
+    m = re.match(r"cg::igemm_patch_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d)>", name)
     if m:
-        wm, _, tm, _, _, nsl = map(int, m.groups())
-        return f"igemm_patch_kernel<{wm * tm * 32}x128,{nsl}>"
+        wm, _, tm, _, _, nsl = map(int, m.groups()[:6])
+        return f"igemm_patch_kernel<{wm * tm * 32}x128,{nsl}{math[m.group(7)]}>"
     m = re.match(r"cg::igemm_patch16_kernel<(\d+), (\d+), (\d+)>", name)
     if m:
         tm, _, nsl = map(int, m.groups())
@@ -40,11 +41,12 @@ def label(name):
     if m:
         wm, _, tm, _, _, cpb, nsl = map(int, m.groups())
         return f"igemm_wgrad_kernel<{wm * tm * 32}x128,{cpb},{nsl}>"
-    m = re.match(r"cg::igemm_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), cg::(\w+)<(\d+)(?:, (\w+))?>, cg::(\w+)<(\d+)(?:, (\w+))?> ?>", name)
+    m = re.match(r"cg::igemm_kernel<(\d+), (\d+), (\d+), (\d+), (\d+), cg::(\w+)<(\d+)(?:, (\w+))?>, cg::(\w+)<(\d+)(?:, (\w+))?>, (\d)>", name)
     if m:
         wm, wn, tm, tn = (int(m.group(i)) for i in (1, 2, 3, 4))
         code = {"KLoader4": "4", "KLoader": "k", "RowsLoader": "r"}
-        return f"igemm_kernel<{wm * tm * 32}x{wn * tn * 32},{code[m.group(6)]}{code[m.group(9)]}{'c' if m.group(11) == 'true' else '-'}>"
+        return (f"igemm_kernel<{wm * tm * 32}x{wn * tn * 32},{code[m.group(6)]}{code[m.group(9)]}"
+                f"{'c' if m.group(11) == 'true' else '-'}{math[m.group(12)]}>")
     m = re.match(r"cg::reduce_sgd_kernel<(\d+), (\w+)>", name)
     if m:       # as the library's own launch log names it: <K> left to right, <K,tree> tree association
         return f"reduce_sgd_kernel<{m.group(1)}{',tree' if m.group(2) == 'true' else ''}>"

@@ -163,6 +163,26 @@ def test_schedules_mixed_from_call_to_call_agree_with_the_serial_one(name):
         assert torch.equal(a.w[li], b.w[li]) and torch.equal(a.v[li], b.v[li]) and torch.equal(a.g[li], b.g[li])
 
 
+def test_launch_counter_counts_the_kernels_of_a_step():
+    """cg_debug_launch_count grows by one per kernel the library launches: by the same amount for every step
+    of a net (the launch sequence depends on shapes only), and by exactly one for the calibration copy."""
+    layers, in_shape, B, t = _build("inception")
+    gn = GpuNet(layers, in_shape, B, t)
+    counts = []
+    for _ in range(3):
+        c0 = cg.cg_debug_launch_count()
+        gn.step(SGD)
+        counts.append(cg.cg_debug_launch_count() - c0)
+    gn.sync()
+    assert counts[0] == counts[1] == counts[2] and counts[0] >= len(layers), counts
+    a = torch.zeros(1024, device="cuda")
+    b = torch.empty_like(a)
+    c0 = cg.cg_debug_launch_count()
+    cg.cg_debug_copy(b, a, a.numel() * 4)
+    assert cg.cg_debug_launch_count() - c0 == 1
+    torch.cuda.synchronize()
+
+
 def test_loss_decreases_over_iterations_on_fixed_batch():
     layers, in_shape, B, t = _build("tiny_cnn_cfg1")
     for li in t["peers"]:
