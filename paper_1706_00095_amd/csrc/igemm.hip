@@ -353,104 +353,138 @@ template <int TN> struct EpiLds {
     static constexpr int W = TN * 32, LS = W + 8, FLOATS = 32 * LS;
 };
 
+// PLAIN: no gate, no accumulation, no scattered rows (forward, ungated backward-data, K-slice partial
+// planes): that instance has a third of the other's instructions, and a block's epilogue is time in
+// which its waves issue no matrix instruction.
+template <int TM, int TN, bool PLAIN>
+__device__ __forceinline__ void store_tile_impl(const IgemmProblem &p, const v16f (&acc)[TM][TN], uint32_t g, uint32_t sp,
+                                                uint32_t mw, uint32_t nw, uint32_t n_end, int lane, float *wlds)
+{
+    constexpr int LS = EpiLds<TN>::LS, QR = TN * 8, RPI = 64 / QR;      // quads per row, rows per instruction
+    constexpr int NRG = 32 / RPI;                   // row groups (one store instruction each) of a 32-row slab
+    constexpr int PB = TM >= 4 ? 2 : NRG < 4 ? NRG : 4;      // row groups per batch (fewer beside 128 accumulator registers)
+    constexpr int NBS = NRG / PB, NBT = TM * NBS;   // batches per slab and of the whole tile
+    const int h = lane >> 5, li = lane & 31, qd = lane % QR, rr = lane / QR;
+    float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
+    const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
+    const float *gate = (!PLAIN && p.gate) ? p.gate + (int64_t)g * p.c_gstride : nullptr;
+    const bool accumulate = !PLAIN && p.accumulate, scatter = !PLAIN && p.c_scatter;
+    const uint32_t n = nw + 4u * (uint32_t)qd;
+    int32_t off[4], ca[4], cb[4];
+    float bcol[4];
+    uint32_t okbits = 0u;       // bit e: column n + e exists (kept in a vector register: lane masks are scalar-register pairs)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const bool ok = n + (uint32_t)e < n_end;
+        const Info ci = map_info(p.c_col, ok ? n + (uint32_t)e : 0u);
+        off[e] = ok ? ci.off : 0;
+        ca[e] = ci.a; cb[e] = ci.b;
+        bcol[e] = (p.bias_mode == 2 && ok) ? bias[n + (uint32_t)e] : 0.f;
+        okbits |= ok ? 1u << e : 0u;
+    }
+    const bool quad = !scatter && (okbits & 8u) && off[1] == off[0] + 1 && off[2] == off[0] + 2 && off[3] == off[0] + 3;
+    // Loads and stores leave the vector-memory counter in the order they were issued, so a load
+    // issued behind stores is waited for together with them, a whole write latency.  Hence what a
+    // batch of row groups reads from global memory (per-row bias, gate, C when accumulating) is
+    // requested one batch ahead, before the stores of the batch in front of it: the wait for it
+    // then leaves those stores outstanding.
+    struct Batch {
+        f4u gt[PB], old[PB];
+        float brow[PB];
+        int32_t roff[PB];
+        uint32_t okm;           // bit 4u+e: element e of row group u is inside C (a vector register, not 16 lane masks)
+    };
+    Batch bt[2];
+    auto prepare = [&](auto BC, Batch &t) {
+        constexpr int b = decltype(BC)::value, i = b / NBS, p0 = (b % NBS) * PB;
+#pragma unroll
+        for (int u = 0; u < PB; ++u) {
+            const int row = (p0 + u) * RPI + rr;
+            const uint32_t m = mw + (uint32_t)(i * 32 + row);
+            t.gt[u] = f4u{1.f, 1.f, 1.f, 1.f};
+            t.old[u] = f4u{0.f, 0.f, 0.f, 0.f};
+            t.roff[u] = (int32_t)m * p.c_row_stride;
+            t.brow[u] = (p.bias_mode == 1 && m < p.M) ? bias[m] : 0.f;
+            uint32_t bits = m < p.M ? okbits : 0u;
+            if (scatter && m < p.M) {
+                const Info ri = map_info(p.c_row, m);
+                t.roff[u] = ri.off;
+                bits = 0u;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    bits |= ((okbits >> e & 1u) && (uint32_t)(ri.a + ca[e]) < p.c_limA && (uint32_t)(ri.b + cb[e]) < p.c_limB) ? 1u << e : 0u;
+            }
+            if (u == 0) t.okm = 0u;
+            t.okm |= bits << (4 * u);
+            if (m < p.M && (gate || accumulate)) {
+                const int32_t row_off = t.roff[u];
+                if (quad) {
+                    if (gate) t.gt[u] = *reinterpret_cast<const f4u *>(gate + row_off + off[0]);
+                    if (accumulate) t.old[u] = *reinterpret_cast<const f4u *>(c_base + row_off + off[0]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (gate && (bits >> e & 1u)) t.gt[u][e] = gate[row_off + off[e]];
+                        if (accumulate && (bits >> e & 1u)) t.old[u][e] = c_base[row_off + off[e]];
+                    }
+                }
+            }
+        }
+    };
+    prepare(std::integral_constant<int, 0>{}, bt[0]);
+    static_for<0, NBT>([&](auto BC) {
+        constexpr int b = decltype(BC)::value, i = b / NBS, p0 = (b % NBS) * PB;
+        if constexpr (b % NBS == 0) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) wlds[((r >> 2) * 8 + h * 4 + (r & 3)) * LS + j * 32 + li] = acc[i][j][r];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the slab is in LDS (one wave: no barrier)
+        }
+        float4 q[PB];
+#pragma unroll
+        for (int u = 0; u < PB; ++u) q[u] = *reinterpret_cast<const float4 *>(wlds + ((p0 + u) * RPI + rr) * LS + 4 * qd);
+        if constexpr (b + 1 < NBT) prepare(std::integral_constant<int, b + 1>{}, bt[(b + 1) & 1]);
+        const Batch &t = bt[b & 1];
+#pragma unroll
+        for (int u = 0; u < PB; ++u) {
+            const int row = (p0 + u) * RPI + rr;
+            const uint32_t m = mw + (uint32_t)(i * 32 + row);
+            if (m >= p.M || !(okbits & 1u)) continue;
+            float val[4] = {q[u].x + bcol[0], q[u].y + bcol[1], q[u].z + bcol[2], q[u].w + bcol[3]};
+            const float br = t.brow[u];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                val[e] += br;
+                if (p.relu) val[e] = fmaxf(val[e], 0.f);
+            }
+            const int32_t row_off = t.roff[u];
+            if constexpr (!PLAIN) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (!(t.gt[u][e] > 0.f)) val[e] = 0.f;
+            }
+            f4u out = {val[0], val[1], val[2], val[3]};
+            if (accumulate) out += t.old[u];
+            if (quad) {
+                *reinterpret_cast<f4u *>(c_base + row_off + off[0]) = out;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (t.okm >> (4 * u + e) & 1u) c_base[row_off + off[e]] = out[e];
+            }
+        }
+        if constexpr (b % NBS == NBS - 1)
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // slab read before the next one overwrites it
+    });
+}
+
 template <int TM, int TN>
 __device__ __forceinline__ void store_tile(const IgemmProblem &p, const v16f (&acc)[TM][TN], uint32_t g, uint32_t sp,
                                            uint32_t mw, uint32_t nw, uint32_t n_end, int lane, float *wlds)
 {
-    constexpr int LS = EpiLds<TN>::LS, QR = TN * 8, RPI = 64 / QR;      // quads per row, rows per instruction
-    const int h = lane >> 5, li = lane & 31, qd = lane % QR, rr = lane / QR;
-    float *c_base = p.c_ptr + (int64_t)g * p.c_gstride + (int64_t)sp * p.c_split_stride;
-    const float *bias = p.bias_mode ? p.bias + (int64_t)g * p.bias_gstride : nullptr;
-    const float *gate = p.gate ? p.gate + (int64_t)g * p.c_gstride : nullptr;
-    const uint32_t n = nw + 4u * (uint32_t)qd;
-    int32_t off[4], ca[4], cb[4];
-    bool ok[4];
-    float bcol[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        ok[e] = n + (uint32_t)e < n_end;
-        const Info ci = map_info(p.c_col, ok[e] ? n + (uint32_t)e : 0u);
-        off[e] = ok[e] ? ci.off : 0;
-        ca[e] = ci.a; cb[e] = ci.b;
-        bcol[e] = (p.bias_mode == 2 && ok[e]) ? bias[n + (uint32_t)e] : 0.f;
-    }
-    const bool quad = !p.c_scatter && ok[3] && off[1] == off[0] + 1 && off[2] == off[0] + 2 && off[3] == off[0] + 3;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) wlds[((r >> 2) * 8 + h * 4 + (r & 3)) * LS + j * 32 + li] = acc[i][j][r];
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // the slab is in LDS (one wave: no barrier)
-        // four row groups at a time: what they read from global memory (gate, C when accumulating)
-        // is loaded before the first of their stores, which the loads could not be moved across
-        constexpr int PB = (32 / RPI) < 4 ? (32 / RPI) : 4;
-#pragma unroll
-        for (int p0 = 0; p0 < 32 / RPI; p0 += PB) {
-            float4 q[PB];
-            f4u gt[PB], old[PB];
-            int32_t roff[PB];
-            bool okm[PB][4];
-#pragma unroll
-            for (int u = 0; u < PB; ++u) {
-                const int row = (p0 + u) * RPI + rr;
-                const uint32_t m = mw + (uint32_t)(i * 32 + row);
-                q[u] = *reinterpret_cast<const float4 *>(wlds + row * LS + 4 * qd);
-                gt[u] = f4u{1.f, 1.f, 1.f, 1.f};
-                old[u] = f4u{0.f, 0.f, 0.f, 0.f};
-                roff[u] = (int32_t)m * p.c_row_stride;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) okm[u][e] = ok[e] && m < p.M;
-                if (p.c_scatter && m < p.M) {
-                    const Info ri = map_info(p.c_row, m);
-                    roff[u] = ri.off;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        okm[u][e] = ok[e] && (uint32_t)(ri.a + ca[e]) < p.c_limA && (uint32_t)(ri.b + cb[e]) < p.c_limB;
-                }
-                if (m < p.M) {
-                    const int32_t row_off = roff[u];
-                    if (quad) {
-                        if (gate) gt[u] = *reinterpret_cast<const f4u *>(gate + row_off + off[0]);
-                        if (p.accumulate) old[u] = *reinterpret_cast<const f4u *>(c_base + row_off + off[0]);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            if (gate && okm[u][e]) gt[u][e] = gate[row_off + off[e]];
-                            if (p.accumulate && okm[u][e]) old[u][e] = c_base[row_off + off[e]];
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < PB; ++u) {
-                const int row = (p0 + u) * RPI + rr;
-                const uint32_t m = mw + (uint32_t)(i * 32 + row);
-                if (m >= p.M || !ok[0]) continue;
-                float val[4] = {q[u].x + bcol[0], q[u].y + bcol[1], q[u].z + bcol[2], q[u].w + bcol[3]};
-                const float brow = p.bias_mode == 1 ? bias[m] : 0.f;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    val[e] += brow;
-                    if (p.relu) val[e] = fmaxf(val[e], 0.f);
-                }
-                const int32_t row_off = roff[u];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (!(gt[u][e] > 0.f)) val[e] = 0.f;
-                f4u out = {val[0], val[1], val[2], val[3]};
-                if (p.accumulate) out += old[u];
-                if (quad) {
-                    *reinterpret_cast<f4u *>(c_base + row_off + off[0]) = out;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (okm[u][e]) c_base[row_off + off[e]] = out[e];
-                }
-            }
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // slab read before the next one overwrites it
-    }
+    if (!p.gate && !p.accumulate && !p.c_scatter) store_tile_impl<TM, TN, true>(p, acc, g, sp, mw, nw, n_end, lane, wlds);
+    else store_tile_impl<TM, TN, false>(p, acc, g, sp, mw, nw, n_end, lane, wlds);
 }
 
 }  // namespace
