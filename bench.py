@@ -125,6 +125,25 @@ def hbm_achievable(cg, torch, reps=20):
     return out
 
 
+def mfma_achievable(cg, torch, blocks=512, iters=20000, reps=5):
+    """What the fp32 matrix pipeline reaches with nothing else to do (cg_debug_mfma_loop: two blocks of
+    four waves per compute unit, four independent accumulators a wave, no loads, no LDS): the measured
+    ceiling beside the published 157.3 TFLOP/s."""
+    out = torch.empty(256 * blocks, device="cuda")
+    cg.cg_debug_mfma_loop(out, blocks, iters)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        cg.cg_debug_mfma_loop(out, blocks, iters)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    tf = 2.0 * 32 * 32 * 2 * 16 * iters * blocks / ms / 1e9
+    return {"tflops": round(tf, 1), "frac_of_peak": round(tf / PEAK_FP32_MFMA_TFLOPS, 4), "ms_per_launch": round(ms, 4),
+            "what": f"{blocks} blocks x 4 waves x {iters} x 4 independent v_mfma_f32_32x32x2_f32, no memory traffic"}
+
+
 def conv_layers_standalone(cg, torch, B, reps=10, math=0):
     """Configuration 2: every AlexNet-shaped convolution layer alone, forward / backward-data /
     backward-weight through the C ABI (the first layer's backward-data included, which a net skips),
@@ -421,7 +440,7 @@ def main():
     if args.update_only:
         # the eight-bucket launches only, so that a profiler's per-kernel means are means over one launch shape
         print(json.dumps({"grad_update": grad_update_standalone(cg, torch, max(args.steps, 1), args.warmup, per_bucket=False),
-                          "hbm_achievable": hbm_achievable(cg, torch)}), flush=True)
+                          "hbm_achievable": hbm_achievable(cg, torch), "mfma_achievable": mfma_achievable(cg, torch)}), flush=True)
         return
 
     flags = cg.CG_STEP_SERIAL if args.serial else cg.CG_STEP_OVERLAP
@@ -491,6 +510,7 @@ def main():
     torch.cuda.empty_cache()
     grad_update = None if args.skip_update_bench else grad_update_standalone(cg, torch, min(max(args.steps, 5), 50), args.warmup)
     achievable = None if args.skip_update_bench else hbm_achievable(cg, torch)
+    mfma_peak = None if args.skip_update_bench else mfma_achievable(cg, torch)
     if grad_update:
         for k, v in grad_update.items():
             if "bytes" not in v:
@@ -565,6 +585,7 @@ def main():
         "kernel_launches_per_step": launches_per_step,
         "grad_update": grad_update,
         "hbm_achievable": achievable,
+        "mfma_achievable": mfma_peak,
         "conv_layers_standalone": layer_bench,
         "alexnet_b64_step": b64,
         "reduced_precision": reduced,

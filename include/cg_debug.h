@@ -87,6 +87,14 @@ unsigned long long cg_debug_launch_count(void);
  * bytes % 16 == 0; src2 is needed for mode 3 only.  All accesses non-temporal. */
 int cg_debug_stream(void *dst, const void *src, const void *src2, size_t bytes, int mode, void *stream);
 
+/* Measurement aid: the rate the fp32 matrix pipeline reaches with nothing else
+ * to do.  `blocks` blocks of four waves; every wave issues `iters` times four
+ * independent v_mfma_f32_32x32x2_f32 (no loads, no LDS), i.e. 2*32*32*2 *
+ * 16 * iters * blocks floating-point operations in all, and then stores its
+ * accumulators' sum: `out` receives 256 * blocks floats (16-byte aligned
+ * device pointer; the values mean nothing).  blocks in 1..65536, iters >= 1. */
+int cg_debug_mfma_loop(float *out, int blocks, int iters, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = [
     "cg_conv_out_shape", "cg_conv_workspace_bytes", "cg_conv_fwd", "cg_conv_bwd_data", "cg_conv_bwd_weight", "cg_conv_bwd_weight_noalloc",
     "cg_conv_fwd_math", "cg_conv_bwd_data_math", "cg_conv_bwd_weight_math",
     "cg_grad_reduce_sgd", "cg_grad_reduce_sgd_multi", "cg_grad_reduce_sgd_tree", "cg_grad_reduce_sgd_tree_multi", "cg_net_create", "cg_net_destroy", "cg_net_param_count", "cg_net_layer_fused", "cg_net_bind",
-    "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_net_tensor_image_stride", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_stream", "cg_debug_launch_count", "cg_debug_fuse_lrn_pool", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
+    "cg_net_workspace_bytes", "cg_train_step", "cg_net_tensor", "cg_net_tensor_image_stride", "cg_strerror", "cg_version", "cg_last_hip_error", "cg_debug_conv_operand", "cg_debug_copy", "cg_debug_stream", "cg_debug_mfma_loop", "cg_debug_launch_count", "cg_debug_fuse_lrn_pool", "cg_debug_patch_min_tiles", "cg_debug_resident_blocks", "cg_debug_band_kernel",
     "cg_profile_enable", "cg_profile_count", "cg_profile_get",
 ]
 
@@ -90,6 +90,7 @@ def lib():
         L.cg_net_destroy.argtypes = [vp]
         L.cg_debug_copy.argtypes = [vp, vp, sz, vp]
         L.cg_debug_stream.argtypes = [vp, vp, vp, sz, C.c_int, vp]
+        L.cg_debug_mfma_loop.argtypes = [vp, C.c_int, C.c_int, vp]
         L.cg_debug_launch_count.restype = C.c_ulonglong
         L.cg_net_param_count.argtypes = [vp, C.c_int]
         L.cg_net_param_count.restype = C.c_longlong
@@ -263,6 +264,10 @@ def cg_debug_launch_count():
 
 def cg_debug_stream(dst, src, src2, nbytes, mode, stream=None):
     _check(lib().cg_debug_stream(_ptr(dst), _ptr(src), _ptr(src2), nbytes, mode, _stream(stream)), "cg_debug_stream")
+
+
+def cg_debug_mfma_loop(out, blocks, iters, stream=None):
+    _check(lib().cg_debug_mfma_loop(_ptr(out), blocks, iters, _stream(stream)), "cg_debug_mfma_loop")
 
 
 def cg_debug_conv_operand(d, which_pass, operand, row, k, group):

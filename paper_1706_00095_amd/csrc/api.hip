@@ -165,6 +165,35 @@ extern "C" int cg_debug_stream(void *dst, const void *src, const void *src2, siz
     return CG_OK;
 }
 
+// The fp32 matrix pipeline alone: four independent accumulators a wave, so that an instruction
+// never waits for the one before it; operands are lane-dependent numbers the compiler cannot fold.
+namespace cg {
+typedef float v16f_dbg __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void debug_mfma_kernel(float *__restrict__ out, int iters)
+{
+    v16f_dbg a0 = {}, a1 = {}, a2 = {}, a3 = {};
+    const float x = 1.f + (float)threadIdx.x * 0x1p-10f, y = 1.f - (float)(threadIdx.x & 31) * 0x1p-12f;
+    for (int i = 0; i < iters; ++i) {
+        a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, x, a1, 0, 0, 0);
+        a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, x, a2, 0, 0, 0);
+        a3 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, y, a3, 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += a0[r] + a1[r] + a2[r] + a3[r];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+}  // namespace cg
+
+extern "C" int cg_debug_mfma_loop(float *out, int blocks, int iters, void *stream)
+{
+    if (!out || !cg::aligned16(out) || blocks < 1 || blocks > 65536 || iters < 1) return CG_EINVAL;
+    hipLaunchKernelGGL(cg::debug_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), out, iters);
+    CG_HIP_TRY(hipGetLastError());
+    return CG_OK;
+}
+
 extern "C" unsigned long long cg_debug_launch_count(void)
 {
     return cg::g_launches.load(std::memory_order_relaxed);

@@ -4,6 +4,7 @@ without specialisation and with padding, and rectifiers in positions where their
 folded into the producer's store and their backward into the consumer's kernel."""
 import numpy as np
 import pytest
+import torch
 
 import cg_synth
 import paper_1706_00095_amd as cg
@@ -108,3 +109,17 @@ def test_alexnet_shaped_iteration_lrn_pool_modes(orc32, mode):
         cg.cg_debug_fuse_lrn_pool(1)
     lrn = [i for i, ly in enumerate(layers) if ly["kind"] == "lrn"]
     assert [cg.cg_net_layer_fused(gn.net, i) for i in lrn] == [mode, mode]
+
+
+def test_measurement_kernels_run():
+    """The ceiling probes of the benchmark (streaming kernels, matrix-pipeline loop) launch and finish;
+    the copy variant copies."""
+    a = torch.arange(4096, dtype=torch.float32, device="cuda")
+    b = torch.zeros_like(a)
+    cg.cg_debug_stream(b, a, a, a.numel() * 4, 0)
+    out = torch.empty(256 * 3, device="cuda")
+    cg.cg_debug_mfma_loop(out, 3, 7)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and bool(torch.isfinite(out).all())
+    with pytest.raises(Exception):
+        cg.cg_debug_mfma_loop(out, 0, 7)
