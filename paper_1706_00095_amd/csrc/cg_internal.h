@@ -213,9 +213,15 @@ void igemm_host_element(const Operand &op, uint32_t row, uint32_t k, int64_t *of
 struct SplitPlan { uint32_t splits, k_per_split; size_t ws_bytes; };
 SplitPlan plan_split(uint32_t M, uint32_t N, uint32_t K, uint32_t groups);
 size_t igemm_ws_bytes(const IgemmProblem &p);
-int igemm_run(const IgemmProblem &p, void *ws, size_t ws_bytes, hipStream_t stream);
+// rider: a small convolution's bias gradient (db[m] = sum of dy over images and pixels), summed by
+// extra blocks of the K-slice finishing launch, one block per channel, instead of a launch of its
+// own; *rider_taken says whether that happened (it does not when the problem runs without K slices).
+struct BiasRider { const float *dy; int N, M, P; float *db; };
+int igemm_run(const IgemmProblem &p, void *ws, size_t ws_bytes, hipStream_t stream, const BiasRider *rider = nullptr,
+              bool *rider_taken = nullptr);
 // db[m] = sum over n and pixels of dy[n][m][pix]; two passes over `ws`, fixed order
 size_t bias_grad_ws_bytes(int N, int M);
+bool bias_grad_single_launch(int N, int P);       // small enough for one block per channel, no partial sums
 int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, size_t ws_bytes,
                      hipStream_t stream);
 

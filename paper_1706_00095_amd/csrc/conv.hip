@@ -697,12 +697,18 @@ int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy,
     // the GPU, between that kernel and the update the next iteration waits for.
     // (bias_stream: a stream of the caller's that has nothing else to do meanwhile -- a net's first
     // layer has no backward-data -- so that the sums run beside the matrix kernel, not in front of it)
-    if (db) {
+    // A small layer's sums (one block per channel, one launch) ride in the launch that adds the K slices.
+    const bool ride = db && !bias_stream && bias_grad_single_launch(d.N, OH * OW);
+    if (db && !ride) {
         const int rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes,
                                         bias_stream ? bias_stream : stream);
         if (rb) return rb;
     }
-    return igemm_run(p, ws, split_bytes, stream);
+    const BiasRider rider{dy, d.N, d.M, OH * OW, db};
+    bool taken = false;
+    const int rr = igemm_run(p, ws, split_bytes, stream, ride ? &rider : nullptr, &taken);
+    if (rr || !ride || taken) return rr;
+    return bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes, stream);
 }
 
 size_t conv_ws_bytes(const cg_conv_desc &d, int pass)

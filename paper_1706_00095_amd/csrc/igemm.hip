@@ -1778,7 +1778,54 @@ struct FinishArgs {
     int accumulate, relu;
     const float *gate;
     uint32_t total;           // groups * M * N
+    // a convolution's bias gradient riding in the same launch: blocks finish_blocks.. sum one channel each
+    const float *r_dy;
+    int rN, rM, rP;
+    FastDiv r_divQP;
+    float *r_db;
+    uint32_t finish_blocks;
 };
+
+typedef float f4u_b __attribute__((ext_vector_type(4), aligned(4)));
+
+// Sum of dy[n][m][0..P) over the images n_beg..n_end-1, by one block; thread 0 returns it.
+// The (image, group of four pixels) pairs are spread over the threads, each moving 16 bytes
+// (4-byte aligned: planes of an odd pixel count start anywhere) with four loads in flight.
+__device__ __forceinline__ float bias_channel_sum(const float *__restrict__ dy, int M, int P, int m, int n_beg, int n_end,
+                                                  FastDiv divQP)
+{
+    const uint32_t QP = divQP.d, total = (uint32_t)(n_end - n_beg) * QP;
+    float s = 0.f;
+    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += 256 * 4) {
+        f4u_b v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = i0 + u * 256;
+            v[u] = f4u_b{0.f, 0.f, 0.f, 0.f};
+            if (i < total) {
+                const uint32_t n = fdiv(i, divQP), qd = i - n * QP;
+                const float *src = dy + ((size_t)(n_beg + (int)n) * M + m) * P + 4 * qd;
+                const int rem = P - 4 * (int)qd;
+                if (rem >= 4) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f4u_b *>(src));
+                else {
+                    v[u].x = src[0];
+                    if (rem > 1) v[u].y = src[1];
+                    if (rem > 2) v[u].z = src[2];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+    }
+    __shared__ float red[256];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    return red[0];
+}
 
 // C = (sum over the K slices) + bias, written through the problem's output map.  With few slices a
 // thread adds them in slice order.  With many (ROWS = 8) a block owns 32 consecutive elements, its
@@ -1808,8 +1855,15 @@ __device__ __forceinline__ void finish_store(const FinishArgs &a, uint32_t i, fl
 
 template <int ROWS> __global__ __launch_bounds__(256) void splitk_finish_kernel(const FinishArgs a)
 {
+    if (a.r_dy && blockIdx.x >= a.finish_blocks) {       // a rider block: one channel of the bias gradient
+        const int m = (int)(blockIdx.x - a.finish_blocks);
+        const float s = bias_channel_sum(a.r_dy, a.rM, a.rP, m, 0, a.rN, a.r_divQP);
+        if (threadIdx.x == 0) a.r_db[m] = s;
+        return;
+    }
+    const uint32_t nblk = a.r_dy ? a.finish_blocks : gridDim.x;
     if (ROWS == 1) {
-        for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < a.total; i += gridDim.x * 256) {
+        for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < a.total; i += nblk * 256) {
             float s = a.part[i];
             for (int k = 1; k < a.splits; ++k) s += a.part[(int64_t)k * a.plane + i];
             finish_store(a, i, s);
@@ -1818,7 +1872,7 @@ template <int ROWS> __global__ __launch_bounds__(256) void splitk_finish_kernel(
     }
     __shared__ float part[8][33];
     const int el = threadIdx.x & 31, r = threadIdx.x >> 5;
-    for (uint32_t i0 = blockIdx.x * 32; i0 < a.total; i0 += gridDim.x * 32) {
+    for (uint32_t i0 = blockIdx.x * 32; i0 < a.total; i0 += nblk * 32) {
         const uint32_t i = i0 + el;
         float s = 0.f;
         if (i < a.total)
@@ -1865,8 +1919,9 @@ size_t igemm_ws_bytes(const IgemmProblem &p)
     return plan_split(p.M, p.N, p.K, p.groups).ws_bytes;
 }
 
-int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t stream)
+int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t stream, const BiasRider *rider, bool *rider_taken)
 {
+    if (rider_taken) *rider_taken = false;
     const SplitPlan pl = p0.use_patch   ? SplitPlan{1, p0.K, 0}
                          : p0.use_wgrad ? SplitPlan{p0.splits, p0.K, igemm_ws_bytes(p0)}
                                         : plan_split(p0.M, p0.N, p0.K, p0.groups);
@@ -1901,12 +1956,22 @@ int igemm_run(const IgemmProblem &p0, void *ws, size_t ws_bytes, hipStream_t str
     a.divMN = make_fastdiv(p0.M * p0.N);
     a.accumulate = p0.accumulate; a.relu = p0.relu; a.gate = p0.gate;
     a.total = p0.groups * p0.M * p0.N;
+    unsigned riders = 0;
+    if (rider && rider->dy && rider->db && rider->M > 0 && rider->M <= 65536 &&
+        (uint64_t)rider->N * (uint64_t)((rider->P + 3) / 4) < (1ull << 31)) {
+        a.r_dy = rider->dy; a.rN = rider->N; a.rM = rider->M; a.rP = rider->P; a.r_db = rider->db;
+        a.r_divQP = make_fastdiv((uint32_t)(rider->P + 3) / 4);
+        riders = (unsigned)rider->M;
+        if (rider_taken) *rider_taken = true;
+    }
     if (pl.splits >= 16) {
         const unsigned blocks = (a.total + 31) / 32 < 65536 ? (a.total + 31) / 32 : 65536;
-        hipLaunchKernelGGL(splitk_finish_kernel<8>, dim3(blocks), dim3(256), 0, stream, a);
+        a.finish_blocks = blocks;
+        hipLaunchKernelGGL(splitk_finish_kernel<8>, dim3(blocks + riders), dim3(256), 0, stream, a);
     } else {
         const unsigned blocks = (a.total + 255) / 256 < 16384 ? (a.total + 255) / 256 : 16384;
-        hipLaunchKernelGGL(splitk_finish_kernel<1>, dim3(blocks), dim3(256), 0, stream, a);
+        a.finish_blocks = blocks;
+        hipLaunchKernelGGL(splitk_finish_kernel<1>, dim3(blocks + riders), dim3(256), 0, stream, a);
     }
     CG_HIP_TRY(hipGetLastError());
     return CG_OK;
@@ -1926,37 +1991,8 @@ __global__ __launch_bounds__(256) void bias_grad_partial_kernel(const float *__r
 {
     const int m = blockIdx.x, sl = blockIdx.y;
     const int n_beg = sl * n_per, n_end = min(N, n_beg + n_per);
-    const uint32_t QP = divQP.d, total = (uint32_t)(n_end - n_beg) * QP;
-    float s = 0.f;
-    for (uint32_t i0 = threadIdx.x; i0 < total; i0 += 256 * 4) {
-        f4u v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t i = i0 + u * 256;
-            v[u] = f4u{0.f, 0.f, 0.f, 0.f};
-            if (i < total) {
-                const uint32_t n = fdiv(i, divQP), qd = i - n * QP;
-                const float *src = dy + ((size_t)(n_beg + (int)n) * M + m) * P + 4 * qd;
-                const int rem = P - 4 * (int)qd;
-                if (rem >= 4) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(src));
-                else {
-                    v[u].x = src[0];
-                    if (rem > 1) v[u].y = src[1];
-                    if (rem > 2) v[u].z = src[2];
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
-    }
-    __shared__ float red[256];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) part[(size_t)sl * M + m] = red[0];
+    const float s = bias_channel_sum(dy, M, P, m, n_beg, n_end, divQP);
+    if (threadIdx.x == 0) part[(size_t)sl * M + m] = s;
 }
 
 __global__ __launch_bounds__(256) void bias_grad_finish_kernel(const float *__restrict__ part, int M, int S,
@@ -1983,13 +2019,15 @@ size_t bias_grad_ws_bytes(int N, int M)
     return (size_t)bias_slices(N, M) * M * sizeof(float);
 }
 
+bool bias_grad_single_launch(int N, int P) { return (uint64_t)N * (uint64_t)P <= 32768; }
+
 int bias_grad_launch(const float *dy, int N, int M, int P, float *db, void *ws, size_t ws_bytes,
                      hipStream_t stream)
 {
     if (!dy || !db || N <= 0 || M <= 0 || P <= 0) return CG_EINVAL;
     if (!ws || ws_bytes < bias_grad_ws_bytes(N, M)) return CG_ENOSPC;
     // a small layer: one block per channel sums all images and writes db itself (one launch)
-    const int S = (uint64_t)N * P <= 32768 ? 1 : bias_slices(N, M);
+    const int S = bias_grad_single_launch(N, P) ? 1 : bias_slices(N, M);
     const int n_per = (N + S - 1) / S;
     const int S2 = (N + n_per - 1) / n_per;
     float *part = static_cast<float *>(ws);
