@@ -239,7 +239,8 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
 // bias_stream: if not null, the bias sums are enqueued there instead of on `stream` (dy must be complete
 // in that stream's order as well, and the caller joins both streams before db is used)
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
-                         void *ws, size_t ws_bytes, hipStream_t stream, int math = 0, hipStream_t bias_stream = nullptr);
+                         void *ws, size_t ws_bytes, hipStream_t stream, int math = 0, hipStream_t bias_stream = nullptr,
+                         void *bias_ws = nullptr, size_t bias_ws_bytes = 0);
 int fc_fwd_impl(int B, int IN, int OUT, const float *x, const float *W, const float *bias, float *y, void *ws,
                 size_t ws_bytes, int relu, hipStream_t stream, int math = 0);
 int fc_bwd_data_impl(int B, int IN, int OUT, const float *dy, const float *W, float *dx, const float *gate,

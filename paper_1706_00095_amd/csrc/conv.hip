@@ -676,7 +676,8 @@ static IgemmProblem bwd_weight_problem(const cg_conv_desc &d, int OH, int OW, co
 }
 
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,
-                         void *ws, size_t ws_bytes, hipStream_t stream, int math, hipStream_t bias_stream)
+                         void *ws, size_t ws_bytes, hipStream_t stream, int math, hipStream_t bias_stream,
+                         void *bias_ws, size_t bias_ws_bytes)
 {
     if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_bwd_weight", -1);
@@ -696,12 +697,18 @@ int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy,
     // kernel still runs; behind the weight gradient of a net's first layer they would sit, alone on
     // the GPU, between that kernel and the update the next iteration waits for.
     // (bias_stream: a stream of the caller's that has nothing else to do meanwhile -- a net's first
-    // layer has no backward-data -- so that the sums run beside the matrix kernel, not in front of it)
+    // layer has no backward-data -- so that the sums run beside the matrix kernel, not in front of it.
+    // Their partial sums then live in bias_ws, scratch memory that is free in THAT stream's order: `ws`
+    // is only ordered by `stream`, on which earlier launches may still be reading it.)
     // A small layer's sums (one block per channel, one launch) ride in the launch that adds the K slices.
     const bool ride = db && !bias_stream && bias_grad_single_launch(d.N, OH * OW);
     if (db && !ride) {
-        const int rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes,
-                                        bias_stream ? bias_stream : stream);
+        int rb;
+        if (bias_stream) {
+            if (!bias_ws || bias_ws_bytes < bias_bytes) return CG_ENOSPC;
+            rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, bias_ws, bias_bytes, bias_stream);
+        } else
+            rb = bias_grad_launch(dy, d.N, d.M, OH * OW, db, static_cast<char *>(ws) + split_bytes, bias_bytes, stream);
         if (rb) return rb;
     }
     const BiasRider rider{dy, d.N, d.M, OH * OW, db};

@@ -544,8 +544,10 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
             if (d.kind == CG_LAYER_CONV)
                 // without a backward-data pass of its own (a first layer) the compute stream is idle during this
                 // turn: the bias sums go there, beside the weight gradient; the update waits for both streams
+                // (their partial sums in the compute stream's own scratch region: the other region may still be
+                // read by an earlier layer's weight-gradient kernels, which only the third stream orders)
                 rc = conv_bwd_weight_impl(ly.conv, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math,
-                                          (!serial && !want_dx) ? S0 : nullptr);
+                                          (!serial && !want_dx) ? S0 : nullptr, scratch, scratch_bytes);
             else
                 rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
             if (rc == CG_OK && want_dx) {
