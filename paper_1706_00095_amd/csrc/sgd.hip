@@ -62,7 +62,7 @@ __device__ __forceinline__ T rank_sum(const T s, const T *q)
 }
 
 // One launch serves up to MAXB buckets: block b belongs to the bucket whose [first, first + blocks)
-// range contains it and updates UNR x 256 consecutive float4 groups there, every load of a group
+// range contains it and updates UNR x TB consecutive float4 groups there, every load of a group
 // issued before the first use.  No loop: one short-lived block per few KB of each stream keeps far
 // more loads in flight than a persistent grid does, which is what the memory system rewards here.
 // Every access is non-temporal, the reads of w and v and the two stores included: each byte is
@@ -71,9 +71,15 @@ __device__ __forceinline__ T rank_sum(const T s, const T *q)
 // the eight buckets' size; either hint alone gained nothing or lost).
 constexpr int MAXB = 8;          // buckets per launch
 constexpr int KMAX_TAB = 16;     // peers per bucket in the table (more: the run-time-K kernel)
-// float4 groups per thread: the more streams a thread reads, the fewer groups it needs in flight
-// (measured on the same array: K = 8 with four groups 75 %, with two 72 %; K = 16 with one 73 %, with two 72 %)
-constexpr int unr_for(int K) { return K <= 4 ? 2 : K <= 8 ? 4 : 1; }
+// Launch shape: blocks of ONE wave, one float4 group per thread -- 1 KB of every stream per block --
+// for every K.  Measured on the eight buckets in one launch, same box, percent of 8 TB/s
+// (groups per thread x threads per block): K = 4: 1x64 76.2, 1x128 72.5, 1x256 72.6, 2x64 71.1,
+// 2x128 72.7, 2x256 72.6, 4x64 72.2, 4x128 72.5; K = 8: 1x64 74.2, 1x128 69.9, 1x256 71.1, 2x64 69.7,
+// 4x64 70.5, 4x128 71.5, 4x256 72.3; K = 16: 1x64 73.5, 1x128 72.0, 1x192 68.7, 1x256 67.5, 1x512 69.3.
+// A wave that is its own block leaves as soon as its own loads have come back and been stored;
+// nothing in the kernel needs a second wave.
+constexpr int unr_for(int) { return 1; }
+constexpr int tb_for(int) { return 64; }
 
 struct Bucket {
     float *w, *v;
@@ -88,22 +94,22 @@ struct BucketTable {
 };
 
 template <int KC, bool TREE>
-__global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, const cg_sgd c)
+__global__ __launch_bounds__(tb_for(KC)) void reduce_sgd_kernel(const BucketTable tab, const cg_sgd c)
 {
-    constexpr int UNR = unr_for(KC);
+    constexpr int UNR = unr_for(KC), TB = tb_for(KC);
     int bi = 0;
 #pragma unroll
     for (int j = 1; j < MAXB; ++j)
         if (j < tab.nb && blockIdx.x >= tab.b[j].first_block) bi = j;
     const Bucket &bk = tab.b[bi];
     const size_t n = bk.n, n4 = n / 4;
-    const size_t i0 = (size_t)(blockIdx.x - bk.first_block) * (256 * UNR) + threadIdx.x;
+    const size_t i0 = (size_t)(blockIdx.x - bk.first_block) * (TB * UNR) + threadIdx.x;
     const f4 *g4 = reinterpret_cast<const f4 *>(bk.g);
     f4 *w4 = reinterpret_cast<f4 *>(bk.w), *v4 = reinterpret_cast<f4 *>(bk.v);
     f4 s[UNR], q[UNR][KC > 0 ? KC : 1], wi[UNR], vi[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-        const size_t i = i0 + (size_t)u * 256;
+        const size_t i = i0 + (size_t)u * TB;
         if (i < n4) {
             s[u] = __builtin_nontemporal_load(g4 + i);
 #pragma unroll
@@ -118,7 +124,7 @@ __global__ __launch_bounds__(256) void reduce_sgd_kernel(const BucketTable tab, 
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-        const size_t i = i0 + (size_t)u * 256;
+        const size_t i = i0 + (size_t)u * TB;
         if (i < n4) {
             const f4 t = rank_sum<KC, TREE, f4>(s[u], q[u]);
             f4 wo, vo;
@@ -240,8 +246,8 @@ void launch_table(const BucketTable &tab, unsigned blocks, int K, bool tree, con
     // up to three ranks the two associations are the same sum
     switch (tree && K >= 3 ? 100 + K : K) {
 #define CG_CASE(k)                                                                                         \
-    case k: hipLaunchKernelGGL((reduce_sgd_kernel<k, false>), dim3(blocks), dim3(256), 0, stream, tab, c); break; \
-    case 100 + k: hipLaunchKernelGGL((reduce_sgd_kernel<k, true>), dim3(blocks), dim3(256), 0, stream, tab, c); break;
+    case k: hipLaunchKernelGGL((reduce_sgd_kernel<k, false>), dim3(blocks), dim3(tb_for(k)), 0, stream, tab, c); break; \
+    case 100 + k: hipLaunchKernelGGL((reduce_sgd_kernel<k, true>), dim3(blocks), dim3(tb_for(k)), 0, stream, tab, c); break;
         CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7) CG_CASE(8)
         CG_CASE(9) CG_CASE(10) CG_CASE(11) CG_CASE(12) CG_CASE(13) CG_CASE(14) CG_CASE(15) CG_CASE(16)
 #undef CG_CASE
@@ -293,7 +299,7 @@ int grad_reduce_sgd_multi_impl(int nb, float *const *w, float *const *v, const f
         double bytes = 0.0;
         while (i < nb && tab.nb < MAXB) {
             if (n[i] == 0) { ++i; continue; }
-            const unsigned long long per_block = 256ull * unr_for(K);
+            const unsigned long long per_block = (unsigned long long)tb_for(K) * unr_for(K);
             const unsigned long long bb = (n[i] / 4 + per_block - 1) / per_block;
             const unsigned long long need = bb ? bb : 1;           // a bucket of 1..3 elements still needs its tail block
             if (blocks + need >= (1ull << 31)) break;
