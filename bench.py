@@ -144,6 +144,17 @@ def mfma_achievable(cg, torch, blocks=512, iters=20000, reps=5):
             "what": f"{blocks} blocks x 4 waves x {iters} x 4 independent v_mfma_f32_32x32x2_f32, no memory traffic"}
 
 
+def gpu_clocks():
+    """Clock levels as the box reports them right after the timed work (rocm-smi; None if it is not there)."""
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        return {k.strip(":"): v for k, v in card.items() if "clock speed" in k and ("sclk" in k or "mclk" in k or "fclk" in k)}
+    except Exception:
+        return None
+
+
 def conv_layers_standalone(cg, torch, B, reps=10, math=0):
     """Configuration 2: every AlexNet-shaped convolution layer alone, forward / backward-data /
     backward-weight through the C ABI (the first layer's backward-data included, which a net skips),
@@ -464,6 +475,7 @@ def main():
     launches_per_step = (cg.cg_debug_launch_count() - launches0) / args.steps
     cg.cg_profile_enable(False)
     agg = collect_profile(cg)
+    clocks = gpu_clocks()
     loss = float(st["loss"].cpu()[0])
     ms_per_step = wall / args.steps * 1e3
     roofline, update_roofline, totals = kernel_rooflines(agg, args.steps, traffic)
@@ -583,6 +595,7 @@ def main():
         "matrix_core_kernels_exclusive": totals_excl,
         "serial_schedule_ms_per_step": serial_ms,
         "kernel_launches_per_step": launches_per_step,
+        "gpu_clocks_after_timed_region": clocks,
         "grad_update": grad_update,
         "hbm_achievable": achievable,
         "mfma_achievable": mfma_peak,
