@@ -107,6 +107,33 @@ def test_gathered_and_strided_kernels_exact(orc32, name):
         assert planes >= (16 if "many" in name else 2), planes
 
 
+def test_small_layer_bias_gradient_rides_in_the_k_slice_launch(orc32):
+    """Backward-weight of a small layer whose reduction is cut into K slices: two launches in all (the
+    matrix kernel and the one that adds the slices, whose extra blocks sum the bias gradient), db exact;
+    a layer too large for one block per channel keeps its own bias launches."""
+    B, cfg = EXTRA_SHAPES["splitk_few"]
+    c, x, w, b, dy = cg_synth.conv_layer_int_tensors(cfg, B, 77)
+    d, od = _descs(B, c)
+    dx_, dyd = dev(x), dev(dy)
+    conv_bwd_weight(d, dx_, dyd)
+    torch.cuda.synchronize()
+    n0 = cg.cg_debug_launch_count()
+    dw, db = conv_bwd_weight(d, dx_, dyd)
+    torch.cuda.synchronize()
+    assert cg.cg_debug_launch_count() - n0 == 2
+    rdw, rdb = orc32.conv_bwd_weight(od, x, dy)
+    _same(host(dw), rdw, "backward-weight")
+    _same(host(db), rdb, "bias gradient")
+    big = cg.conv_desc(64, 32, 27, 27, 64, 3, stride=1, pad=1, groups=1)         # 64 * 729 pixels a channel: two-phase sums
+    xb = torch.zeros((64, 32, 27, 27), device="cuda")
+    dyb = torch.ones((64, 64, 27, 27), device="cuda")
+    n0 = cg.cg_debug_launch_count()
+    _, dbb = conv_bwd_weight(big, xb, dyb)
+    torch.cuda.synchronize()
+    assert cg.cg_debug_launch_count() - n0 == 4
+    assert bool((dbb == 64 * 729).all())
+
+
 @pytest.fixture
 def patch_path():
     cg.cg_debug_patch_min_tiles(1)
