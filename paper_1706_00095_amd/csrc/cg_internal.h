@@ -232,10 +232,27 @@ size_t conv_ws_bytes(const cg_conv_desc &d, int pass);
 size_t fc_ws_bytes(int B, int IN, int OUT, int pass);
 // relu != 0: y = max(conv + bias, 0), the rectifier that follows folded into the store
 // math: CG_MATH_* (what the matrix instructions multiply in; workspace sizes do not depend on it)
+// prepared: if not null, the rearranged copy of the filters this pass multiplies with (what
+// conv_fwd_filter_prep / conv_bwd_data_filter_prep describe for this descriptor), made beforehand by
+// filter_prep_launch from the same w; the pass then launches no rearrangement of its own
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0, int math = 0);
+                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0, int math = 0,
+                  const float *prepared = nullptr);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
-                       size_t ws_bytes, int accumulate, hipStream_t stream, int math = 0);
+                       size_t ws_bytes, int accumulate, hipStream_t stream, int math = 0, const float *prepared = nullptr);
+// Which rearranged copy of its filters a pass needs (kind CG_PREP_NONE: it reads w itself), and how
+// many floats the copy has.  The answer follows the same kernel choice the pass itself makes.
+enum { CG_PREP_NONE = 0, CG_PREP_TRANSPOSE, CG_PREP_PERMUTE_FWD, CG_PREP_PERMUTE_BWD, CG_PREP_STRIDED_TAPS, CG_PREP_STRIDED_ROWS };
+struct FilterPrep {
+    int kind;
+    size_t floats;
+    int Mg, Cg, KH, KW, sh, sw, Ah, Aw;
+};
+FilterPrep conv_fwd_filter_prep(const cg_conv_desc &d);
+FilterPrep conv_bwd_data_filter_prep(const cg_conv_desc &d);
+size_t conv_filter_prep_max_floats(const cg_conv_desc &d);      // upper bound of either copy, for sizing
+// n copies, eight per launch: job i reads w[i] and writes dst[i] (16-byte aligned, jobs[i].floats floats)
+int filter_prep_launch(int n, const FilterPrep *jobs, const float *const *w, float *const *dst, hipStream_t stream);
 // bias_stream: if not null, the bias sums are enqueued there instead of on `stream` (dy must be complete
 // in that stream's order as well, and the caller joins both streams before db is used)
 int conv_bwd_weight_impl(const cg_conv_desc &d, const float *x, const float *dy, float *dw, float *db,

@@ -46,58 +46,108 @@ IndexMap tap_map(const cg_conv_desc &d, int Cg)
 
 // wt[g][c][ml][kh][kw] = w[g*Mg + ml][c][kh][kw]: the filters as the row-major matrix that
 // backward-data multiplies with (rows = input channels, reduction index = (ml, kh, kw))
-__global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__restrict__ w, float *__restrict__ wt,
-                                                                int G, int Mg, int Cg, int KK)
+__device__ __forceinline__ float transpose_filters_elem(const float *__restrict__ w, size_t i, int Mg, int Cg, int KK)
 {
-    const size_t total = (size_t)G * Mg * Cg * KK;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const int kk = (int)(i % KK);
-        size_t r = i / KK;
-        const int ml = (int)(r % Mg); r /= Mg;
-        const int c = (int)(r % Cg);
-        const int g = (int)(r / Cg);
-        wt[i] = w[(((size_t)g * Mg + ml) * Cg + c) * KK + kk];
-    }
+    const int kk = (int)(i % KK);
+    size_t r = i / KK;
+    const int ml = (int)(r % Mg); r /= Mg;
+    const int c = (int)(r % Cg);
+    const int g = (int)(r / Cg);
+    return w[(((size_t)g * Mg + ml) * Cg + c) * KK + kk];
 }
 
 // Filters as the tap-major matrix the patch kernel multiplies with: dst[g][r][t][c], t = kh*KW + kw.
 // Forward (bwd = 0): r = output channel, c = input channel: dst = w[g*Mg + r][c][t].
 // Backward-data (bwd = 1): r = input channel, c = output channel: dst = w[g*Mg + c][r][t].
-__global__ __launch_bounds__(256) void permute_filters_kernel(const float *__restrict__ w, float *__restrict__ dst,
-                                                              int G, int Mg, int Cg, int KK, int bwd)
+__device__ __forceinline__ float permute_filters_elem(const float *__restrict__ w, size_t i, int Mg, int Cg, int KK, int bwd)
 {
     const int R = bwd ? Cg : Mg, Cr = bwd ? Mg : Cg;
-    const size_t total = (size_t)G * Mg * Cg * KK;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const int c = (int)(i % Cr);
-        size_t q = i / Cr;
-        const int t = (int)(q % KK); q /= KK;
-        const int r = (int)(q % R);
-        const int g = (int)(q / R);
-        const int m = bwd ? c : r, ci = bwd ? r : c;
-        dst[i] = w[(((size_t)g * Mg + m) * Cg + ci) * KK + t];
-    }
+    const int c = (int)(i % Cr);
+    size_t q = i / Cr;
+    const int t = (int)(q % KK); q /= KK;
+    const int r = (int)(q % R);
+    const int g = (int)(q / R);
+    const int m = bwd ? c : r, ci = bwd ? r : c;
+    return w[(((size_t)g * Mg + m) * Cg + ci) * KK + t];
 }
 
 // Filters as the matrix of strided backward-data (see bwd_data_strided_problem): row (c, rh, rw),
 // reduction index (m, a, b) with filter tap kh = rh + sh*a, kw = rw + sw*b (zero where that tap
 // does not exist).  tap_major = 1: dst[g][row][t = a*Aw + b][m] (the patch kernel's order);
 // 0: dst[g][row][m][t] (the gathered kernel's).
+__device__ __forceinline__ float strided_filters_elem(const float *__restrict__ w, size_t i, int Mg, int Cg, int KH, int KW,
+                                                      int sh, int sw, int Ah, int Aw, int tap_major)
+{
+    const int R = Cg * sh * sw, T = Ah * Aw;
+    int m, t;
+    size_t q;
+    if (tap_major) { m = (int)(i % Mg); q = i / Mg; t = (int)(q % T); q /= T; }
+    else { t = (int)(i % T); q = i / T; m = (int)(q % Mg); q /= Mg; }
+    const int row = (int)(q % R), g = (int)(q / R);
+    const int rw = row % sw, rh = (row / sw) % sh, c = row / (sw * sh);
+    const int kh = rh + sh * (t / Aw), kw = rw + sw * (t % Aw);
+    return (kh < KH && kw < KW) ? w[(((size_t)g * Mg + m) * Cg + c) * KH * KW + kh * KW + kw] : 0.f;
+}
+
+__global__ __launch_bounds__(256) void transpose_filters_kernel(const float *__restrict__ w, float *__restrict__ wt,
+                                                                int G, int Mg, int Cg, int KK)
+{
+    const size_t total = (size_t)G * Mg * Cg * KK;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256)
+        wt[i] = transpose_filters_elem(w, i, Mg, Cg, KK);
+}
+
+__global__ __launch_bounds__(256) void permute_filters_kernel(const float *__restrict__ w, float *__restrict__ dst,
+                                                              int G, int Mg, int Cg, int KK, int bwd)
+{
+    const size_t total = (size_t)G * Mg * Cg * KK;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256)
+        dst[i] = permute_filters_elem(w, i, Mg, Cg, KK, bwd);
+}
+
 __global__ __launch_bounds__(256) void strided_filters_kernel(const float *__restrict__ w, float *__restrict__ dst,
                                                               int G, int Mg, int Cg, int KH, int KW, int sh, int sw,
                                                               int Ah, int Aw, int tap_major)
 {
-    const int R = Cg * sh * sw, T = Ah * Aw;
-    const size_t total = (size_t)G * R * T * Mg;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        int m, t;
-        size_t q;
-        if (tap_major) { m = (int)(i % Mg); q = i / Mg; t = (int)(q % T); q /= T; }
-        else { t = (int)(i % T); q = i / T; m = (int)(q % Mg); q /= Mg; }
-        const int row = (int)(q % R), g = (int)(q / R);
-        const int rw = row % sw, rh = (row / sw) % sh, c = row / (sw * sh);
-        const int kh = rh + sh * (t / Aw), kw = rw + sw * (t % Aw);
-        dst[i] = (kh < KH && kw < KW) ? w[(((size_t)g * Mg + m) * Cg + c) * KH * KW + kh * KW + kw] : 0.f;
+    const size_t total = (size_t)G * (Cg * sh * sw) * (Ah * Aw) * Mg;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256)
+        dst[i] = strided_filters_elem(w, i, Mg, Cg, KH, KW, sh, sw, Ah, Aw, tap_major);
+}
+
+// The rearranged filters of several layers in one launch (a net prepares those of all its layers at
+// the start of an iteration): block b belongs to the job whose [first_block, ...) range holds it and
+// writes 1024 consecutive elements of that job's copy.
+constexpr int kPrepJobs = 8;
+struct PrepJob {
+    const float *w;
+    float *dst;
+    int kind, Mg, Cg, KH, KW, sh, sw, Ah, Aw;
+    unsigned first_block;
+    unsigned long long total;
+};
+struct PrepTable {
+    PrepJob j[kPrepJobs];
+    int n;
+};
+__global__ __launch_bounds__(256) void prepare_filters_kernel(const PrepTable t)
+{
+    int ji = 0;
+#pragma unroll
+    for (int k = 1; k < kPrepJobs; ++k)
+        if (k < t.n && blockIdx.x >= t.j[k].first_block) ji = k;
+    const PrepJob &jb = t.j[ji];
+    const size_t base = (size_t)(blockIdx.x - jb.first_block) * 1024 + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const size_t i = base + (size_t)u * 256;
+        if (i >= jb.total) break;
+        float v;
+        if (jb.kind == CG_PREP_TRANSPOSE) v = transpose_filters_elem(jb.w, i, jb.Mg, jb.Cg, jb.KH * jb.KW);
+        else if (jb.kind == CG_PREP_PERMUTE_FWD) v = permute_filters_elem(jb.w, i, jb.Mg, jb.Cg, jb.KH * jb.KW, 0);
+        else if (jb.kind == CG_PREP_PERMUTE_BWD) v = permute_filters_elem(jb.w, i, jb.Mg, jb.Cg, jb.KH * jb.KW, 1);
+        else v = strided_filters_elem(jb.w, i, jb.Mg, jb.Cg, jb.KH, jb.KW, jb.sh, jb.sw, jb.Ah, jb.Aw,
+                                      jb.kind == CG_PREP_STRIDED_TAPS ? 1 : 0);
+        jb.dst[i] = v;
     }
 }
 
@@ -341,7 +391,7 @@ static void tap_major_filters(IgemmProblem &p, const float *m, int rows, int K, 
 static bool math_ok(int math) { return math == CG_MATH_FP32 || math == CG_MATH_BF16 || math == CG_MATH_BF16X3; }
 
 int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const float *bias, float *y, void *ws,
-                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride, int math)
+                  size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride, int math, const float *prepared)
 {
     if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_fwd", -1);
@@ -360,9 +410,11 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
         const size_t wt_bytes = round256((size_t)d.M * Cg * KK * sizeof(float));
         if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
         if (!aligned16(ws)) return CG_EINVAL;
-        const int rc2 = permute_filters(w, static_cast<float *>(ws), G, Mg, Cg, KK, 0, stream);
-        if (rc2) return rc2;
-        tap_major_filters(p, static_cast<const float *>(ws), Mg, Cg * KK, (uint64_t)d.M * Cg * KK);
+        if (!prepared) {
+            const int rc2 = permute_filters(w, static_cast<float *>(ws), G, Mg, Cg, KK, 0, stream);
+            if (rc2) return rc2;
+        }
+        tap_major_filters(p, prepared ? prepared : static_cast<const float *>(ws), Mg, Cg * KK, (uint64_t)d.M * Cg * KK);
         return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
     }
     return igemm_run(p, ws, ws_bytes, stream);
@@ -536,7 +588,7 @@ static int strided_filters(const float *w, float *dst, const cg_conv_desc &d, co
 }
 
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
-                       size_t ws_bytes, int accumulate, hipStream_t stream, int math)
+                       size_t ws_bytes, int accumulate, hipStream_t stream, int math, const float *prepared)
 {
     if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_bwd_data", -1);
@@ -549,12 +601,14 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
         if (!aligned16(ws)) return CG_EINVAL;
         float *wt = static_cast<float *>(ws);
-        IgemmProblem p = bwd_data_strided_problem(d, sg, OH, OW, dy, wt, dx, accumulate);
+        IgemmProblem p = bwd_data_strided_problem(d, sg, OH, OW, dy, prepared ? prepared : wt, dx, accumulate);
         p.gate = gate;
         p.math = math;
         const bool patch = bwd_data_strided_patch(d, sg, OH, OW, dy, p);
-        const int rc2 = strided_filters(w, wt, d, sg, patch ? 1 : 0, stream);
-        if (rc2) return rc2;
+        if (!prepared) {
+            const int rc2 = strided_filters(w, wt, d, sg, patch ? 1 : 0, stream);
+            if (rc2) return rc2;
+        }
         return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
     }
     if ((d.stride_h != 1 || d.stride_w != 1) && math != CG_MATH_FP32) return CG_EUNSUPPORTED;   // plain vector arithmetic below
@@ -601,28 +655,107 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
     if (!ws || ws_bytes < wt_bytes) return CG_ENOSPC;
     if (!aligned16(ws)) return CG_EINVAL;
     float *wt = static_cast<float *>(ws);
+    const float *wuse = prepared ? prepared : wt;
     {
-        IgemmProblem pp = bwd_data_problem(d, OH, OW, dy, wt, dx, accumulate);
+        IgemmProblem pp = bwd_data_problem(d, OH, OW, dy, wuse, dx, accumulate);
         pp.gate = gate;
         pp.math = math;
         if (bwd_data_patch(d, OH, OW, dy, pp)) {
-            const int rc2 = permute_filters(w, wt, G, Mg, Cg, KK, 1, stream);
-            if (rc2) return rc2;
-            tap_major_filters(pp, wt, Cg, Mg * KK, (uint64_t)d.M * Cg * KK);
+            if (!prepared) {
+                const int rc2 = permute_filters(w, wt, G, Mg, Cg, KK, 1, stream);
+                if (rc2) return rc2;
+            }
+            tap_major_filters(pp, wuse, Cg, Mg * KK, (uint64_t)d.M * Cg * KK);
             return igemm_run(pp, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
         }
     }
     const bool in_place = bwd_data_reads_filters_in_place(d);
-    if (!in_place) {
+    if (!in_place && !prepared) {
         const size_t total = (size_t)d.M * Cg * KK;
         const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
         hipLaunchKernelGGL(transpose_filters_kernel, dim3(blocks), dim3(256), 0, stream, w, wt, G, Mg, Cg, KK);
         CG_HIP_TRY(hipGetLastError());
     }
-    IgemmProblem p = bwd_data_problem(d, OH, OW, dy, in_place ? w : wt, dx, accumulate);
+    IgemmProblem p = bwd_data_problem(d, OH, OW, dy, in_place ? w : wuse, dx, accumulate);
     p.gate = gate;
     p.math = math;
     return igemm_run(p, static_cast<char *>(ws) + wt_bytes, ws_bytes - wt_bytes, stream);
+}
+
+FilterPrep conv_fwd_filter_prep(const cg_conv_desc &d)
+{
+    FilterPrep f{};
+    int OH, OW;
+    if (conv_check(&d, &OH, &OW)) return f;
+    IgemmProblem p = fwd_problem(d, OH, OW, nullptr, nullptr, nullptr, nullptr);
+    if (!fwd_patch(d, OH, OW, nullptr, p)) return f;
+    f.kind = CG_PREP_PERMUTE_FWD;
+    f.Mg = d.M / d.groups; f.Cg = d.C / d.groups; f.KH = d.KH; f.KW = d.KW;
+    f.floats = (size_t)d.M * f.Cg * d.KH * d.KW;
+    return f;
+}
+
+FilterPrep conv_bwd_data_filter_prep(const cg_conv_desc &d)
+{
+    FilterPrep f{};
+    int OH, OW;
+    if (conv_check(&d, &OH, &OW)) return f;
+    f.Mg = d.M / d.groups; f.Cg = d.C / d.groups; f.KH = d.KH; f.KW = d.KW;
+    StridedGeom sg;
+    if ((d.stride_h != 1 || d.stride_w != 1) && strided_geom(d, sg)) {
+        IgemmProblem p = bwd_data_strided_problem(d, sg, OH, OW, nullptr, nullptr, nullptr, 0);
+        f.kind = bwd_data_strided_patch(d, sg, OH, OW, nullptr, p) ? CG_PREP_STRIDED_TAPS : CG_PREP_STRIDED_ROWS;
+        f.sh = sg.sh; f.sw = sg.sw; f.Ah = sg.Ah; f.Aw = sg.Aw;
+        f.floats = (size_t)d.groups * sg.R * sg.Kp;
+        return f;
+    }
+    if (d.stride_h != 1 || d.stride_w != 1) return f;            // the vector kernels read w itself
+    IgemmProblem pp = bwd_data_problem(d, OH, OW, nullptr, nullptr, nullptr, 0);
+    if (bwd_data_patch(d, OH, OW, nullptr, pp)) f.kind = CG_PREP_PERMUTE_BWD;
+    else if (!bwd_data_reads_filters_in_place(d)) f.kind = CG_PREP_TRANSPOSE;
+    else return f;
+    f.floats = (size_t)d.M * f.Cg * d.KH * d.KW;
+    return f;
+}
+
+size_t conv_filter_prep_max_floats(const cg_conv_desc &d)
+{
+    size_t m = (size_t)d.M * (d.C / d.groups) * d.KH * d.KW;
+    StridedGeom sg;
+    if ((d.stride_h != 1 || d.stride_w != 1) && strided_geom(d, sg)) {
+        const size_t s2 = (size_t)d.groups * sg.R * sg.Kp;
+        if (s2 > m) m = s2;
+    }
+    return m;
+}
+
+int filter_prep_launch(int n, const FilterPrep *jobs, const float *const *w, float *const *dst, hipStream_t stream)
+{
+    int i = 0;
+    while (i < n) {
+        PrepTable t{};
+        unsigned long long blocks = 0;
+        while (i < n && t.n < kPrepJobs) {
+            const FilterPrep &f = jobs[i];
+            if (f.kind == CG_PREP_NONE || f.floats == 0) { ++i; continue; }
+            if (!w[i] || !dst[i] || !aligned16(dst[i])) return CG_EINVAL;
+            const unsigned long long need = (f.floats + 1023) / 1024;
+            if (blocks + need >= (1ull << 31)) break;
+            PrepJob &j = t.j[t.n++];
+            j.w = w[i]; j.dst = dst[i]; j.kind = f.kind; j.Mg = f.Mg; j.Cg = f.Cg; j.KH = f.KH; j.KW = f.KW;
+            j.sh = f.sh; j.sw = f.sw; j.Ah = f.Ah; j.Aw = f.Aw;
+            j.first_block = (unsigned)blocks; j.total = f.floats;
+            blocks += need;
+            ++i;
+        }
+        if (t.n == 0) {
+            if (i < n) return CG_EUNSUPPORTED;
+            break;
+        }
+        hipLaunchKernelGGL(prepare_filters_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, t);
+        CG_HIP_TRY(hipGetLastError());
+    }
+    return CG_OK;
 }
 
 // The reduction runs over pixels (n, oh, ow).  Its index space pads every image's OH*OW pixels to

@@ -75,6 +75,10 @@ struct cg_net {
         // with respect to it are never written.
         int fused_pool = -1, fused_lrn = -1;
         bool fused_pool_bwd = false;          // (LRN layer) backward fused as well
+        // (CONV) room for the rearranged copies of the filters that forward and backward-data multiply
+        // with; all of a net's copies are made by one or a few launches at the start of an iteration
+        size_t prep_fwd_off = 0, prep_bd_off = 0;
+        const float *prep_fwd = nullptr, *prep_bd = nullptr;      // per step: the copy, or null where the pass reads w itself
     };
 
     int B = 0, C = 0, H = 0, W = 0;
@@ -279,6 +283,12 @@ extern "C" int cg_net_create(const cg_layer_desc *descs, int L, int B, int C, in
     }
     if (rc == CG_OK) {
         net->loss_off = off; off += round_up((size_t)B, 64);
+        for (Layer &ly : net->layers)
+            if (ly.d.kind == CG_LAYER_CONV) {
+                const size_t n = round_up(conv_filter_prep_max_floats(ly.conv), 64);
+                ly.prep_fwd_off = off; off += n;
+                ly.prep_bd_off = off; off += n;
+            }
         net->scratch_off = off; net->scratch_bytes = round_up(scratch, 256);
         off += 2 * (net->scratch_bytes / sizeof(float));
         net->ws_floats = off;
@@ -401,6 +411,44 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
 
     hipEvent_t waited_upd = nullptr;             // the update event the compute stream waited for last
 
+    // ---- the rearranged filter copies of every convolution, for forward and backward-data of this
+    // iteration, eight layers a launch (the model changes again only in this iteration's updates).
+    // Their layers' updates of the previous call must have landed: the first layer's is the last one
+    // the update stream runs, so nothing is lost by waiting for them up front.
+    {
+        std::vector<FilterPrep> jobs;
+        std::vector<const float *> jw;
+        std::vector<float *> jd;
+        for (int i = 0; i < L; ++i) {
+            Layer &ly = net->layers[i];
+            if (ly.d.kind != CG_LAYER_CONV) continue;
+            ly.prep_fwd = ly.prep_bd = nullptr;
+            const FilterPrep f = conv_fwd_filter_prep(ly.conv);
+            if (f.kind != CG_PREP_NONE) {
+                ly.prep_fwd = base + ly.prep_fwd_off;
+                jobs.push_back(f); jw.push_back(ly.w); jd.push_back(base + ly.prep_fwd_off);
+            }
+            const int s0 = ly.d.inputs[0];
+            if (ly.needs_grad && s0 >= 0 && net->layers[s0].needs_grad) {
+                const FilterPrep b = conv_bwd_data_filter_prep(ly.conv);
+                if (b.kind != CG_PREP_NONE) {
+                    ly.prep_bd = base + ly.prep_bd_off;
+                    jobs.push_back(b); jw.push_back(ly.w); jd.push_back(base + ly.prep_bd_off);
+                }
+            }
+            if ((ly.prep_fwd || ly.prep_bd) && ly.n_params && ly.upd_pending) {
+                if (ly.upd_event != waited_upd) CG_HIP_TRY(hipStreamWaitEvent(S0, ly.upd_event, 0));
+                waited_upd = ly.upd_event;
+                ly.upd_pending = false;
+            }
+        }
+        if (!jobs.empty()) {
+            ProfTag tag("filter_prep", -1);
+            rc = filter_prep_launch((int)jobs.size(), jobs.data(), jw.data(), jd.data(), S0);
+            if (rc) return rc;
+        }
+    }
+
     // ---- forward, layers 1..L --------------------------------------------------------------
     for (int i = 0; i < L && rc == CG_OK; ++i) {
         Layer &ly = net->layers[i];
@@ -419,7 +467,7 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
         switch (d.kind) {
         case CG_LAYER_CONV:
             rc = conv_fwd_impl(ly.conv, in, ly.w, ly.w + ly.n_weights, out, scratch, scratch_bytes, ly.fused_relu, S0,
-                               ly.out_img_stride, math);
+                               ly.out_img_stride, math, ly.prep_fwd);
             break;
         case CG_LAYER_FC:
             rc = fc_fwd_impl(B, ly.inC * ly.inH * ly.inW, d.fc_out, in, ly.w, ly.w + ly.n_weights, out, scratch,
@@ -552,7 +600,7 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                 rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
             if (rc == CG_OK && want_dx) {
                 if (d.kind == CG_LAYER_CONV)
-                    rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0, math);
+                    rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0, math, ly.prep_bd);
                 else
                     rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0, math);
             }
