@@ -1,9 +1,9 @@
 """Matrix-pipeline occupancy per kernel from one rocprofv3 counter run.
 
     rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES --kernel-trace --output-format csv \\
-              -d gpurun_out/pmc_m -o m -- python3 bench.py --steps 3 --warmup 2 --cpu-sample 0 --serial --skip-update-bench
-    python3 paper_1706_00095_amd/pmc_mfma_busy.py gpurun_out/pmc_m/m_counter_collection.csv \\
-              gpurun_out/pmc_m/m_kernel_trace.csv <out.txt> '<bench arguments>'
+              -d <dir> -o m -- python3 bench.py <bench arguments>
+    python3 paper_1706_00095_amd/pmc_mfma_busy.py <dir>/m_counter_collection.csv \\
+              <dir>/m_kernel_trace.csv <out.txt> '<bench arguments>'
 
 Per kernel label (the labels of pmc_traffic.py), over the matrix-core launches of the run:
   busy    = SQ_BUSY_CU_CYCLES / (duration x 2.4 GHz x 256 compute units): share of the launch's duration in
