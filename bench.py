@@ -3,11 +3,12 @@
 gradient aggregation over K peers + model update, overlapped on three streams) on one MI355X.
 
 Prints ONE JSON line.  `value` is images/s of whole iterations with every input resident in
-HBM.  `roofline` describes the matrix-core kernel that takes the most time inside the step and
-`update_roofline` the fused gradient-sum + update kernel, both timed with HIP events around each
-launch on its own stream while the kernel has the GPU to itself (a few more iterations with the
-one-stream schedule, right after the timed region); the `*_in_timed_region` objects hold the same
-kernels' durations inside the timed region, where up to three kernels share the GPU.
+HBM, timed without any instrumentation (two HIP events around every launch cost the three-stream
+step 0.35-0.45 ms, 4 %).  Right after the timed region the same iterations run again with those
+events: once with the three-stream schedule (`*_three_stream_pass`: up to three kernels share the
+GPU, a launch's duration is its share) and a few times with the one-stream schedule, where every
+kernel has the GPU to itself: `roofline` describes the matrix-core kernel that takes the most time
+inside the step and `update_roofline` the fused gradient-sum + update kernel, from that pass.
 `grad_update` is the stand-alone update over the eight AlexNet buckets; `cpu_baseline` is the CPU
 oracle timed on a bounded sample of the same workload.
 """
@@ -460,43 +461,53 @@ def main():
                                                                args.kernel_table)}), flush=True)
         return
     extra = args.exclusive_steps if not args.serial else 0
-    st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps + extra)))
+    inst_steps = max(1, min(args.steps, 20))          # iterations of the instrumented pass of the timed schedule
+    st = build_net(cg, torch, B, K, seed=4, n_batches=max(1, min(64, args.warmup + args.steps + inst_steps + extra)))
     torch.cuda.synchronize()
     run_steps(cg, torch, st, sgd, args.warmup, flags)
     sync(torch, st)
 
-    # ---- the timed region: K whole iterations, every matrix-core and update launch bracketed by events
-    cg.cg_profile_enable(True)
+    # ---- the timed region: K whole iterations, nothing but the library's own launches on the streams
     launches0 = cg.cg_debug_launch_count()
     t0 = time.perf_counter()
     run_steps(cg, torch, st, sgd, args.steps, flags)
     sync(torch, st)
     wall = time.perf_counter() - t0
     launches_per_step = (cg.cg_debug_launch_count() - launches0) / args.steps
-    cg.cg_profile_enable(False)
-    agg = collect_profile(cg)
     clocks = gpu_clocks()
     loss = float(st["loss"].cpu()[0])
     ms_per_step = wall / args.steps * 1e3
-    roofline, update_roofline, totals = kernel_rooflines(agg, args.steps, traffic)
+    # ---- the same schedule again, every matrix-core and update launch bracketed by two events
+    cg.cg_profile_enable(True)
+    t0 = time.perf_counter()
+    run_steps(cg, torch, st, sgd, inst_steps, flags)
+    sync(torch, st)
+    inst_ms = (time.perf_counter() - t0) / inst_steps * 1e3
+    cg.cg_profile_enable(False)
+    agg = collect_profile(cg)
+    roofline, update_roofline, totals = kernel_rooflines(agg, inst_steps, traffic)
     roofline["measured"] = update_roofline["measured"] = (
-        "HIP events around every launch of the timed region" +
+        f"HIP events around every launch of {inst_steps} iterations run right after the timed region with its schedule" +
         ("" if args.serial else ", in which backward-data, backward-weight and the update run on three streams: "
          "a launch's duration is its share of a GPU it does not have to itself"))
     if args.kernel_table:
-        kernel_table(agg, args.steps)
+        kernel_table(agg, inst_steps)
         log(f"matrix-core kernels: {totals['ms_per_step']:.3f} ms/step of launch time, {totals['tflops']:.1f} TFLOP/s over it; "
-            f"wall {ms_per_step:.3f} ms/step; loss {loss:.4f}")
+            f"wall {ms_per_step:.3f} ms/step ({inst_ms:.3f} with launch events); loss {loss:.4f}")
 
     # ---- the same kernels alone on the GPU: a few iterations of the one-stream schedule
     roofline_excl = update_excl = totals_excl = None
     serial_ms = None
     if extra > 0:
-        cg.cg_profile_enable(True)
+        run_steps(cg, torch, st, sgd, 2, cg.CG_STEP_SERIAL)
+        sync(torch, st)
         t0 = time.perf_counter()
         run_steps(cg, torch, st, sgd, extra, cg.CG_STEP_SERIAL)
         sync(torch, st)
-        serial_ms = (time.perf_counter() - t0) / extra * 1e3
+        serial_ms = (time.perf_counter() - t0) / extra * 1e3          # plain, like the timed region
+        cg.cg_profile_enable(True)
+        run_steps(cg, torch, st, sgd, extra, cg.CG_STEP_SERIAL)
+        sync(torch, st)
         cg.cg_profile_enable(False)
         agg1 = collect_profile(cg)
         roofline_excl, update_excl, totals_excl = kernel_rooflines(agg1, extra, traffic)
@@ -509,13 +520,13 @@ def main():
             a = agg[roofline_excl["kernel"]]
             roofline = dict(roofline, kernel=roofline_excl["kernel"], achieved=a["flops"] / a["ms"] / 1e9,
                             frac=a["flops"] / a["ms"] / 1e9 / PEAK_FP32_MFMA_TFLOPS,
-                            avg_launch_ms=a["ms"] / a["launches"], launches_per_step=a["launches"] / args.steps,
+                            avg_launch_ms=a["ms"] / a["launches"], launches_per_step=a["launches"] / inst_steps,
                             flops_per_launch=a["flops"] / a["launches"], traffic=roofline_excl["traffic"])
         if args.kernel_table:
             log("-- one-stream pass --")
             kernel_table(agg1, extra)
             log(f"matrix-core kernels alone: {totals_excl['ms_per_step']:.3f} ms/step, {totals_excl['tflops']:.1f} TFLOP/s; "
-                f"wall {serial_ms:.3f} ms/step")
+                f"wall without events {serial_ms:.3f} ms/step")
 
     # free the net before the stand-alone update benchmark
     del st
@@ -585,14 +596,15 @@ def main():
         # the kernel's own speed: timed alone on the GPU (one-stream pass of the same iteration, same
         # process, HIP events around every launch); the shared-GPU durations of the timed region follow
         "roofline": roofline_excl if roofline_excl else roofline,
-        "roofline_in_timed_region": roofline,
+        "roofline_three_stream_pass" if not args.serial else "roofline_instrumented_pass": roofline,
         "update_roofline": update_excl if update_excl else update_roofline,
-        "update_roofline_in_timed_region": update_roofline,
+        "update_roofline_three_stream_pass" if not args.serial else "update_roofline_instrumented_pass": update_roofline,
         "whole_step_matrix_core": {"tflops": totals["flops_per_step"] / (ms_per_step * 1e-3) / 1e12,
                                    "frac": totals["flops_per_step"] / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
                                    "what": "algorithmic FLOP of all matrix-core launches of a step / wall time of the step "
                                            "(glue layers and updates included in the time)"},
         "matrix_core_kernels_exclusive": totals_excl,
+        "ms_per_step_with_launch_events": inst_ms,
         "serial_schedule_ms_per_step": serial_ms,
         "kernel_launches_per_step": launches_per_step,
         "gpu_clocks_after_timed_region": clocks,
