@@ -182,6 +182,7 @@ struct IgemmProblem {
     const float *gate;        // same layout as C, or NULL: result = 0 where gate <= 0 (backward-data into a
                               // rectifier: the gradient with respect to the rectifier's input), before accumulate
     int math;                 // CG_MATH_FP32, CG_MATH_BF16 or CG_MATH_BF16X3: what the matrix instructions multiply in
+    int beside_other_stream;  // the caller runs matrix kernels on another stream meanwhile (tile choice of the patch kernel)
     int use_patch;            // B is described by `patch` (and A is the matching tap-major matrix); B unused
     PatchGeom patch;
     int use_wgrad;            // backward-weight from image bands (`wgrad`): A = dy rows, B unused, K counted in pixels
@@ -239,7 +240,8 @@ int conv_fwd_impl(const cg_conv_desc &d, const float *x, const float *w, const f
                   size_t ws_bytes, int relu, hipStream_t stream, int64_t y_img_stride = 0, int math = 0,
                   const float *prepared = nullptr);
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
-                       size_t ws_bytes, int accumulate, hipStream_t stream, int math = 0, const float *prepared = nullptr);
+                       size_t ws_bytes, int accumulate, hipStream_t stream, int math = 0, const float *prepared = nullptr,
+                       bool beside_other_stream = false);
 // Which rearranged copy of its filters a pass needs (kind CG_PREP_NONE: it reads w itself), and how
 // many floats the copy has.  The answer follows the same kernel choice the pass itself makes.
 enum { CG_PREP_NONE = 0, CG_PREP_TRANSPOSE, CG_PREP_PERMUTE_FWD, CG_PREP_PERMUTE_BWD, CG_PREP_STRIDED_TAPS, CG_PREP_STRIDED_ROWS };

@@ -588,7 +588,8 @@ static int strided_filters(const float *w, float *dst, const cg_conv_desc &d, co
 }
 
 int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, float *dx, const float *gate, void *ws,
-                       size_t ws_bytes, int accumulate, hipStream_t stream, int math, const float *prepared)
+                       size_t ws_bytes, int accumulate, hipStream_t stream, int math, const float *prepared,
+                       bool beside_other_stream)
 {
     if (!math_ok(math)) return CG_EINVAL;
     ProfTag tag("conv_bwd_data", -1);
@@ -660,6 +661,7 @@ int conv_bwd_data_impl(const cg_conv_desc &d, const float *dy, const float *w, f
         IgemmProblem pp = bwd_data_problem(d, OH, OW, dy, wuse, dx, accumulate);
         pp.gate = gate;
         pp.math = math;
+        pp.beside_other_stream = beside_other_stream ? 1 : 0;
         if (bwd_data_patch(d, OH, OW, dy, pp)) {
             if (!prepared) {
                 const int rc2 = permute_filters(w, wt, G, Mg, Cg, KK, 1, stream);
