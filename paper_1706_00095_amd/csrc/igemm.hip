@@ -1487,10 +1487,10 @@ int patch_launch(const IgemmProblem &p, hipStream_t stream)
     // Backward-data (mirrored taps) in the same situation takes 64-row tiles for the whole launch: three
     // of those blocks fit a compute unit, and twice or three times as many, shorter blocks quantise
     // better (676 blocks of 192 rows = 1.32 rounds of 512; 2028 of 64 rows = 2.64 rounds of 768).
-    // Alone on the GPU: conv4-shaped 0.516 -> 0.461 ms, conv5-shaped 0.352 -> 0.315 ms at B = 256, the
-    // one-stream step 11.17 -> 10.82 ms; beside backward-weight on another stream, whose blocks fill the
-    // short round anyway, the step was 0.07 ms slower with it, so a caller that knows of such a stream
-    // says so (beside_other_stream) and keeps the large tiles.
+    // Alone on the GPU: conv4-shaped 0.516 -> 0.461 ms, conv5-shaped 0.352 -> 0.315 ms at B = 256 (a
+    // one-stream step 11.17 -> 10.82 ms); beside backward-weight on another stream, whose blocks fill the
+    // short round anyway, the step was 0.07 ms slower with it, so a caller that runs such a stream says
+    // so (beside_other_stream) and keeps the large tiles.
     if (mt > 64 && p.patch.tile_count == 0 && p.patch.flip && p.patch.nsl == 4 && !p.beside_other_stream) {
         const uint32_t rb = resident_blocks();
         const uint64_t blocks = (uint64_t)patch_pixel_tiles(p) * ((p.M + mt - 1) / mt) * p.groups;

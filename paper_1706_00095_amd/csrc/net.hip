@@ -600,8 +600,10 @@ extern "C" int cg_train_step(cg_net *net, const float *x, const int32_t *labels,
                 rc = fc_bwd_weight_impl(B, IN, d.fc_out, in, dy, ly.g, ly.g + ly.n_weights, scratch2, scratch_bytes, S2, math);
             if (rc == CG_OK && want_dx) {
                 if (d.kind == CG_LAYER_CONV)
+                    // (true: the tile choice made for the three-stream schedule, in the one-stream schedule as well,
+                    // which thereby issues exactly the same launches, one at a time)
                     rc = conv_bwd_data_impl(ly.conv, dy, ly.w, dx, gate, scratch, scratch_bytes, accum, S0, math, ly.prep_bd,
-                                            !serial);
+                                            true);
                 else
                     rc = fc_bwd_data_impl(B, IN, d.fc_out, dy, ly.w, dx, gate, accum, scratch, scratch_bytes, S0, math);
             }
